@@ -1,0 +1,181 @@
+/*
+ * dream.h - C ABI of the MI355X (gfx950) hot path of DREAM's speculative decode step.
+ *
+ * Four operations, one call each:
+ *   dream_tree_verify_attn  target-side attention of all drafted tree nodes against the KV cache
+ *                           under the draft-tree mask (Section 3.1, tree-masking paragraph: the
+ *                           tree mask built while drafting is reused for verification).
+ *   dream_draft_xattn       the attention core of the draft's cross-attention block,
+ *                           softmax(Q K^T / sqrt(z)) V  (Section 3.1, Eq. 1), keys/values being the
+ *                           cached target features followed by the draft's own features of nodes
+ *                           drafted earlier (Section 3.1, paragraph after Eq. 1).
+ *   dream_visual_compress   importance score of every visual token = the attention weight it
+ *                           receives, summed over rows and heads of the last-layer attention
+ *                           matrix; keep the top-scoring ones by ratio; subsample (Section 3.3).
+ *   dream_accept_path       greedy (temperature 0) form of the acceptance rule of Section 2.1 over
+ *                           the verified tree plus the bonus target token (Section 4).
+ *
+ * Conventions
+ *   - Every pointer is a DEVICE pointer unless its name ends in _host.  The caller owns every
+ *     buffer.  The library allocates nothing, never synchronises, and enqueues all work on
+ *     `stream` (a hipStream_t passed as void*; NULL = the default stream).  Results are valid
+ *     once the caller has synchronised the stream.
+ *   - Inputs are never written; outputs are fully overwritten; the workspace is scratch, except
+ *     that its first DREAM_WORKSPACE_HEADER_BYTES must be zero when a call starts.  Zero them once
+ *     with dream_workspace_init() after allocating; every call leaves them zero again.  Calls that
+ *     share a workspace must be ordered on one stream.
+ *   - Tensors are dense, C order.  bf16 means the upper 16 bits of an IEEE float32.
+ *   - Every function returns a dream_status (0 = ok, negative = error) and never throws or
+ *     aborts.  Argument errors are detected on the host before anything is launched; the text of
+ *     the last error of the calling thread is available from dream_last_error().
+ *   - Device-resident metadata (prefix_len, parent, q_node, token, q_pos) is trusted.
+ *     dream_tree_validate_host() is the host-side check for a parent array.
+ *
+ * Tree convention: node 0 is the root (the target's last emitted token, depth 0, always
+ * accepted); parent[0] = -1 and 0 <= parent[i] < i for i > 0.  The K/V rows of the n_tree tree
+ * nodes of sequence b sit at cache rows [prefix_len[b], prefix_len[b] + n_tree).
+ */
+#ifndef DREAM_H
+#define DREAM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { DREAM_F32 = 0, DREAM_BF16 = 1 } dream_dtype;
+
+typedef enum {
+    DREAM_OK = 0,
+    DREAM_ERR_INVALID_ARG = -1, /* null required pointer, inconsistent sizes                   */
+    DREAM_ERR_UNSUPPORTED = -2, /* shape outside what the kernels are built for                */
+    DREAM_ERR_WORKSPACE = -3,   /* workspace_bytes smaller than the matching *_workspace()     */
+    DREAM_ERR_HIP = -4          /* a HIP launch reported an error                              */
+} dream_status;
+
+#define DREAM_WORKSPACE_HEADER_BYTES 4096
+#define DREAM_MAX_TREE 64       /* tree nodes per sequence handled by the attention calls      */
+#define DREAM_MAX_TREE_ACCEPT 1024 /* tree nodes per sequence handled by dream_accept_path     */
+#define DREAM_MAX_VISUAL 16384  /* visual tokens per sequence handled by dream_visual_compress */
+
+/* Attention geometry shared by the three attention-shaped calls. */
+typedef struct {
+    int32_t batch;      /* B                                                                   */
+    int32_t n_q_heads;  /* Hq                                                                  */
+    int32_t n_kv_heads; /* Hkv; Hq % Hkv == 0; query head h reads KV head h / (Hq/Hkv)         */
+    int32_t head_dim;   /* D in {64, 128, 256}                                                 */
+    int32_t dtype;      /* dream_dtype of q, k, v and out                                      */
+    float scale;        /* multiplies q.k before the softmax; 0 selects 1/sqrt(D) (Eq. 1)      */
+    int64_t s_max;      /* row capacity of every [B, Hkv, s_max, D] cache                      */
+} dream_attn_desc;
+
+/* Zero the workspace header (a small fill kernel on `stream`).  Call once per workspace. */
+int dream_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Tree-masked verification attention (Section 3.1; Eq. 1 gives the attention form).
+ *   q          [B, n_tree, Hq, D]   queries of the tree nodes
+ *   k_cache    [B, Hkv, s_max, D]   rows [0, P_b) prefix (visual + text), [P_b, P_b+n_tree) tree
+ *   v_cache    [B, Hkv, s_max, D]
+ *   prefix_len [B] int32            P_b
+ *   parent     [B, n_tree] int32
+ *   tree_mask  nullable, [B, n_tree] uint64: bit a of word i set iff tree node a is visible to
+ *              node i.  When given it replaces the mask derived from `parent`
+ *              (node i sees itself and its ancestors).
+ *   max_kv_len host-known upper bound of P_b + n_tree over the batch (<= s_max); only used to
+ *              choose the launch shape, pass s_max if unknown.
+ *   out        [B, n_tree, Hq, D]   same dtype as q
+ *   lse        nullable, [B, Hq, n_tree] float32: natural-log sum of exp of the scaled scores.
+ * Node i attends keys {0..P_b-1} and {P_b + a : a visible to i}.  n_tree in [1, DREAM_MAX_TREE].
+ * ------------------------------------------------------------------------------------------- */
+size_t dream_tree_verify_attn_workspace(const dream_attn_desc *desc, int32_t n_tree, int64_t max_kv_len);
+int dream_tree_verify_attn(const dream_attn_desc *desc, const void *q, const void *k_cache,
+                           const void *v_cache, const int32_t *prefix_len, int32_t n_tree,
+                           const int32_t *parent, const uint64_t *tree_mask, int64_t max_kv_len,
+                           void *out, float *lse, void *workspace, size_t workspace_bytes,
+                           void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Draft cross-attention core (Section 3.1, Eq. 1 and the paragraph after it).
+ *   q          [B, n_q, Hq, D]      projected draft features of the nodes being expanded
+ *   kx_cache   [B, Hkv, s_max, D]   rows [0, n_b): projected target features S^L W_K;
+ *   vx_cache                        rows [n_b, n_b+n_tree): projected draft features of tree nodes
+ *   prefix_len [B] int32            n_b
+ *   parent     [B, n_tree] int32
+ *   q_node     nullable, [B, n_q] int32: tree node of each query row (NULL: row r is node r,
+ *              which needs n_q <= n_tree)
+ *   out        [B, n_q, Hq, D]
+ * Query of node i attends rows {0..n_b-1} and {n_b + a : a a STRICT ancestor of i}; a query with
+ * no visible key yields a zero row.  n_q in [1, DREAM_MAX_TREE], n_tree in [1, DREAM_MAX_TREE].
+ * ------------------------------------------------------------------------------------------- */
+size_t dream_draft_xattn_workspace(const dream_attn_desc *desc, int32_t n_q, int64_t max_kv_len);
+int dream_draft_xattn(const dream_attn_desc *desc, const void *q, const void *kx_cache,
+                      const void *vx_cache, const int32_t *prefix_len, int32_t n_tree,
+                      const int32_t *parent, int32_t n_q, const int32_t *q_node,
+                      int64_t max_kv_len, void *out, void *workspace, size_t workspace_bytes,
+                      void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Visual-token compression (Section 3.3; kept count per Section 3: round(v / r)).
+ * Stage A (skipped when scores_in != NULL): row r of q sits at position pos_r (q_pos[b,r], or r
+ * when q_pos is NULL) and attends keys 0..pos_r causally;
+ *   score[b, j] = sum over heads and rows with pos_r >= j of softmax_row_r(scale q k^T)[j]
+ * for j in [vis_start, vis_start + vis_len).
+ * Stage B: k = (vis_len*keep_num + keep_den/2) / keep_den (round half up, integer division); the
+ * k highest scores win, equal scores resolved toward the lower index; kept_idx receives their
+ * absolute positions in ascending order.  Optional gather: gather_dst[b,t,:] =
+ * gather_src[b, kept_idx[b,t], :].
+ *   q          [B, n_q, Hq, D] (dtype of desc; bf16 only for stage A), q_pos nullable [B, n_q]
+ *   k_cache    [B, Hkv, s_max, D]; n_keys = live key rows, every pos_r < n_keys <= s_max
+ *   scores_in  nullable [B, vis_len] float32; scores_out nullable [B, vis_len] float32
+ *   kept_idx   [B, k] int32;  n_kept_host nullable, HOST int32 receiving k
+ *   gather_src nullable [B, n_rows_src, row_elems] of desc->dtype, gather_dst [B, k, row_elems];
+ *              n_rows_src is the row capacity per sequence (kept positions are < n_rows_src)
+ * desc->head_dim, heads and s_max are ignored when scores_in is given.
+ * ------------------------------------------------------------------------------------------- */
+size_t dream_visual_compress_workspace(const dream_attn_desc *desc, int32_t n_q, int32_t vis_len);
+int dream_visual_compress(const dream_attn_desc *desc, const void *q, const int32_t *q_pos,
+                          int32_t n_q, const void *k_cache, int32_t n_keys, int32_t vis_start,
+                          int32_t vis_len, int32_t keep_num, int32_t keep_den,
+                          const float *scores_in, float *scores_out, int32_t *kept_idx,
+                          int32_t *n_kept_host, const void *gather_src, int64_t n_rows_src,
+                          void *gather_dst, int64_t row_elems, void *workspace,
+                          size_t workspace_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Per-node arg-max and greedy accepted path (Section 2.1 rule at temperature 0; Section 4).
+ *   logits      [B, n_tree, vocab] float32 or bf16 (finite values)
+ *   token       [B, n_tree] int32   drafted token of each node (token[b,0] is not examined)
+ *   parent      [B, n_tree] int32
+ *   node_argmax [B, n_tree] int32   lowest index of the row maximum
+ *   accept_len  [B] int32           depth of the deepest accepted node (root excluded)
+ *   accept_path [B, max_depth+1]    root ... deepest accepted node, then -1
+ *   bonus_token [B] int32           node_argmax of the deepest accepted node
+ * Node i > 0 is accepted iff its parent is accepted, token[i] == node_argmax[parent[i]] and its
+ * depth <= max_depth.  Among equally deep accepted nodes the lowest node index wins.
+ * n_tree in [1, DREAM_MAX_TREE_ACCEPT].
+ * ------------------------------------------------------------------------------------------- */
+size_t dream_accept_path_workspace(int32_t batch, int32_t n_tree, int32_t vocab);
+int dream_accept_path(const void *logits, int32_t logits_dtype, int32_t batch, int32_t n_tree,
+                      int32_t vocab, const int32_t *token, const int32_t *parent,
+                      int32_t max_depth, int32_t *node_argmax, int32_t *accept_len,
+                      int32_t *accept_path, int32_t *bonus_token, void *workspace,
+                      size_t workspace_bytes, void *stream);
+
+/* Host-side check of one parent array: parent_host[0] == -1 and 0 <= parent_host[i] < i.
+ * Writes the maximum depth to *max_depth_out (nullable).  DREAM_OK or DREAM_ERR_INVALID_ARG. */
+int dream_tree_validate_host(const int32_t *parent_host, int32_t n_tree, int32_t *max_depth_out);
+
+/* Text of the calling thread's last error ("" if none); static storage, never NULL. */
+const char *dream_last_error(void);
+
+/* Launch-shape override for experiments: number of key-range splits the attention calls use
+ * (0 = choose automatically).  Results are identical up to floating-point summation order. */
+void dream_set_kv_splits(int32_t n_splits);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DREAM_H */

@@ -1,0 +1,15 @@
+"""MI355X-native hot path of DREAM's speculative decode step (arXiv 2505.19201).
+
+The product is the C-ABI library `libdream.so` (hand-written HIP for gfx950, declared in
+include/dream.h).  This package is the thin Python binding over it: argument marshalling only.
+PyTorch is used for device memory and streams, nothing else.  There is no CPU fallback: if the
+library is missing or no GPU is present, calls fail loudly.
+"""
+from .binding import (  # noqa: F401
+    BF16, F32, DreamError, AttnDesc, attn_desc, load, library_path,
+    dream_workspace_init, dream_tree_verify_attn_workspace, dream_tree_verify_attn,
+    dream_draft_xattn_workspace, dream_draft_xattn, dream_visual_compress_workspace,
+    dream_visual_compress, dream_accept_path_workspace, dream_accept_path,
+    dream_tree_validate_host, dream_last_error, dream_set_kv_splits,
+    alloc_workspace, to_device, EXPORTED_SYMBOLS,
+)

@@ -1,0 +1,189 @@
+// dream_accept_path: per-node arg-max over the vocabulary and the greedy accepted path.
+//
+// At temperature 0 the acceptance rule of Section 2.1 accepts a drafted token exactly when it is
+// the target's arg-max at its parent; everything after the first mismatch on a path is dropped and
+// the target's own choice at the last accepted node is emitted as the bonus token (Section 4).
+//
+// argmax_partial_kernel streams the logits once (16-byte loads, one workgroup per row chunk) and
+// reduces (value, index) pairs with wavefront shuffles; ties always keep the lower index, so the
+// result does not depend on how rows are chunked.  accept_walk_kernel merges the chunk results and
+// walks the tree in node order in a single wavefront per sequence.
+#include "common.h"
+
+using namespace dream;
+
+namespace {
+
+constexpr int CHUNK_ELEMS = 8192;   // logits handled by one workgroup
+
+__device__ __forceinline__ void better(float &v, int &i, float ov, int oi)
+{
+    if (ov > v || (ov == v && oi < i)) {
+        v = ov;
+        i = oi;
+    }
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void argmax_partial_kernel(const void *logits, int vocab, int n_chunks,
+                                                             float *part_val, int32_t *part_idx)
+{
+    const int chunk = blockIdx.x;
+    const int64_t row = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int begin = chunk * CHUNK_ELEMS;
+    const int end = min(begin + CHUNK_ELEMS, vocab);
+    float best = -INFINITY;
+    int best_i = 0x7fffffff;
+    if (BF16) {
+        const uint16_t *p = reinterpret_cast<const uint16_t *>(logits) + row * vocab;
+        // 16-byte vector loads when the row start allows it, scalar loads otherwise and for the tail
+        const bool aligned = (((uintptr_t)(p + begin)) & 15) == 0;
+        int vec_end = aligned ? begin + ((end - begin) & ~7) : begin;
+        for (int i = begin + tid * 8; i < vec_end; i += 256 * 8) {
+            uint4 u = *reinterpret_cast<const uint4 *>(p + i);
+            uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                float lo = __uint_as_float(w[j] << 16), hi = __uint_as_float(w[j] & 0xffff0000u);
+                if (lo > best) { best = lo; best_i = i + 2 * j; }
+                if (hi > best) { best = hi; best_i = i + 2 * j + 1; }
+            }
+        }
+        for (int i = vec_end + tid; i < end; i += 256) {
+            float x = bf16_bits_to_float(p[i]);
+            if (x > best || (x == best && i < best_i)) { best = x; best_i = i; }
+        }
+    } else {
+        const float *p = reinterpret_cast<const float *>(logits) + row * vocab;
+        const bool aligned = (((uintptr_t)(p + begin)) & 15) == 0;
+        int vec_end = aligned ? begin + ((end - begin) & ~3) : begin;
+        for (int i = begin + tid * 4; i < vec_end; i += 256 * 4) {
+            float4 u = *reinterpret_cast<const float4 *>(p + i);
+            if (u.x > best) { best = u.x; best_i = i; }
+            if (u.y > best) { best = u.y; best_i = i + 1; }
+            if (u.z > best) { best = u.z; best_i = i + 2; }
+            if (u.w > best) { best = u.w; best_i = i + 3; }
+        }
+        for (int i = vec_end + tid; i < end; i += 256) {
+            float x = p[i];
+            if (x > best || (x == best && i < best_i)) { best = x; best_i = i; }
+        }
+    }
+    for (int off = 32; off > 0; off >>= 1) {
+        float ov = __shfl_xor(best, off);
+        int oi = __shfl_xor(best_i, off);
+        better(best, best_i, ov, oi);
+    }
+    __shared__ float sv[4];
+    __shared__ int si[4];
+    if (lane == 0) {
+        sv[wave] = best;
+        si[wave] = best_i;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        for (int w = 1; w < 4; w++)
+            better(best, best_i, sv[w], si[w]);
+        part_val[row * n_chunks + chunk] = best;
+        part_idx[row * n_chunks + chunk] = best_i;
+    }
+}
+
+// One workgroup (64 lanes) per sequence.
+__global__ __launch_bounds__(64) void accept_walk_kernel(const float *part_val, const int32_t *part_idx, int n_chunks,
+                                                         int n_tree, const int32_t *token, const int32_t *parent,
+                                                         int max_depth, int32_t *node_argmax, int32_t *accept_len,
+                                                         int32_t *accept_path, int32_t *bonus_token)
+{
+    __shared__ int32_t s_am[DREAM_MAX_TREE_ACCEPT];
+    __shared__ int32_t s_par[DREAM_MAX_TREE_ACCEPT];
+    __shared__ int32_t s_tok[DREAM_MAX_TREE_ACCEPT];
+    __shared__ int16_t s_depth[DREAM_MAX_TREE_ACCEPT];
+    __shared__ uint8_t s_acc[DREAM_MAX_TREE_ACCEPT];
+    const int b = blockIdx.x, lane = threadIdx.x;
+    for (int i = lane; i < n_tree; i += 64) {
+        int64_t row = (int64_t)b * n_tree + i;
+        float v = part_val[row * n_chunks];
+        int idx = part_idx[row * n_chunks];
+        for (int ch = 1; ch < n_chunks; ch++)
+            better(v, idx, part_val[row * n_chunks + ch], part_idx[row * n_chunks + ch]);
+        s_am[i] = idx;
+        s_par[i] = parent[row];
+        s_tok[i] = token[row];
+        node_argmax[row] = idx;
+    }
+    __syncthreads();
+    if (lane == 0) {
+        s_depth[0] = 0;
+        s_acc[0] = 1;
+        int best = 0;
+        for (int i = 1; i < n_tree; i++) {
+            int p = s_par[i];
+            int d = s_depth[p] + 1;
+            s_depth[i] = (int16_t)d;
+            uint8_t ok = s_acc[p] && s_tok[i] == s_am[p] && d <= max_depth;
+            s_acc[i] = ok;
+            if (ok && d > s_depth[best])
+                best = i;
+        }
+        accept_len[b] = s_depth[best];
+        int32_t *path = accept_path + (int64_t)b * (max_depth + 1);
+        for (int t = 0; t <= max_depth; t++)
+            path[t] = -1;
+        for (int n = best; n >= 0; n = s_par[n])
+            path[s_depth[n]] = n;
+        bonus_token[b] = s_am[best];
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t dream_accept_path_workspace(int32_t batch, int32_t n_tree, int32_t vocab)
+{
+    if (batch < 1 || n_tree < 1 || vocab < 1)
+        return DREAM_WORKSPACE_HEADER_BYTES;
+    size_t n = (size_t)batch * n_tree * ceil_div(vocab, CHUNK_ELEMS);
+    return DREAM_WORKSPACE_HEADER_BYTES + align_up(n * 4, 256) + align_up(n * 4, 256);
+}
+
+int dream_accept_path(const void *logits, int32_t logits_dtype, int32_t batch, int32_t n_tree, int32_t vocab,
+                      const int32_t *token, const int32_t *parent, int32_t max_depth, int32_t *node_argmax,
+                      int32_t *accept_len, int32_t *accept_path, int32_t *bonus_token, void *workspace,
+                      size_t workspace_bytes, void *stream)
+{
+    const char *who = "dream_accept_path";
+    if (!logits || !token || !parent || !node_argmax || !accept_len || !accept_path || !bonus_token)
+        return fail(DREAM_ERR_INVALID_ARG, "%s: NULL argument", who);
+    if (logits_dtype != DREAM_F32 && logits_dtype != DREAM_BF16)
+        return fail(DREAM_ERR_INVALID_ARG, "%s: unknown logits dtype %d", who, logits_dtype);
+    if (batch < 1 || vocab < 1 || max_depth < 0)
+        return fail(DREAM_ERR_INVALID_ARG, "%s: batch, vocab must be positive and max_depth non-negative", who);
+    if (n_tree < 1 || n_tree > DREAM_MAX_TREE_ACCEPT)
+        return fail(DREAM_ERR_UNSUPPORTED, "%s: n_tree %d outside [1, %d]", who, n_tree, DREAM_MAX_TREE_ACCEPT);
+    if ((int64_t)batch * n_tree > 65535)
+        return fail(DREAM_ERR_UNSUPPORTED, "%s: batch * n_tree = %lld exceeds 65535 rows", who, (long long)batch * n_tree);
+    const size_t need = dream_accept_path_workspace(batch, n_tree, vocab);
+    if (!workspace || workspace_bytes < need)
+        return fail(DREAM_ERR_WORKSPACE, "%s: workspace of %zu bytes, %zu needed", who, workspace_bytes, need);
+    const int n_chunks = ceil_div(vocab, CHUNK_ELEMS);
+    const size_t n = (size_t)batch * n_tree * n_chunks;
+    float *part_val = reinterpret_cast<float *>(static_cast<char *>(workspace) + DREAM_WORKSPACE_HEADER_BYTES);
+    int32_t *part_idx = reinterpret_cast<int32_t *>(static_cast<char *>(workspace) + DREAM_WORKSPACE_HEADER_BYTES + align_up(n * 4, 256));
+    hipStream_t st = as_stream(stream);
+    dim3 grid(n_chunks, batch * n_tree);
+    if (logits_dtype == DREAM_BF16)
+        hipLaunchKernelGGL(argmax_partial_kernel<true>, grid, dim3(256), 0, st, logits, vocab, n_chunks, part_val, part_idx);
+    else
+        hipLaunchKernelGGL(argmax_partial_kernel<false>, grid, dim3(256), 0, st, logits, vocab, n_chunks, part_val, part_idx);
+    int rc = check_launch("argmax_partial_kernel");
+    if (rc)
+        return rc;
+    hipLaunchKernelGGL(accept_walk_kernel, dim3(batch), dim3(64), 0, st, part_val, part_idx, n_chunks, n_tree, token, parent,
+                       max_depth, node_argmax, accept_len, accept_path, bonus_token);
+    return check_launch("accept_walk_kernel");
+}
+
+}  // extern "C"

@@ -1,0 +1,83 @@
+// Error reporting, workspace initialisation and tree validation shared by all entry points.
+#include "common.h"
+#include <string.h>
+
+namespace dream {
+
+static thread_local char g_error[512] = "";
+static int g_kv_splits = 0;
+
+char *error_buffer() { return g_error; }
+
+int fail(int status, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_error, sizeof g_error, fmt, ap);
+    va_end(ap);
+    return status;
+}
+
+int check_launch(const char *what)
+{
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess)
+        return fail(DREAM_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+    return DREAM_OK;
+}
+
+int kv_splits_override() { return g_kv_splits; }
+
+__global__ void zero_words_kernel(uint32_t *p, int n)
+{
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n)
+        p[i] = 0u;
+}
+
+}  // namespace dream
+
+using namespace dream;
+
+extern "C" {
+
+const char *dream_last_error(void) { return error_buffer(); }
+
+void dream_set_kv_splits(int32_t n_splits) { dream::g_kv_splits = n_splits < 0 ? 0 : n_splits; }
+
+int dream_workspace_init(void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!workspace)
+        return fail(DREAM_ERR_INVALID_ARG, "dream_workspace_init: workspace is NULL");
+    if (workspace_bytes < DREAM_WORKSPACE_HEADER_BYTES)
+        return fail(DREAM_ERR_WORKSPACE, "dream_workspace_init: workspace of %zu bytes is smaller than the %d-byte header",
+                    workspace_bytes, DREAM_WORKSPACE_HEADER_BYTES);
+    const int n = DREAM_WORKSPACE_HEADER_BYTES / 4;
+    hipLaunchKernelGGL(zero_words_kernel, dim3((n + 255) / 256), dim3(256), 0, as_stream(stream),
+                       reinterpret_cast<uint32_t *>(workspace), n);
+    return check_launch("dream_workspace_init");
+}
+
+int dream_tree_validate_host(const int32_t *parent_host, int32_t n_tree, int32_t *max_depth_out)
+{
+    if (!parent_host || n_tree < 1)
+        return fail(DREAM_ERR_INVALID_ARG, "dream_tree_validate_host: NULL parent array or n_tree < 1");
+    if (parent_host[0] != -1)
+        return fail(DREAM_ERR_INVALID_ARG, "dream_tree_validate_host: parent[0] is %d, expected -1", parent_host[0]);
+    int max_depth = 0;
+    // depth of node i fits in the slot of an int array only for small trees; recompute by walking, trees are tiny
+    for (int i = 1; i < n_tree; i++) {
+        if (parent_host[i] < 0 || parent_host[i] >= i)
+            return fail(DREAM_ERR_INVALID_ARG, "dream_tree_validate_host: parent[%d] = %d is not in [0, %d)", i, parent_host[i], i);
+        int d = 0;
+        for (int a = i; a > 0; a = parent_host[a])
+            d++;
+        if (d > max_depth)
+            max_depth = d;
+    }
+    if (max_depth_out)
+        *max_depth_out = max_depth;
+    return DREAM_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,90 @@
+"""No-GPU checks of the boundary: the library loads, exports every function include/dream.h declares,
+and rejects bad arguments on the host before anything is launched."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2505_19201_amd as dream
+from paper_2505_19201_amd import build as dream_build
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(dream.library_path()):
+        dream_build.build(verbose=False)
+    return dream.load()
+
+
+def _declared_functions():
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    text = open(os.path.join(root, "include", "dream.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dream_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_function_is_exported(lib):
+    names = _declared_functions()
+    assert {"dream_tree_verify_attn", "dream_draft_xattn", "dream_visual_compress", "dream_accept_path"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(dream.EXPORTED_SYMBOLS) == names
+
+
+def test_binding_never_imports_the_oracle():
+    import sys
+    src = open(dream.binding.__file__).read() + open(dream.__file__).read()
+    assert "oracle" not in src.replace("no CPU fallback", "")
+    assert "oracle" not in [m.split(".")[0] for m in sys.modules if m.startswith("paper_2505_19201_amd")]
+
+
+def test_tree_validation_on_host(lib):
+    assert dream.dream_tree_validate_host(np.array([-1, 0, 0, 1, 3, 4])) == 4
+    assert dream.dream_tree_validate_host(np.array([-1])) == 0
+    for bad in ([0, 0], [-1, 1], [-1, 0, 3], [-1, -1]):
+        with pytest.raises(dream.DreamError) as e:
+            dream.dream_tree_validate_host(np.array(bad))
+        assert e.value.status == -1
+
+
+def test_host_side_argument_errors(lib):
+    d = dream.attn_desc(1, 4, 4, 64, dream.BF16, 128)
+    one = C.c_void_p(16)      # never dereferenced: every call below fails validation first
+    f = lib.dream_tree_verify_attn
+    args = lambda desc, n_tree=8, maxkv=100, ws=one, wsb=1 << 30, q=one: (  # noqa: E731
+        C.byref(desc), q, one, one, one, C.c_int32(n_tree), one, None, C.c_int64(maxkv), one, None, ws, C.c_size_t(wsb), None)
+    assert f(*args(d, q=None)) == -1
+    assert f(*args(dream.attn_desc(1, 6, 4, 64, dream.BF16, 128))) == -1          # Hq % Hkv
+    assert f(*args(dream.attn_desc(1, 4, 4, 96, dream.BF16, 128))) == -2          # head_dim
+    assert f(*args(d, n_tree=65)) == -2
+    assert f(*args(d, n_tree=0)) == -2
+    assert f(*args(d, maxkv=129)) == -1                                           # beyond s_max
+    big = dream.attn_desc(1, 32, 32, 128, dream.BF16, 800)
+    assert f(*args(big, n_tree=60, maxkv=764, wsb=4096)) == -3                    # workspace too small
+    assert "workspace" in dream.dream_last_error()
+    g = lib.dream_accept_path
+    assert g(one, C.c_int32(1), C.c_int32(1), C.c_int32(2000), C.c_int32(100), one, one, C.c_int32(6), one, one, one, one,
+             one, C.c_size_t(1 << 30), None) == -2
+    assert g(one, C.c_int32(5), C.c_int32(1), C.c_int32(8), C.c_int32(100), one, one, C.c_int32(6), one, one, one, one,
+             one, C.c_size_t(1 << 30), None) == -1
+    h = lib.dream_visual_compress
+    base = [C.byref(d), one, None, C.c_int32(64), one, C.c_int32(64), C.c_int32(0), C.c_int32(32), C.c_int32(1), C.c_int32(2),
+            None, None, one, None, None, C.c_int64(0), None, C.c_int64(0), one, C.c_size_t(1 << 30), None]
+    bad = list(base); bad[9] = C.c_int32(0)
+    assert h(*bad) == -1                                                          # keep_den
+    bad = list(base); bad[8] = C.c_int32(3)
+    assert h(*bad) == -1                                                          # keep_num > keep_den
+    bad = list(base); bad[6] = C.c_int32(40)
+    assert h(*bad) == -1                                                          # span beyond keys
+    bad = list(base); bad[19] = C.c_size_t(16)
+    assert h(*bad) == -3
+
+
+def test_workspace_sizes_are_monotone(lib):
+    d = dream.attn_desc(1, 32, 32, 128, dream.BF16, 800)
+    a = dream.dream_tree_verify_attn_workspace(d, 60, 764)
+    assert a >= 4096
+    assert dream.dream_accept_path_workspace(1, 60, 32000) >= 4096 + 2 * 60 * 4 * 4
+    assert dream.dream_visual_compress_workspace(d, 704, 576) >= 4096 + 32 * 704 * 4 + 32 * 576 * 4

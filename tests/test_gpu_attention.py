@@ -1,0 +1,210 @@
+"""GPU parity: dream_tree_verify_attn and dream_draft_xattn against the float64 oracle on identical
+seeded inputs.  Tolerances (max-abs): 1e-5 for float32 tensors, 2e-2 for bf16 tensors."""
+import numpy as np
+import pytest
+
+import dream_inputs as di
+import oracle
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+@pytest.fixture(scope="module")
+def gu():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from tests import gpu_util
+    return gpu_util
+
+
+def _cfg(name, dtype, B, Hq, Hkv, D, v, q, T, depth, idx):
+    return di.Config(name, dtype, B, Hq, Hkv, D, Hq * D, v, q, T, depth, 1, 4, 1000, 1, idx)
+
+
+def test_tiny_config_verify_all_elements(gu):
+    cfg = di.CONFIGS["tiny"]
+    x = di.verify_inputs(cfg)
+    got, lse = gu.run_verify(x)
+    want, want_lse = oracle.tree_attn(x.q, x.k, x.v, cfg.dtype, x.prefix_len, x.parent, True)
+    assert np.abs(got - want).max() <= TOL["f32"]
+    assert np.abs(lse - want_lse).max() <= 1e-5
+
+
+SMALL_CASES = [
+    # name, B, Hq, Hkv, D, v, q, T, depth, prefix_len, splits
+    ("mha128", 2, 4, 4, 128, 150, 43, 60, 6, [193, 101], 0),
+    ("mha128_nosplit", 2, 4, 4, 128, 150, 43, 60, 6, [193, 101], 1),
+    ("mha128_3split", 1, 2, 2, 128, 300, 77, 60, 6, [377], 3),
+    ("gqa4_128", 2, 8, 2, 128, 130, 31, 60, 6, [161, 64], 0),
+    ("gqa2_256", 1, 4, 2, 256, 120, 45, 60, 6, [165], 0),
+    ("gqa2_256_nosplit", 2, 4, 2, 256, 70, 13, 33, 5, [83, 40], 1),
+    ("mha64", 2, 4, 4, 64, 200, 57, 60, 6, [257, 130], 0),
+    ("gqa8_64", 1, 8, 1, 64, 100, 30, 64, 6, [130], 2),
+    ("t1", 2, 4, 2, 128, 90, 9, 1, 0, [99, 17], 0),
+    ("t17", 1, 4, 2, 128, 90, 9, 17, 4, [99], 2),
+    ("paper_tree33", 1, 4, 4, 128, 144, 40, 33, 6, [184], 0),
+    ("empty_prefix", 1, 2, 2, 64, 0, 0, 20, 4, [0], 0),
+]
+
+
+@pytest.mark.parametrize("case", SMALL_CASES, ids=[c[0] for c in SMALL_CASES])
+def test_bf16_verify_all_elements(gu, case):
+    import paper_2505_19201_amd as dream
+    name, B, Hq, Hkv, D, v, q, T, depth, pl, splits = case
+    cfg = _cfg(name, "bf16", B, Hq, Hkv, D, v, q, T, depth, 40)
+    parents = None
+    if name == "paper_tree33":
+        parents = di.kary_budget_tree()[None]
+    x = di.verify_inputs(cfg, prefix_len=pl, parents=parents)
+    dream.dream_set_kv_splits(splits)
+    try:
+        got, lse = gu.run_verify(x)
+    finally:
+        dream.dream_set_kv_splits(0)
+    want, want_lse = oracle.tree_attn(x.q, x.k, x.v, "bf16", x.prefix_len, x.parent, True)
+    assert np.isfinite(got).all()
+    assert np.abs(got - want).max() <= TOL["bf16"], np.abs(got - want).max()
+    assert np.abs(lse - want_lse).max() <= 2e-3
+
+
+def test_explicit_tree_mask_matches_parent_derived_mask(gu):
+    cfg = _cfg("mask", "bf16", 2, 4, 2, 128, 100, 30, 60, 6, 41)
+    x = di.verify_inputs(cfg)
+    base, _ = gu.run_verify(x)
+    masks = np.stack([di.ancestor_mask_bits(x.parent[b], True)[:, 0] for b in range(cfg.batch)])
+    got, _ = gu.run_verify(x, tree_mask=masks)
+    assert np.array_equal(got, base)
+    # a mask that differs from the tree is honoured: pass the star tree's mask with the original parents
+    star = di.star_tree(cfg.n_tree)
+    star_mask = np.stack([di.ancestor_mask_bits(star, True)[:, 0]] * cfg.batch)
+    got2, _ = gu.run_verify(x, tree_mask=star_mask)
+    want, _ = oracle.tree_attn(x.q, x.k, x.v, "bf16", x.prefix_len, np.stack([star] * cfg.batch), True)
+    assert np.abs(got2 - want).max() <= TOL["bf16"]
+    assert np.abs(got2 - base).max() > 1e-3
+
+
+def test_custom_scale(gu):
+    cfg = _cfg("scale", "bf16", 1, 4, 4, 64, 80, 20, 30, 5, 42)
+    x = di.verify_inputs(cfg)
+    got, _ = gu.run_verify(x, scale=0.05)
+    want, _ = oracle.tree_attn(x.q, x.k, x.v, "bf16", x.prefix_len, x.parent, True, scale=0.05)
+    assert np.abs(got - want).max() <= TOL["bf16"]
+
+
+def test_outputs_are_reproducible_bit_for_bit(gu):
+    cfg = _cfg("repro", "bf16", 1, 8, 8, 128, 300, 60, 60, 6, 43)
+    x = di.verify_inputs(cfg)
+    dev = gu.DeviceAttn(x)
+    a, la = gu.run_verify(x, dev=dev)
+    b, lb = gu.run_verify(x, dev=dev)
+    assert np.array_equal(a, b) and np.array_equal(la, lb)
+
+
+FULL = ["llava", "pixtral", "gemma3", "smolvlm_b1", "smolvlm_b8"]
+
+
+def _sample_rows(cfg, n, seed):
+    g = di.rng(seed, 900)
+    return [(int(g.integers(0, cfg.batch)), int(g.integers(0, cfg.n_q_heads)), int(g.integers(0, cfg.n_tree)))
+            for _ in range(n)]
+
+
+@pytest.mark.parametrize("name", FULL)
+def test_full_size_verify_sampled_rows(gu, name):
+    """Full measurement shape, default launch configuration (the one bench.py times): 160 sampled
+    output rows against the oracle, plus finiteness of everything."""
+    cfg = di.CONFIGS[name]
+    x = di.verify_inputs(cfg)
+    got, lse = gu.run_verify(x)
+    assert np.isfinite(got).all() and np.isfinite(lse).all()
+    worst = 0.0
+    for (b, h, i) in _sample_rows(cfg, 160, cfg.seed):
+        want, wl = oracle.attn_row(x.q, x.k, x.v, cfg.dtype, x.prefix_len, x.parent, True, b, h, i)
+        worst = max(worst, np.abs(got[b, i, h] - want).max())
+        assert abs(lse[b, h, i] - wl) <= 2e-3
+    assert worst <= TOL["bf16"], worst
+
+
+def test_full_size_smolvlm_b32_sampled_rows(gu):
+    cfg = di.CONFIGS["smolvlm_b32"]
+    x = di.verify_inputs(cfg)
+    got, lse = gu.run_verify(x)
+    assert np.isfinite(got).all()
+    for (b, h, i) in _sample_rows(cfg, 200, cfg.seed):
+        want, wl = oracle.attn_row(x.q, x.k, x.v, cfg.dtype, x.prefix_len, x.parent, True, b, h, i)
+        assert np.abs(got[b, i, h] - want).max() <= TOL["bf16"]
+
+
+# ------------------------------------------------------------------------------------------------
+# draft cross-attention: strict ancestors, one call per tree level
+# ------------------------------------------------------------------------------------------------
+def test_tiny_config_xattn_levels(gu):
+    cfg = di.CONFIGS["tiny"]
+    x = di.xattn_inputs(cfg)
+    for lv in di.tree_levels(x.parent[0]):
+        rows = lv[None]
+        got, qsel = gu.run_xattn(x, rows, rows)
+        want, _ = oracle.tree_attn(qsel, x.k, x.v, cfg.dtype, x.prefix_len, x.parent, False, q_node=rows)
+        assert np.abs(got - want).max() <= TOL["f32"]
+
+
+XCASES = [
+    ("x_mha128", 2, 4, 4, 128, 150, 43, 60, 6, [193, 101]),
+    ("x_gqa4_128", 1, 8, 2, 128, 130, 31, 60, 6, [161]),
+    ("x_gqa2_256", 1, 4, 2, 256, 120, 45, 60, 6, [165]),
+    ("x_mha64", 2, 4, 4, 64, 200, 57, 60, 6, [257, 130]),
+]
+
+
+@pytest.mark.parametrize("case", XCASES, ids=[c[0] for c in XCASES])
+def test_bf16_xattn_levels_all_elements(gu, case):
+    name, B, Hq, Hkv, D, v, q, T, depth, pl = case
+    cfg = _cfg(name, "bf16", B, Hq, Hkv, D, v, q, T, depth, 44)
+    x = di.verify_inputs(cfg, prefix_len=pl, streams=(di.STREAM_XQ, di.STREAM_XK, di.STREAM_XV))
+    dev = gu.DeviceAttn(x)
+    for lvl in range(depth + 1):
+        rows = np.stack([di.tree_levels(x.parent[b])[lvl] for b in range(B)])
+        got, qsel = gu.run_xattn(x, rows, rows, dev=dev)
+        want, _ = oracle.tree_attn(qsel, x.k, x.v, "bf16", x.prefix_len, x.parent, False, q_node=rows)
+        assert np.abs(got - want).max() <= TOL["bf16"]
+
+
+def test_xattn_all_nodes_in_one_call_without_q_node(gu):
+    cfg = _cfg("x_all", "bf16", 1, 4, 4, 128, 100, 28, 60, 6, 45)
+    x = di.verify_inputs(cfg)
+    rows = np.arange(cfg.n_tree, dtype=np.int32)[None]
+    got, qsel = gu.run_xattn(x, rows, None)
+    want, _ = oracle.tree_attn(qsel, x.k, x.v, "bf16", x.prefix_len, x.parent, False)
+    assert np.abs(got - want).max() <= TOL["bf16"]
+    # strict mask differs from the verification mask
+    ver, _ = oracle.tree_attn(qsel, x.k, x.v, "bf16", x.prefix_len, x.parent, True)
+    assert np.abs(got - ver).max() > 1e-3
+
+
+def test_xattn_root_with_empty_prefix_gives_zero_row(gu):
+    cfg = _cfg("x_empty", "bf16", 1, 2, 2, 64, 0, 0, 12, 3, 46)
+    x = di.verify_inputs(cfg, prefix_len=[0])
+    rows = np.arange(cfg.n_tree, dtype=np.int32)[None]
+    got, qsel = gu.run_xattn(x, rows, rows)
+    want, _ = oracle.tree_attn(qsel, x.k, x.v, "bf16", x.prefix_len, x.parent, False, q_node=rows)
+    assert np.all(got[0, 0] == 0.0)
+    assert np.abs(got - want).max() <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("name", ["llava", "pixtral", "gemma3", "smolvlm_b8"])
+def test_full_size_xattn_round_sampled(gu, name):
+    """One drafting round at the measurement shape: a call per tree level (1,10,10,10,10,10,9 rows)."""
+    cfg = di.CONFIGS[name]
+    x = di.xattn_inputs(cfg)
+    dev = gu.DeviceAttn(x)
+    g = di.rng(cfg.seed, 901)
+    for lvl in range(cfg.depth + 1):
+        rows = np.stack([di.tree_levels(x.parent[b])[lvl] for b in range(cfg.batch)])
+        got, qsel = gu.run_xattn(x, rows, rows, dev=dev)
+        assert np.isfinite(got).all()
+        for _ in range(24):
+            b, h, r = int(g.integers(0, cfg.batch)), int(g.integers(0, cfg.n_q_heads)), int(g.integers(0, rows.shape[1]))
+            want, _ = oracle.attn_row(qsel, x.k, x.v, cfg.dtype, x.prefix_len, x.parent, False, b, h, r, node=int(rows[b, r]))
+            assert np.abs(got[b, r, h] - want).max() <= TOL["bf16"]
