@@ -1,0 +1,260 @@
+#!/usr/bin/env python3
+"""Benchmark of the DREAM decode-step hot path on one MI355X.
+
+One step = one pass over the whole hot path on one batch of synthetic input:
+  n_layers x dream_tree_verify_attn (one call per target layer, each over its own K/V cache)
+  + 6 x dream_draft_xattn (one call per drafted tree level)
+  + dream_visual_compress (scores over all prefill rows, top-k keep, row gather)
+  + dream_accept_path.
+All inputs are resident in HBM before the timed region.  The four phases are captured as HIP graphs
+(no memset nodes) and replayed; HIP events between the graph launches, on the launching stream, give
+the time of the verification block, from which the roofline figure of the dominant kernel is derived.
+
+Prints ONE JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+PAPER_TAU = {"llava": 5.51, "pixtral": 3.78, "gemma3": 2.36, "smolvlm_b1": 3.09, "smolvlm_b8": 3.09, "smolvlm_b32": 3.09}
+PLANT_DEPTH = 4   # accepted drafted tokens per step in the synthetic logits (5 tokens a step with the bonus)
+
+
+def verify_bytes_per_launch(cfg) -> int:
+    """Algorithmic bytes of one dream_tree_verify_attn call: K and V rows once, Q in, O out."""
+    S = cfg.prefix + cfg.n_tree
+    e = cfg.elem_bytes
+    return 2 * cfg.batch * cfg.n_kv_heads * S * cfg.head_dim * e + 2 * cfg.batch * cfg.n_q_heads * cfg.n_tree * cfg.head_dim * e
+
+
+def read_traffic(name: str):
+    """HBM traffic per launch measured with rocprofv3 --pmc (committed summary), or None."""
+    path = os.path.join(ROOT, "profiles", f"attn_verify_{name}_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", default="llava")
+    ap.add_argument("--layers", type=int, default=0, help="target layers per step (0 = the configuration's)")
+    ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--splits", type=int, default=0, help="force the number of key-range splits (0 = automatic)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); --gpus must be 1", file=sys.stderr)
+        return 2
+
+    import torch
+    import dream_inputs as di
+    import paper_2505_19201_amd as dream
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    dream.load()
+    cfg = di.CONFIGS[args.config]
+    L = args.layers or cfg.n_layers
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    B, T, Hq, Hkv, D, P = cfg.batch, cfg.n_tree, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.prefix
+    S = P + T
+    s_max = S
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(cfg.seed)
+
+    def randn(*shape):
+        return torch.randn(*shape, generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+
+    # ---- resident inputs -------------------------------------------------------------------------
+    parents_np = np.stack([di.config_tree(cfg, b) for b in range(B)])
+    parent = dream.to_device(parents_np)
+    prefix_len = torch.full((B,), P, dtype=torch.int32, device=dev)
+    vq = [randn(B, T, Hq, D) for _ in range(L)]
+    vk = [randn(B, Hkv, s_max, D) for _ in range(L)]
+    vv = [randn(B, Hkv, s_max, D) for _ in range(L)]
+    vout = [torch.empty(B, T, Hq, D, dtype=torch.bfloat16, device=dev) for _ in range(L)]
+    desc = dream.attn_desc(B, Hq, Hkv, D, dream.BF16, s_max)
+    if args.splits:
+        dream.dream_set_kv_splits(args.splits)
+    ws_v = dream.alloc_workspace(dream.dream_tree_verify_attn_workspace(desc, T, S))
+
+    levels = [np.stack([di.tree_levels(parents_np[b])[lv] for b in range(B)]) for lv in range(cfg.depth)]
+    xk, xv = randn(B, Hkv, s_max, D), randn(B, Hkv, s_max, D)
+    xq = [randn(B, lv.shape[1], Hq, D) for lv in levels]
+    xnode = [dream.to_device(np.ascontiguousarray(lv, dtype=np.int32)) for lv in levels]
+    xout = [torch.empty_like(t) for t in xq]
+    ws_x = dream.alloc_workspace(max(dream.dream_draft_xattn_workspace(desc, lv.shape[1], S) for lv in levels))
+
+    pq = randn(B, P, Hq, D)
+    rows = randn(B, P, cfg.hidden)
+    k_keep = (cfg.n_visual * cfg.keep_num + cfg.keep_den // 2) // cfg.keep_den
+    kept = torch.empty(B, k_keep, dtype=torch.int32, device=dev)
+    gathered = torch.empty(B, k_keep, cfg.hidden, dtype=torch.bfloat16, device=dev)
+    scores = torch.empty(B, cfg.n_visual, dtype=torch.float32, device=dev)
+    ws_c = dream.alloc_workspace(dream.dream_visual_compress_workspace(desc, P, cfg.n_visual))
+
+    lg_np, tok_np, par_np, _ = di.accept_inputs(cfg, plant_depths=[PLANT_DEPTH] * B)
+    logits = dream.to_device(lg_np, "bf16")
+    token = dream.to_device(tok_np)
+    node_argmax = torch.empty(B, T, dtype=torch.int32, device=dev)
+    accept_len = torch.empty(B, dtype=torch.int32, device=dev)
+    accept_path = torch.empty(B, cfg.depth + 1, dtype=torch.int32, device=dev)
+    bonus = torch.empty(B, dtype=torch.int32, device=dev)
+    ws_a = dream.alloc_workspace(dream.dream_accept_path_workspace(B, T, cfg.vocab))
+
+    def phase_verify():
+        for l in range(L):
+            dream.dream_tree_verify_attn(desc, vq[l], vk[l], vv[l], prefix_len, T, parent, None, S, vout[l], None, ws_v)
+
+    def phase_xattn():
+        for i in range(len(levels)):
+            dream.dream_draft_xattn(desc, xq[i], xk, xv, prefix_len, T, parent, levels[i].shape[1], xnode[i], S, xout[i], ws_x)
+
+    def phase_compress():
+        dream.dream_visual_compress(desc, pq, None, P, vk[L - 1], P, 0, cfg.n_visual, cfg.keep_num, cfg.keep_den, None,
+                                    scores, kept, rows, P, gathered, cfg.hidden, ws_c)
+
+    def phase_accept():
+        dream.dream_accept_path(logits, dream.BF16, B, T, cfg.vocab, token, parent, cfg.depth, node_argmax, accept_len,
+                                accept_path, bonus, ws_a)
+
+    phases = [("verify", phase_verify), ("xattn", phase_xattn), ("compress", phase_compress), ("accept", phase_accept)]
+    for _, f in phases:      # eager warm-up: also sets kernel attributes before any capture
+        f()
+    torch.cuda.synchronize()
+
+    stream = torch.cuda.Stream()
+    runners = []
+    if args.no_graph:
+        runners = [f for _, f in phases]
+    else:
+        for _, f in phases:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=stream):
+                f()
+            runners.append(g.replay)
+    torch.cuda.synchronize()
+
+    def one_step(evs=None):
+        for i, r in enumerate(runners):
+            if evs is not None:
+                evs[i].record()
+            r()
+        if evs is not None:
+            evs[len(runners)].record()
+
+    with torch.cuda.stream(stream):
+        for _ in range(args.warmup):
+            one_step()
+        stream.synchronize()
+        torch.cuda.synchronize()
+        all_evs = [[torch.cuda.Event(enable_timing=True) for _ in range(len(runners) + 1)] for _ in range(args.steps)]
+        t0 = time.perf_counter()
+        for s in range(args.steps):
+            one_step(all_evs[s])
+        stream.synchronize()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    phase_ms = [float(np.mean([all_evs[s][i].elapsed_time(all_evs[s][i + 1]) for s in range(args.steps)]))
+                for i in range(len(runners))]
+    tokens_per_step = int((accept_len + 1).sum().item())
+    assert tokens_per_step == B * (PLANT_DEPTH + 1), "accept_path did not return the planted path"
+    value = tokens_per_step / (ms_per_step * 1e-3)
+
+    launch_us = phase_ms[0] * 1e3 / L
+    bytes_launch = verify_bytes_per_launch(cfg)
+    achieved = bytes_launch / (launch_us * 1e-6) / 1e9
+    roofline = {"bound": "hbm", "kernel": "attn_bf16_kernel (dream_tree_verify_attn)", "achieved": round(achieved, 1),
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": read_traffic(cfg.name), "bytes_per_launch": bytes_launch,
+                "launch_us": round(launch_us, 3), "launches_per_step": L}
+
+    out = {
+        "metric": "verify+draft step throughput (tokens/s) and latency on 1 MI355X",
+        "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5), "step_latency_us": round(ms_per_step * 1e3, 2),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: B={B} Hq={Hq} Hkv={Hkv} D={D} prefix={cfg.n_visual}+{cfg.n_text} tree={T} "
+                               f"depth={cfg.depth} layers={L} vocab={cfg.vocab} keep={cfg.keep_num}/{cfg.keep_den}",
+                   "tokens_per_step": tokens_per_step, "hip_graph": not args.no_graph,
+                   "kv_splits": args.splits or "auto"},
+        "phase_us": {n: round(ms * 1e3, 2) for (n, _), ms in zip(phases, phase_ms)},
+        "tokens_per_s_at_paper_tau": round(B * PAPER_TAU.get(cfg.name, 0.0) / (ms_per_step * 1e-3), 1),
+        "roofline": roofline,
+    }
+
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(cfg, L, tokens_per_step)
+    print(json.dumps(out))
+    return 0
+
+
+def cpu_baseline(cfg, L, tokens_per_step):
+    """The float64 oracle, as it stands, timed on this host: one verification layer (scaled by the layer
+    count), the six cross-attention calls, the compression call and the acceptance call."""
+    import dream_inputs as di
+    import oracle
+
+    threads = min(16, oracle.hw_threads())
+    oracle.set_threads(threads)
+    x = di.verify_inputs(cfg)
+    nb = min(cfg.batch, 2)   # bounded sample of the batch
+    scale_b = cfg.batch / nb
+
+    def sub(a):
+        return np.ascontiguousarray(a[:nb])
+
+    t = time.perf_counter()
+    oracle.tree_attn(sub(x.q), sub(x.k), sub(x.v), cfg.dtype, x.prefix_len[:nb], x.parent[:nb], True)
+    t_verify = (time.perf_counter() - t) * scale_b
+    t = time.perf_counter()
+    for lv in range(cfg.depth):
+        rows = np.stack([di.tree_levels(x.parent[b])[lv] for b in range(nb)])
+        qsel = np.stack([x.q[b, rows[b]] for b in range(nb)])
+        oracle.tree_attn(qsel, sub(x.k), sub(x.v), cfg.dtype, x.prefix_len[:nb], x.parent[:nb], False, q_node=rows)
+    t_xattn = (time.perf_counter() - t) * scale_b
+    pq = di.prefill_q(cfg)[:nb]
+    t = time.perf_counter()
+    sc = oracle.visual_scores(np.ascontiguousarray(pq), sub(x.k), cfg.dtype, 0, cfg.n_visual)
+    kept = oracle.topk_keep(sc, 0, cfg.keep_num, cfg.keep_den)
+    oracle.gather_rows(di.feature_rows(cfg)[:nb], cfg.dtype, kept)
+    t_comp = (time.perf_counter() - t) * scale_b
+    lg, tok, par, _ = di.accept_inputs(cfg, plant_depths=[PLANT_DEPTH] * cfg.batch)
+    t = time.perf_counter()
+    oracle.accept_path(np.ascontiguousarray(lg[:nb]), cfg.dtype, tok[:nb], par[:nb], cfg.depth)
+    t_acc = (time.perf_counter() - t) * scale_b
+    oracle.set_threads(1)
+    step_s = L * t_verify + t_xattn + t_comp + t_acc
+    return {"value": round(tokens_per_step / step_s, 3), "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "step_s": round(step_s, 3),
+            "sample": f"{nb} of {cfg.batch} sequences; 1 of {L} verification layers timed and scaled by {L}; "
+                      f"6 cross-attention calls, compression and acceptance timed in full",
+            "parts_s": {"verify_layer": round(t_verify, 4), "xattn": round(t_xattn, 4), "compress": round(t_comp, 4),
+                        "accept": round(t_acc, 4)}}
+
+
+if __name__ == "__main__":
+    sys.exit(main())
