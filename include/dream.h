@@ -55,7 +55,7 @@ typedef enum {
     DREAM_ERR_HIP = -4          /* a HIP launch reported an error                              */
 } dream_status;
 
-#define DREAM_WORKSPACE_HEADER_BYTES 4096
+#define DREAM_WORKSPACE_HEADER_BYTES 65536
 #define DREAM_MAX_TREE 64       /* tree nodes per sequence handled by the attention calls      */
 #define DREAM_MAX_TREE_ACCEPT 1024 /* tree nodes per sequence handled by dream_accept_path     */
 #define DREAM_MAX_VISUAL 16384  /* visual tokens per sequence handled by dream_visual_compress */
@@ -171,9 +171,12 @@ int dream_tree_validate_host(const int32_t *parent_host, int32_t n_tree, int32_t
 /* Text of the calling thread's last error ("" if none); static storage, never NULL. */
 const char *dream_last_error(void);
 
-/* Launch-shape override for experiments: number of key-range splits the attention calls use
- * (0 = choose automatically).  Results are identical up to floating-point summation order. */
+/* Launch-shape overrides for experiments (0 = choose automatically): number of key-range splits
+ * the attention calls use, and number of 16-row query tiles one workgroup serves (1, 2 or 4).
+ * Results are identical up to floating-point summation order.  Query the workspace size again
+ * after changing either. */
 void dream_set_kv_splits(int32_t n_splits);
+void dream_set_q_tiles(int32_t q_tiles);
 
 #ifdef __cplusplus
 }

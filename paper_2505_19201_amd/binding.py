@@ -21,7 +21,7 @@ EXPORTED_SYMBOLS = (
     "dream_workspace_init", "dream_tree_verify_attn_workspace", "dream_tree_verify_attn",
     "dream_draft_xattn_workspace", "dream_draft_xattn", "dream_visual_compress_workspace",
     "dream_visual_compress", "dream_accept_path_workspace", "dream_accept_path",
-    "dream_tree_validate_host", "dream_last_error", "dream_set_kv_splits",
+    "dream_tree_validate_host", "dream_last_error", "dream_set_kv_splits", "dream_set_q_tiles",
 )
 
 
@@ -63,6 +63,7 @@ def load() -> C.CDLL:
             getattr(lib, name).restype = C.c_size_t
         lib.dream_last_error.restype = C.c_char_p
         lib.dream_set_kv_splits.restype = None
+        lib.dream_set_q_tiles.restype = None
         _lib = lib
     return _lib
 
@@ -95,6 +96,10 @@ def dream_set_kv_splits(n_splits: int) -> None:
     load().dream_set_kv_splits(C.c_int32(n_splits))
 
 
+def dream_set_q_tiles(q_tiles: int) -> None:
+    load().dream_set_q_tiles(C.c_int32(q_tiles))
+
+
 def dream_workspace_init(workspace: torch.Tensor, stream=None) -> None:
     _check(load().dream_workspace_init(_dev(workspace), C.c_size_t(workspace.numel() * workspace.element_size()),
                                        _stream(stream)))
@@ -102,7 +107,7 @@ def dream_workspace_init(workspace: torch.Tensor, stream=None) -> None:
 
 def alloc_workspace(nbytes: int, device="cuda") -> torch.Tensor:
     """Device scratch of at least nbytes with its header zeroed (allocation is the caller's job in C)."""
-    ws = torch.empty(max(int(nbytes), 4096), dtype=torch.uint8, device=device)
+    ws = torch.empty(max(int(nbytes), 65536), dtype=torch.uint8, device=device)
     dream_workspace_init(ws)
     return ws
 

@@ -6,6 +6,7 @@ namespace dream {
 
 static thread_local char g_error[512] = "";
 static int g_kv_splits = 0;
+static int g_q_tiles = 0;
 
 char *error_buffer() { return g_error; }
 
@@ -27,6 +28,7 @@ int check_launch(const char *what)
 }
 
 int kv_splits_override() { return g_kv_splits; }
+int q_tiles_override() { return g_q_tiles; }
 
 __global__ void zero_words_kernel(uint32_t *p, int n)
 {
@@ -44,6 +46,8 @@ extern "C" {
 const char *dream_last_error(void) { return error_buffer(); }
 
 void dream_set_kv_splits(int32_t n_splits) { dream::g_kv_splits = n_splits < 0 ? 0 : n_splits; }
+
+void dream_set_q_tiles(int32_t q_tiles) { dream::g_q_tiles = q_tiles < 0 ? 0 : q_tiles; }
 
 int dream_workspace_init(void *workspace, size_t workspace_bytes, void *stream)
 {
