@@ -4,27 +4,33 @@
 // see: the whole cached prefix plus its ancestors in the draft tree (Section 3.1, tree-masking
 // paragraph); verification includes the node itself, the draft's cross-attention does not.
 //
-// bf16 path (attn_bf16_kernel).  A workgroup serves one (sequence, KV head, key-range split,
-// query group); a query group is QG 16-row query tiles out of the G * ceil(n_q/16) tiles that
-// share the KV head (all tree rows of all query heads of the GQA group).  Its 4 waves stream
-// disjoint 32-key tiles of the range: a wave loads its tile with 16-byte coalesced loads, parks
-// it in a wave-private LDS area (no workgroup barrier in the loop) and reuses every K/V byte
-// for all QG*16 query rows.  Scores are formed transposed, S^T = K Q^T, with
+// bf16 path (attn_bf16_kernel).  A workgroup serves one (sequence, KV head, key-range split, query
+// group).  The query rows that share a KV head - every tree row of every query head of the GQA
+// group - are cut into 16-row tiles; a query group is 4*QG of them and each of the 4 waves owns QG.
+// All 256 threads stream the key range in 32-key K/V tiles with 16-byte coalesced loads kept two
+// or three tiles ahead in registers, park each tile in one of two LDS stages (one barrier per
+// tile), and every wave reads the tile's MFMA fragments from LDS: a K/V byte leaves HBM once and
+// serves all tree rows and all heads of the group.  Scores are formed transposed, S^T = K Q^T, with
 // v_mfma_f32_16x16x32_bf16, so a lane owns one query column: the online-softmax state is a
 // per-lane scalar and the fp32 score registers, converted to bf16, already are the B operand of
 // the second contraction O^T += V^T P^T, whose A operand (V transposed) comes from the LDS
-// transpose read ds_read_b64_tr_b16.  At the end the 4 waves merge their (max, sum, O) states
-// through LDS in a fixed order.  When B * Hkv * query groups cannot fill 256 CUs the key range is
-// split over several workgroups; each writes its state to the workspace, takes a ticket, and
-// the last arrival merges all states of its group in split order (deterministic) and writes the
-// output - one launch, no separate combine kernel.  Workgroups that read the same K/V stream
-// (the query groups of one split) are given ids congruent mod 8 so that they run on one XCD and
-// share its L2: HBM sees every K/V byte once.
+// transpose read ds_read_b64_tr_b16.  The softmax reference of a column is raised only when a
+// score exceeds it by 8 octaves, so accumulators are rescaled a handful of times per call.
+//
+// One CU can keep only a few tens of KB of loads in flight, so a short stream is bandwidth-starved
+// unless all 256 CUs pull a share of it: when B * Hkv * query groups is small the key range is split
+// over several workgroups, each writes its (reference, sum, O) state to the workspace, and
+// attn_merge_kernel merges the states of a group in split order (deterministic) and writes the
+// rows.  (A last-arrival merge inside the kernel needs device-scope fences, whose L2 write-back
+// and invalidate cost more than the second launch.)  Workgroups that read the same K/V stream (the
+// query groups of one split) get ids congruent mod 8 so that they run on one XCD and share its L2.
 //
 // fp32 path (attn_f32_kernel): plain vector-ALU kernel, one workgroup per (query row, head,
 // sequence), used for float32 tensors (the small correctness configuration).
 #include "common.h"
 #include <math.h>
+#include <stdlib.h>
+#include <string.h>
 
 using namespace dream;
 
@@ -36,8 +42,7 @@ struct AttnArgs {
     const uint64_t *tree_mask;
     void *out;
     float *lse;
-    float *part;        // [groups, splits, state] merged wave states of every split
-    int32_t *counters;  // [groups] arrival tickets, zero between calls
+    float *part;             // [groups, splits, 4 waves, state] per-wave states of every split
     int32_t n_q_heads, n_kv_heads, group;
     int32_t n_q, n_tree, include_self;
     int32_t tiles_per_head;  // 16-row query tiles per head
@@ -58,25 +63,22 @@ __device__ __forceinline__ uint64_t visible_nodes(const AttnArgs &a, int b, int 
     return m;
 }
 
-// LDS traffic inside one wave needs no barrier, only program order.
-__device__ __forceinline__ void wave_lds_fence()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
-template <int D, int QG>
+template <int D, int QG, int KT>
 struct Geom {
     static constexpr int KSTR = D + 8;    // K row stride in LDS (elements): 16-byte pad, b128 reads spread over all banks
     static constexpr int VSTR = D + 16;   // V row stride in LDS (elements): 4 consecutive rows land 8 banks apart
-    static constexpr int WAVE_ELEMS = 32 * (KSTR + VSTR);
+    static constexpr int TILE_ELEMS = 32 * (KSTR + VSTR);   // one 32-key K tile followed by its V tile
+    static constexpr int STAGE_ELEMS = KT * TILE_ELEMS;     // a step handles KT tiles
     static constexpr int NDT = D / 16;
-    static constexpr int CH = 32 * D / 8 / 64;                       // 16-byte chunks per lane per tensor per tile
-    static constexpr int STATE_FLOATS = QG * NDT * 256 + QG * 2 * 64;  // one wave's (O, max, sum) in lane-major order
-    static constexpr size_t TILE_BYTES = (size_t)4 * WAVE_ELEMS * 2;
-    static constexpr size_t MERGE_BYTES = (size_t)2 * STATE_FLOATS * 4;
-    static constexpr size_t LDS_BYTES = (TILE_BYTES > MERGE_BYTES ? TILE_BYTES : MERGE_BYTES) + DREAM_MAX_TREE * sizeof(int32_t);
+    static constexpr int NKS = D / 32;
+    static constexpr int CH = 32 * D / 8 / 256;             // 16-byte chunks per thread per tensor per tile
+    static constexpr size_t LDS_BYTES = (size_t)2 * STAGE_ELEMS * 2 + DREAM_MAX_TREE * sizeof(int32_t);
+};
+
+template <int D, int QG>
+struct StateGeom {
+    static constexpr int NDT = D / 16;
+    static constexpr int STATE_FLOATS = QG * NDT * 256 + QG * 2 * 64;   // one wave's (O, reference, sum) in lane-major order
 };
 
 template <int QG, int NDT>
@@ -98,39 +100,184 @@ __device__ __forceinline__ void state_store(const WaveState<QG, NDT> &s, float *
     }
 }
 
-// s <- s (+) state at src, the associative merge of two online-softmax states
-template <int QG, int NDT>
-__device__ __forceinline__ void state_merge(WaveState<QG, NDT> &s, const float *src, int lane)
+// Row ownership of a lane: query tile qt of wave `wave` in query group qg -> (query head, query row) of column c.
+struct RowOwner {
+    int row, head;
+};
+__device__ __forceinline__ RowOwner row_owner(const AttnArgs &a, int kvh, int qg, int wave, int QG, int qt, int c)
 {
+    int tq = (qg * 4 + wave) * QG + qt;
+    int hh = tq / a.tiles_per_head, nt = tq % a.tiles_per_head;
+    int row = nt * 16 + c;
+    bool valid = tq < a.group * a.tiles_per_head && row < a.n_q;
+    RowOwner r;
+    r.row = valid ? row : -1;
+    r.head = kvh * a.group + hh;
+    return r;
+}
+
+// The softmax reference of a column is only raised when a score exceeds it by more than this many
+// octaves, so exp2(score - reference) stays below 2^8 and the accumulators are seldom rescaled.
+#define DREAM_SOFTMAX_SLACK 8.0f
+#ifndef DREAM_Q1_WAVES
+#define DREAM_Q1_WAVES 2
+#endif
+
+// Optional in-kernel timeline (build with -DDREAM_TIMESTAMPS): lane 0 of each wave of workgroup 8 records
+// the shader clock at a few points into a host-visible buffer.  Compiled out of the product build.
+#ifdef DREAM_TIMESTAMPS
+__device__ unsigned long long *g_dev_ts = nullptr;
+#define TS(i) do { if (g_dev_ts && blockIdx.x == 8 && lane == 0) g_dev_ts[wave * 64 + (i)] = clock64(); } while (0)
+#else
+#define TS(i) do { } while (0)
+#endif
+
+// QK^T, online softmax and PV for KT consecutive 32-key tiles held in LDS at `stage` (K tile, then V tile,
+// per 32 keys), for the QG query tiles of this wave.  key0 is the global key index of the first row.
+template <int D, int QG, int KT>
+__device__ __forceinline__ void tiles_compute(const uint16_t *stage, int key0, int P, int key_end, int n_tree, float scale_log2,
+                                              const bf16x8 (&qf)[QG][D / 32], const uint64_t (&qmask)[QG],
+                                              WaveState<QG, D / 16> &st, int c, int g)
+{
+    using G = Geom<D, QG, KT>;
+    constexpr int KSTR = G::KSTR, VSTR = G::VSTR, NDT = G::NDT, NKS = G::NKS;
+    const bool needs_mask = key0 + KT * 32 > min(P, key_end);   // step touches tree rows, the ragged end or the next split
+
+    // ---- S^T = K Q^T for KT*32 keys x (16 * QG) query columns; independent accumulators keep the MFMA pipe full
+    f32x4 sacc[KT][2][QG];
+#pragma unroll
+    for (int kt = 0; kt < KT; kt++) {
+        const uint16_t *sk = stage + kt * G::TILE_ELEMS;
+        bf16x8 kfr[2][NKS];
+#pragma unroll
+        for (int ks = 0; ks < NKS; ks++) {
+            kfr[0][ks] = *reinterpret_cast<const bf16x8 *>(sk + c * KSTR + ks * 32 + g * 8);
+            kfr[1][ks] = *reinterpret_cast<const bf16x8 *>(sk + (16 + c) * KSTR + ks * 32 + g * 8);
+        }
+#pragma unroll
+        for (int qt = 0; qt < QG; qt++) {
+            sacc[kt][0][qt] = f32x4{0.f, 0.f, 0.f, 0.f};
+            sacc[kt][1][qt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+#pragma unroll
+        for (int ks = 0; ks < NKS; ks++) {
+#pragma unroll
+            for (int qt = 0; qt < QG; qt++) {
+                sacc[kt][0][qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kfr[0][ks], qf[qt][ks], sacc[kt][0][qt], 0, 0, 0);
+                sacc[kt][1][qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kfr[1][ks], qf[qt][ks], sacc[kt][1][qt], 0, 0, 0);
+            }
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // ---- V^T fragments of the first tile (first half of the head dimension for D = 256) are requested
+    // now, so their LDS latency hides behind the softmax arithmetic
+    constexpr int VH = D == 256 ? 2 : 1, NDH = NDT / VH;
+    s16x4 vfr[NDH][2];
+    const int v_off = 32 * KSTR + (g * 4 + (c >> 2)) * VSTR + (c & 3) * 4;
+    auto read_v = [&](int kt, int h) {
+        const uint16_t *vrow = stage + kt * G::TILE_ELEMS + v_off + h * NDH * 16;
+#pragma unroll
+        for (int dt = 0; dt < NDH; dt++) {
+            vfr[dt][0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(vrow + dt * 16));
+            vfr[dt][1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(vrow + dt * 16 + 16 * VSTR));
+        }
+    };
+    read_v(0, 0);
+    // ---- online softmax; lane owns query column c and key rows g*4+r of every 16-key block
+    bf16x8 pf[KT][QG];
+    bool raise = false;
 #pragma unroll
     for (int qt = 0; qt < QG; qt++) {
-        float mo = src[QG * NDT * 256 + (qt * 2) * 64 + lane];
-        float lo = src[QG * NDT * 256 + (qt * 2 + 1) * 64 + lane];
-        float mn = fmaxf(s.m[qt], mo);
-        float ms = (mn == -INFINITY) ? 0.0f : mn;
-        float a1 = __builtin_amdgcn_exp2f(s.m[qt] - ms), a2 = __builtin_amdgcn_exp2f(mo - ms);
-        s.l[qt] = s.l[qt] * a1 + lo * a2;
-        s.m[qt] = mn;
+        float mx = -INFINITY;
 #pragma unroll
-        for (int dt = 0; dt < NDT; dt++) {
-            f32x4 oo = reinterpret_cast<const f32x4 *>(src)[(qt * NDT + dt) * 64 + lane];
-            s.o[qt][dt] = s.o[qt][dt] * a1 + oo * a2;
+        for (int kt = 0; kt < KT; kt++) {
+#pragma unroll
+            for (int e = 0; e < 8; e++) {
+                float x = sacc[kt][e >> 2][qt][e & 3] * scale_log2;
+                if (needs_mask) {
+                    const int key = key0 + kt * 32 + (e >> 2) * 16 + g * 4 + (e & 3);
+                    const int rel = key - P;
+                    const uint32_t bit = (uint32_t)(qmask[qt] >> (rel & 63)) & 1u;
+                    const uint32_t vis = ((uint32_t)(rel < 0) | ((uint32_t)(rel < n_tree) & bit)) & (uint32_t)(key < key_end);
+                    x = vis ? x : -INFINITY;
+                }
+                sacc[kt][e >> 2][qt][e & 3] = x;
+                mx = fmaxf(mx, x);
+            }
+        }
+        raise = raise || (mx > st.m[qt] + DREAM_SOFTMAX_SLACK);
+    }
+    if (__any(raise)) {
+        // rare: some column's reference is raised to the true maximum over its 4 row groups
+#pragma unroll
+        for (int qt = 0; qt < QG; qt++) {
+            float mx = -INFINITY;
+#pragma unroll
+            for (int kt = 0; kt < KT; kt++)
+#pragma unroll
+                for (int e = 0; e < 8; e++)
+                    mx = fmaxf(mx, sacc[kt][e >> 2][qt][e & 3]);
+            mx = fmaxf(mx, __shfl_xor(mx, 16));
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            if (mx > st.m[qt] + DREAM_SOFTMAX_SLACK) {
+                float alpha = __builtin_amdgcn_exp2f(st.m[qt] - mx);   // 0 when the old reference was -inf
+                st.m[qt] = mx;
+                st.l[qt] *= alpha;
+#pragma unroll
+                for (int dt = 0; dt < NDT; dt++)
+                    st.o[qt][dt] *= alpha;
+            }
+        }
+    }
+#pragma unroll
+    for (int qt = 0; qt < QG; qt++) {
+        const float m_safe = (st.m[qt] == -INFINITY) ? 0.0f : st.m[qt];
+        float psum = 0.0f;
+#pragma unroll
+        for (int kt = 0; kt < KT; kt++) {
+#pragma unroll
+            for (int e = 0; e < 8; e++) {
+                float p = __builtin_amdgcn_exp2f(sacc[kt][e >> 2][qt][e & 3] - m_safe);
+                psum += p;
+                pf[kt][qt][e] = (__bf16)p;
+            }
+        }
+        st.l[qt] += psum;
+    }
+    // ---- O^T += V^T P^T
+#pragma unroll
+    for (int kt = 0; kt < KT; kt++) {
+#pragma unroll
+        for (int h = 0; h < VH; h++) {
+            if (kt > 0 || h > 0)
+                read_v(kt, h);
+#pragma unroll
+            for (int dt = 0; dt < NDH; dt++) {
+                s16x8 vv = __builtin_shufflevector(vfr[dt][0], vfr[dt][1], 0, 1, 2, 3, 4, 5, 6, 7);
+                bf16x8 vf = __builtin_bit_cast(bf16x8, vv);
+#pragma unroll
+                for (int qt = 0; qt < QG; qt++)
+                    st.o[qt][h * NDH + dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[kt][qt], st.o[qt][h * NDH + dt], 0, 0, 0);
+            }
         }
     }
 }
 
-template <int D, int QG>
-__global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a)
+// KT: 32-key tiles handled per step (per barrier, per softmax update); PFD: steps kept in flight in registers.
+template <int D, int QG, int KT, int PFD>
+__global__ __launch_bounds__(256, (QG == 1 && D <= 128) ? DREAM_Q1_WAVES : 1) void attn_bf16_kernel(AttnArgs a)
 {
-    using G = Geom<D, QG>;
-    constexpr int KSTR = G::KSTR, VSTR = G::VSTR, CH = G::CH, NDT = G::NDT;
-    constexpr int NKS = D / 32;   // 32-deep contraction steps of q.k
+    using G = Geom<D, QG, KT>;
+    constexpr int KSTR = G::KSTR, VSTR = G::VSTR, CH = G::CH, NDT = G::NDT, NKS = G::NKS;
+    constexpr int NLD = KT * CH;   // 16-byte chunks per thread per tensor per step
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     uint16_t *lds = reinterpret_cast<uint16_t *>(smem_raw);
-    int32_t *lds_parent = reinterpret_cast<int32_t *>(smem_raw + (G::LDS_BYTES - DREAM_MAX_TREE * sizeof(int32_t)));
+    int32_t *lds_parent = reinterpret_cast<int32_t *>(smem_raw + (size_t)2 * G::STAGE_ELEMS * 2);
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps bookkeeping in scalar registers
     const int c = lane & 15, g = lane >> 4;
+    TS(0);
 
     // workgroup id -> (K/V stream, query group): ids that share a stream are congruent mod 8 (same XCD)
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
@@ -140,75 +287,80 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a)
     const int nsplit = a.n_splits;
     const int split = stream % nsplit, bk = stream / nsplit;
     const int kvh = bk % a.n_kv_heads, b = bk / a.n_kv_heads;
+
+    // tree metadata is requested first: the mask walk then overlaps the K/V loads still in flight
+    int32_t my_parent = -1;
+    if (!a.tree_mask && tid < a.n_tree)
+        my_parent = a.parent[(int64_t)b * a.n_tree + tid];
+
     const int P = a.prefix_len[b];
     const int kv_len = P + a.n_tree;
     const int tiles_total = (kv_len + 31) / 32;
     const int tps = (tiles_total + nsplit - 1) / nsplit;
     const int t_begin = split * tps;
     const int t_end = min(t_begin + tps, tiles_total);
+    const int n_my = max(t_end - t_begin, 0);
+    const int n_steps = (n_my + KT - 1) / KT;
+    const int key_end = min(kv_len, t_end * 32);   // keys at or past it belong to nobody or to the next split
+    if (key_end >= 0) TS(1);
 
     const uint16_t *kbase = reinterpret_cast<const uint16_t *>(a.k) + ((int64_t)b * a.n_kv_heads + kvh) * a.s_max * D;
     const uint16_t *vbase = reinterpret_cast<const uint16_t *>(a.v) + ((int64_t)b * a.n_kv_heads + kvh) * a.s_max * D;
 
-    if (!a.tree_mask && tid < a.n_tree)
-        lds_parent[tid] = a.parent[(int64_t)b * a.n_tree + tid];
-
-    uint4 kreg[CH], vreg[CH];
-    auto load_tile = [&](int t) {
+    // ---- cooperative loads: thread owns CH 16-byte chunks of K and of V per tile.  Rows past the live
+    // range are clamped to the last live row (their scores are masked, so only finite values ever meet a
+    // zero probability); tile indices past this workgroup's range are clamped too, so the number of loads
+    // issued never depends on control flow and prefetches stay in flight across iterations.
+    u32x4 kreg[PFD][NLD], vreg[PFD][NLD];
+    const int ld_row = tid / (D / 8), ld_col = tid % (D / 8);
+    auto load_step = [&](int i, u32x4(&kr)[NLD], u32x4(&vr)[NLD]) {
 #pragma unroll
-        for (int i = 0; i < CH; i++) {
-            int chunk = i * 64 + lane;
-            int row = chunk / (D / 8), col = chunk % (D / 8);
-            int key = t * 32 + row;
-            if (key < kv_len) {
-                kreg[i] = *reinterpret_cast<const uint4 *>(kbase + (int64_t)key * D + col * 8);
-                vreg[i] = *reinterpret_cast<const uint4 *>(vbase + (int64_t)key * D + col * 8);
-            } else {
-                kreg[i] = make_uint4(0, 0, 0, 0);
-                vreg[i] = make_uint4(0, 0, 0, 0);
+        for (int kt = 0; kt < KT; kt++) {
+            const int t = min(t_begin + i * KT + kt, t_end - 1);
+#pragma unroll
+            for (int j = 0; j < CH; j++) {
+                const int key = min(t * 32 + ld_row + j * (2048 / D), kv_len - 1);
+                kr[kt * CH + j] = *reinterpret_cast<const u32x4 *>(kbase + (int64_t)key * D + ld_col * 8);
+                vr[kt * CH + j] = *reinterpret_cast<const u32x4 *>(vbase + (int64_t)key * D + ld_col * 8);
             }
         }
     };
-    uint16_t *wk = lds + wave * G::WAVE_ELEMS;
-    uint16_t *wv = wk + 32 * KSTR;
-    auto store_tile = [&]() {
+    if (n_my > 0) {
 #pragma unroll
-        for (int i = 0; i < CH; i++) {
-            int chunk = i * 64 + lane;
-            int row = chunk / (D / 8), col = chunk % (D / 8);
-            *reinterpret_cast<uint4 *>(wk + row * KSTR + col * 8) = kreg[i];
-            *reinterpret_cast<uint4 *>(wv + row * VSTR + col * 8) = vreg[i];
-        }
-    };
-    int t = t_begin + wave;
-    if (t < t_end)
-        load_tile(t);
+        for (int pf = 0; pf < PFD; pf++)
+            load_step(pf, kreg[pf], vreg[pf]);
+    }
 
-    __syncthreads();   // parents staged
-
-    // per query tile: which (head, row) this lane's column is, its mask, its Q fragments
+    // ---- this wave's queries: fragments, owning rows, masks
     bf16x8 qf[QG][NKS];
-    uint64_t qmask[QG];
-    int q_row[QG], q_head[QG];
-    const int n_qtiles = a.group * a.tiles_per_head;
+    int q_node_of[QG];
+    bool q_valid[QG];
+    bool wave_active = false;
 #pragma unroll
     for (int qt = 0; qt < QG; qt++) {
-        int tq = qg * QG + qt;
-        int hh = tq / a.tiles_per_head, nt = tq % a.tiles_per_head;
-        int row = nt * 16 + c;
-        bool valid = tq < n_qtiles && row < a.n_q;
-        q_row[qt] = valid ? row : -1;
-        q_head[qt] = kvh * a.group + hh;
-        qmask[qt] = 0;
-        if (valid) {
-            int node = a.q_node ? a.q_node[(int64_t)b * a.n_q + row] : row;
-            qmask[qt] = visible_nodes(a, b, node, lds_parent);
-            const uint16_t *qp = reinterpret_cast<const uint16_t *>(a.q) +
-                                 (((int64_t)b * a.n_q + row) * a.n_q_heads + q_head[qt]) * D + g * 8;
+        RowOwner ro = row_owner(a, kvh, qg, wave, QG, qt, c);
+        q_valid[qt] = ro.row >= 0;
+        wave_active = wave_active || q_valid[qt];
+        const int row = q_valid[qt] ? ro.row : 0;
+        const int head = q_valid[qt] ? ro.head : kvh * a.group;
+        q_node_of[qt] = a.q_node ? a.q_node[(int64_t)b * a.n_q + row] : row;
+        const uint16_t *qp = reinterpret_cast<const uint16_t *>(a.q) + (((int64_t)b * a.n_q + row) * a.n_q_heads + head) * D + g * 8;
 #pragma unroll
-            for (int ks = 0; ks < NKS; ks++)
-                qf[qt][ks] = *reinterpret_cast<const bf16x8 *>(qp + ks * 32);
-        } else {
+        for (int ks = 0; ks < NKS; ks++)
+            qf[qt][ks] = *reinterpret_cast<const bf16x8 *>(qp + ks * 32);
+    }
+    wave_active = __any(wave_active);
+    if (!a.tree_mask && tid < a.n_tree)
+        lds_parent[tid] = my_parent;
+    TS(2);
+    __syncthreads();   // parents staged
+    TS(3);
+
+    uint64_t qmask[QG];
+#pragma unroll
+    for (int qt = 0; qt < QG; qt++) {
+        qmask[qt] = q_valid[qt] ? visible_nodes(a, b, q_node_of[qt], lds_parent) : 0ull;
+        if (!q_valid[qt]) {
 #pragma unroll
             for (int ks = 0; ks < NKS; ks++)
 #pragma unroll
@@ -227,81 +379,52 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a)
             st.o[qt][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
-    for (; t < t_end; t += 4) {
-        store_tile();
-        wave_lds_fence();
-        if (t + 4 < t_end)
-            load_tile(t + 4);
-        const int key0 = t * 32;
-        const bool needs_mask = key0 + 32 > P;   // tile touches tree rows or the ragged end
-
-        // ---- S^T = K Q^T for 32 keys x (16 * QG) query columns
-        f32x4 sacc[2][QG];
+    // one step of KT tiles: registers -> LDS stage, barrier, refill the register set, compute from LDS
+    auto step = [&](int i, u32x4(&kr)[NLD], u32x4(&vr)[NLD]) {
+        TS(8 + i * 5);
+        uint16_t *stage = lds + (i & 1) * G::STAGE_ELEMS;
+        {
+            uint16_t *dk = stage + ld_row * KSTR + ld_col * 8, *dv = stage + 32 * KSTR + ld_row * VSTR + ld_col * 8;
 #pragma unroll
-        for (int qt = 0; qt < QG; qt++) {
-            sacc[0][qt] = f32x4{0.f, 0.f, 0.f, 0.f};
-            sacc[1][qt] = f32x4{0.f, 0.f, 0.f, 0.f};
-        }
+            for (int kt = 0; kt < KT; kt++) {
 #pragma unroll
-        for (int ks = 0; ks < NKS; ks++) {
-            bf16x8 kf0 = *reinterpret_cast<const bf16x8 *>(wk + c * KSTR + ks * 32 + g * 8);
-            bf16x8 kf1 = *reinterpret_cast<const bf16x8 *>(wk + (16 + c) * KSTR + ks * 32 + g * 8);
-#pragma unroll
-            for (int qt = 0; qt < QG; qt++) {
-                sacc[0][qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf0, qf[qt][ks], sacc[0][qt], 0, 0, 0);
-                sacc[1][qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf1, qf[qt][ks], sacc[1][qt], 0, 0, 0);
-            }
-        }
-        // ---- online softmax; lane owns query column c and key rows g*4+r of both 16-key tiles
-        bf16x8 pf[QG];
-#pragma unroll
-        for (int qt = 0; qt < QG; qt++) {
-            float sv[8];
-            float mx = -INFINITY;
-#pragma unroll
-            for (int i = 0; i < 8; i++) {
-                float x = sacc[i >> 2][qt][i & 3] * a.scale_log2;
-                if (needs_mask) {
-                    int rel = key0 + (i >> 2) * 16 + g * 4 + (i & 3) - P;
-                    bool vis = rel < 0 || (rel < a.n_tree && ((qmask[qt] >> (rel & 63)) & 1ull));
-                    x = vis ? x : -INFINITY;
+                for (int j = 0; j < CH; j++) {
+                    *reinterpret_cast<u32x4 *>(dk + kt * G::TILE_ELEMS + j * (2048 / D) * KSTR) = kr[kt * CH + j];
+                    *reinterpret_cast<u32x4 *>(dv + kt * G::TILE_ELEMS + j * (2048 / D) * VSTR) = vr[kt * CH + j];
                 }
-                sv[i] = x;
-                mx = fmaxf(mx, x);
             }
-            mx = fmaxf(mx, __shfl_xor(mx, 16));
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
-            float m_new = fmaxf(st.m[qt], mx);
-            float m_safe = (m_new == -INFINITY) ? 0.0f : m_new;
-            float alpha = __builtin_amdgcn_exp2f(st.m[qt] - m_safe);
-            st.m[qt] = m_new;
-            float psum = 0.0f;
-#pragma unroll
-            for (int i = 0; i < 8; i++) {
-                float p = __builtin_amdgcn_exp2f(sv[i] - m_safe);
-                psum += p;
-                pf[qt][i] = (__bf16)p;
-            }
-            st.l[qt] = st.l[qt] * alpha + psum;
-#pragma unroll
-            for (int dt = 0; dt < NDT; dt++)
-                st.o[qt][dt] *= alpha;
         }
-        // ---- O^T += V^T P^T
-#pragma unroll
-        for (int dt = 0; dt < NDT; dt++) {
-            const uint16_t *vp = wv + (g * 4 + (c >> 2)) * VSTR + dt * 16 + (c & 3) * 4;
-            s16x4 v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(vp));
-            s16x4 v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(vp + 16 * VSTR));
-            s16x8 vv = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
-            bf16x8 vf = __builtin_bit_cast(bf16x8, vv);
-#pragma unroll
-            for (int qt = 0; qt < QG; qt++)
-                st.o[qt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[qt], st.o[qt][dt], 0, 0, 0);
-        }
-        wave_lds_fence();
-    }
+        __syncthreads();
+        TS(9 + i * 5);
+        load_step(i + PFD, kr, vr);
+        TS(10 + i * 5);
+        if (!wave_active)
+            return;
+        tiles_compute<D, QG, KT>(stage, (t_begin + i * KT) * 32, P, key_end, a.n_tree, a.scale_log2, qf, qmask, st, c, g);
+    };
 
+    // every load issued so far (queries, masks, first tiles) has to land before the loop: the in-order
+    // load counter then only ever counts tile prefetches inside it
+    TS(4);
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+    TS(5);
+    {
+        int i = 0;
+        for (; i + PFD <= n_steps; i += PFD) {
+#pragma unroll
+            for (int pf = 0; pf < PFD; pf++)
+                step(i + pf, kreg[pf], vreg[pf]);
+        }
+        // leftover steps run outside the loop so that its body always issues the same number of loads
+#pragma unroll
+        for (int pf = 0; pf < PFD - 1; pf++)
+            if (i + pf < n_steps)
+                step(i + pf, kreg[pf], vreg[pf]);
+    }
+    if (!wave_active)
+        return;
+
+    if (st.o[0][0][0] != 12345.f) TS(6);
     // the softmax sum was kept per lane over the lane's own key rows: complete it across the 4 row groups
 #pragma unroll
     for (int qt = 0; qt < QG; qt++) {
@@ -310,72 +433,109 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(AttnArgs a)
         l += __shfl_xor(l, 32);
         st.l[qt] = l;
     }
-
-    // ---- merge the 4 waves through LDS, fixed order: (0<-2, 1<-3), then 0<-1
-    float *mbuf = reinterpret_cast<float *>(smem_raw);
-    __syncthreads();
-    if (wave >= 2)
-        state_store<QG, NDT>(st, mbuf + (wave - 2) * G::STATE_FLOATS, lane);
-    __syncthreads();
-    if (wave < 2)
-        state_merge<QG, NDT>(st, mbuf + wave * G::STATE_FLOATS, lane);
-    __syncthreads();
-    if (wave == 1)
-        state_store<QG, NDT>(st, mbuf, lane);
-    __syncthreads();
-    if (wave != 0)
-        return;
-    state_merge<QG, NDT>(st, mbuf, lane);
-
-    // ---- several splits: publish this workgroup's state; the last arrival of the group merges all of them
     if (nsplit > 1) {
+        // several splits: publish this wave's state for attn_merge_kernel
         const int64_t grp = ((int64_t)b * a.n_kv_heads + kvh) * a.n_qg + qg;
-        float *mine = a.part + (grp * nsplit + split) * G::STATE_FLOATS;
-        state_store<QG, NDT>(st, mine, lane);
-        __threadfence();
-        int ticket = 0;
-        if (lane == 0)
-            ticket = atomicAdd(&a.counters[grp], 1);
-        ticket = __shfl(ticket, 0);
-        if (ticket != nsplit - 1)
-            return;
-        __threadfence();
-#pragma unroll
-        for (int qt = 0; qt < QG; qt++) {
-            st.m[qt] = -INFINITY;
-            st.l[qt] = 0.0f;
-#pragma unroll
-            for (int dt = 0; dt < NDT; dt++)
-                st.o[qt][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
-        }
-        for (int s = 0; s < nsplit; s++)
-            state_merge<QG, NDT>(st, a.part + (grp * nsplit + s) * G::STATE_FLOATS, lane);
-        if (lane == 0)
-            a.counters[grp] = 0;   // ready for the next call on this workspace
+        state_store<QG, NDT>(st, a.part + ((grp * nsplit + split) * 4 + wave) * StateGeom<D, QG>::STATE_FLOATS, lane);
+        TS(7);
+        return;
     }
-
-    // ---- normalise and write
     constexpr float LN2 = 0.6931471805599453f;
 #pragma unroll
     for (int qt = 0; qt < QG; qt++) {
-        if (q_row[qt] < 0)
+        RowOwner ro = row_owner(a, kvh, qg, wave, QG, qt, c);
+        if (ro.row < 0)
             continue;
         const float l = st.l[qt];
         const float inv = l > 0.0f ? 1.0f / l : 0.0f;
-        uint16_t *op = reinterpret_cast<uint16_t *>(a.out) +
-                       (((int64_t)b * a.n_q + q_row[qt]) * a.n_q_heads + q_head[qt]) * D + g * 4;
+        uint16_t *op = reinterpret_cast<uint16_t *>(a.out) + (((int64_t)b * a.n_q + ro.row) * a.n_q_heads + ro.head) * D + g * 4;
 #pragma unroll
         for (int dt = 0; dt < NDT; dt++) {
-            bf16x4 o;
+            bf16x4 ob;
 #pragma unroll
             for (int r = 0; r < 4; r++)
-                o[r] = (__bf16)(st.o[qt][dt][r] * inv);
-            *reinterpret_cast<bf16x4 *>(op + dt * 16) = o;
+                ob[r] = (__bf16)(st.o[qt][dt][r] * inv);
+            *reinterpret_cast<bf16x4 *>(op + dt * 16) = ob;
         }
         if (a.lse && g == 0)
-            a.lse[((int64_t)b * a.n_q_heads + q_head[qt]) * a.n_q + q_row[qt]] =
-                l > 0.0f ? (st.m[qt] + log2f(l)) * LN2 : -INFINITY;
+            a.lse[((int64_t)b * a.n_q_heads + ro.head) * a.n_q + ro.row] = l > 0.0f ? (st.m[qt] + log2f(l)) * LN2 : -INFINITY;
     }
+}
+
+// Merge the split states of one (group, wave, query tile) in split order and write the rows.  One
+// workgroup of 4 waves per state; wave w owns the 16-wide output column tiles w, w+4, ...; loads of
+// up to 8 splits are in flight at once.
+template <int D, int QG>
+__global__ __launch_bounds__(256) void attn_merge_kernel(AttnArgs a)
+{
+    constexpr int NDT = D / 16, NDW = NDT / 4;
+    constexpr int STATE = StateGeom<D, QG>::STATE_FLOATS;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int qt = blockIdx.x % QG;
+    const int wave = (blockIdx.x / QG) % 4;
+    const int64_t grp = blockIdx.x / (QG * 4);
+    const int qg = (int)(grp % a.n_qg);
+    const int kvh = (int)((grp / a.n_qg) % a.n_kv_heads), b = (int)(grp / ((int64_t)a.n_qg * a.n_kv_heads));
+    RowOwner ro = row_owner(a, kvh, qg, wave, QG, qt, lane & 15);
+    if (__all(ro.row < 0))
+        return;
+    const int nsplit = a.n_splits;
+    const float *base = a.part + (grp * nsplit * 4 + wave) * STATE;
+    const int64_t stride = (int64_t)4 * STATE;
+    const int ml = QG * NDT * 256 + (qt * 2) * 64 + lane;
+    float m = -INFINITY;
+    for (int s0 = 0; s0 < nsplit; s0 += 8) {
+        float mm[8];
+#pragma unroll
+        for (int j = 0; j < 8; j++)
+            mm[j] = s0 + j < nsplit ? base[(s0 + j) * stride + ml] : -INFINITY;
+#pragma unroll
+        for (int j = 0; j < 8; j++)
+            m = fmaxf(m, mm[j]);
+    }
+    const float ms = (m == -INFINITY) ? 0.0f : m;
+    float l = 0.0f;
+    f32x4 o[NDW];
+#pragma unroll
+    for (int d = 0; d < NDW; d++)
+        o[d] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int s0 = 0; s0 < nsplit; s0 += 8) {
+        float mm[8], ll[8];
+        f32x4 oo[8][NDW];
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+            const bool live = s0 + j < nsplit;
+            const float *src = base + (live ? s0 + j : s0) * stride;
+            mm[j] = live ? src[ml] : -INFINITY;
+            ll[j] = src[ml + 64];
+#pragma unroll
+            for (int d = 0; d < NDW; d++)
+                oo[j][d] = reinterpret_cast<const f32x4 *>(src)[(qt * NDT + w + 4 * d) * 64 + lane];
+        }
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+            const float wgt = __builtin_amdgcn_exp2f(mm[j] - ms);   // 0 for splits past the end
+            l += wgt * ll[j];
+#pragma unroll
+            for (int d = 0; d < NDW; d++)
+                o[d] += oo[j][d] * wgt;
+        }
+    }
+    if (ro.row < 0)
+        return;
+    const int g = lane >> 4;
+    const float inv = l > 0.0f ? 1.0f / l : 0.0f;
+    uint16_t *op = reinterpret_cast<uint16_t *>(a.out) + (((int64_t)b * a.n_q + ro.row) * a.n_q_heads + ro.head) * D + g * 4;
+#pragma unroll
+    for (int d = 0; d < NDW; d++) {
+        bf16x4 ob;
+#pragma unroll
+        for (int r = 0; r < 4; r++)
+            ob[r] = (__bf16)(o[d][r] * inv);
+        *reinterpret_cast<bf16x4 *>(op + (w + 4 * d) * 16) = ob;
+    }
+    if (a.lse && g == 0 && w == 0)
+        a.lse[((int64_t)b * a.n_q_heads + ro.head) * a.n_q + ro.row] = l > 0.0f ? (m + log2f(l)) * 0.6931471805599453f : -INFINITY;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -468,7 +628,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(AttnArgs a, int D)
 // host side
 // ------------------------------------------------------------------------------------------------
 struct Plan {
-    int tiles_per_head, qg, n_qg, n_splits, n_streams, grid;
+    int tiles_per_head, qg, n_qg, n_splits, n_streams, grid, n_groups, kt, pfd;
     size_t state_floats, off_part, total;
 };
 
@@ -478,40 +638,51 @@ int make_plan(const dream_attn_desc *d, int n_q, int64_t max_kv_len, Plan *p)
     p->tiles_per_head = ceil_div(n_q, 16);
     const int n_qtiles = G * p->tiles_per_head;
     const int qg_max = d->head_dim == 256 ? 2 : 4;   // accumulator registers bound the query tiles per wave
-    const int64_t base = (int64_t)d->batch * d->n_kv_heads;
     int qg = q_tiles_override();
-    if (qg <= 0) {
-        // largest query group that still yields at least ~half a chip of workgroups before splitting keys
-        qg = qg_max;
-        while (qg > 1 && base * ceil_div(n_qtiles, qg) < 128)
-            qg >>= 1;
-    }
+    if (qg <= 0)
+        qg = n_qtiles <= 4 ? 1 : n_qtiles <= 8 ? 2 : 4;
     if (qg > qg_max)
         qg = qg_max;
     if (qg != 1 && qg != 2 && qg != 4)
         qg = 1;
-    while (qg > 1 && qg / 2 >= n_qtiles)
-        qg >>= 1;
     p->qg = qg;
-    p->n_qg = ceil_div(n_qtiles, qg);
+    p->n_qg = ceil_div(n_qtiles, 4 * qg);
+    const int64_t base = (int64_t)d->batch * d->n_kv_heads;
     const int tiles = ceil_div(max_kv_len, 32);
     int s = kv_splits_override();
     if (s <= 0)
-        s = ceil_div(256, base * p->n_qg);
-    const int max_split = tiles / 8 > 0 ? tiles / 8 : 1;   // keep at least two 32-key tiles per wave
-    if (s > max_split)
-        s = max_split;
+        s = ceil_div(256, base * p->n_qg);   // one workgroup per CU before anything is split further
+    if (s > tiles)
+        s = tiles;
     if (s < 1)
         s = 1;
     const int64_t groups = base * p->n_qg;
-    if (groups > DREAM_WORKSPACE_HEADER_BYTES / 4)
+    if (groups * qg * 4 > 0x7fffffff)
         s = 1;
     p->n_splits = s;
+    p->n_groups = (int)groups;
     p->n_streams = (int)(base * s);
     p->grid = ceil_div(p->n_streams, 8) * 8 * p->n_qg;
+    // short streams (latency regime): the whole share of a workgroup is one step, everything in flight at once;
+    // long streams: two tiles per step, two steps in flight
+    const int tps = ceil_div(tiles, s);
+    if (qg == 1 && d->head_dim <= 128 && tps <= 4) {
+        p->kt = tps < 2 ? 2 : tps;
+        p->pfd = 1;
+    } else if (qg == 1) {
+        p->kt = 2;
+        p->pfd = 2;
+    } else {
+        p->kt = 1;
+        p->pfd = 2;
+    }
+    if (getenv("DREAM_KT") && qg == 1)
+        p->kt = atoi(getenv("DREAM_KT"));
+    if (getenv("DREAM_PFD") && qg == 1)
+        p->pfd = atoi(getenv("DREAM_PFD"));
     p->state_floats = (size_t)qg * (d->head_dim / 16) * 256 + (size_t)qg * 2 * 64;
     p->off_part = DREAM_WORKSPACE_HEADER_BYTES;
-    p->total = p->off_part + (s > 1 ? (size_t)groups * s * p->state_floats * sizeof(float) : 0);
+    p->total = p->off_part + (s > 1 ? (size_t)groups * s * 4 * p->state_floats * sizeof(float) : 0);
     if (d->dtype == DREAM_F32)
         p->total = DREAM_WORKSPACE_HEADER_BYTES;
     return 0;
@@ -534,19 +705,47 @@ int validate_desc(const dream_attn_desc *d, const char *who)
     return DREAM_OK;
 }
 
-template <int D, int QG>
+template <int D, int QG, int KT, int PFD>
 int launch_bf16(const AttnArgs &a, const Plan &p, hipStream_t st)
 {
-    using G = Geom<D, QG>;
+    using G = Geom<D, QG, KT>;
     static bool attr_set = false;
     if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_kernel<D, QG>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_kernel<D, QG, KT, PFD>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)G::LDS_BYTES) != hipSuccess)
             return fail(DREAM_ERR_HIP, "attention: cannot reserve %zu bytes of LDS", G::LDS_BYTES);
         attr_set = true;
     }
-    hipLaunchKernelGGL((attn_bf16_kernel<D, QG>), dim3(p.grid), dim3(256), G::LDS_BYTES, st, a);
-    return check_launch("attn_bf16_kernel");
+    hipLaunchKernelGGL((attn_bf16_kernel<D, QG, KT, PFD>), dim3(p.grid), dim3(256), G::LDS_BYTES, st, a);
+    int rc = check_launch("attn_bf16_kernel");
+    if (rc || p.n_splits == 1)
+        return rc;
+    hipLaunchKernelGGL((attn_merge_kernel<D, QG>), dim3(p.n_groups * 4 * QG), dim3(256), 0, st, a);
+    return check_launch("attn_merge_kernel");
+}
+
+// query group of one 16-row tile per wave: several tiles per step
+template <int D>
+int launch_bf16_q1(const AttnArgs &a, const Plan &p, hipStream_t st)
+{
+    switch (p.kt * 10 + p.pfd) {
+    case 11: return launch_bf16<D, 1, 1, 1>(a, p, st);
+    case 12: return launch_bf16<D, 1, 1, 2>(a, p, st);
+    case 13: return launch_bf16<D, 1, 1, 3>(a, p, st);
+    case 21: return launch_bf16<D, 1, 2, 1>(a, p, st);
+    case 22: return launch_bf16<D, 1, 2, 2>(a, p, st);
+    default: break;
+    }
+    if constexpr (D <= 128) {
+        switch (p.kt * 10 + p.pfd) {
+        case 23: return launch_bf16<D, 1, 2, 3>(a, p, st);
+        case 31: return launch_bf16<D, 1, 3, 1>(a, p, st);
+        case 41: return launch_bf16<D, 1, 4, 1>(a, p, st);
+        case 42: return launch_bf16<D, 1, 4, 2>(a, p, st);
+        default: break;
+        }
+    }
+    return launch_bf16<D, 1, 1, 2>(a, p, st);
 }
 
 int run_attention(const char *who, const dream_attn_desc *d, const void *q, const void *k, const void *v,
@@ -578,7 +777,6 @@ int run_attention(const char *who, const dream_attn_desc *d, const void *q, cons
     a.q = q; a.k = k; a.v = v;
     a.prefix_len = prefix_len; a.parent = parent; a.q_node = q_node; a.tree_mask = tree_mask;
     a.out = out; a.lse = lse;
-    a.counters = reinterpret_cast<int32_t *>(ws);
     a.part = reinterpret_cast<float *>(static_cast<char *>(ws) + p.off_part);
     a.n_q_heads = d->n_q_heads; a.n_kv_heads = d->n_kv_heads; a.group = d->n_q_heads / d->n_kv_heads;
     a.n_q = n_q; a.n_tree = n_tree; a.include_self = include_self;
@@ -595,14 +793,14 @@ int run_attention(const char *who, const dream_attn_desc *d, const void *q, cons
     }
 
     switch (d->head_dim * 10 + p.qg) {
-    case 641:  return launch_bf16<64, 1>(a, p, st);
-    case 642:  return launch_bf16<64, 2>(a, p, st);
-    case 644:  return launch_bf16<64, 4>(a, p, st);
-    case 1281: return launch_bf16<128, 1>(a, p, st);
-    case 1282: return launch_bf16<128, 2>(a, p, st);
-    case 1284: return launch_bf16<128, 4>(a, p, st);
-    case 2561: return launch_bf16<256, 1>(a, p, st);
-    case 2562: return launch_bf16<256, 2>(a, p, st);
+    case 641:  return launch_bf16_q1<64>(a, p, st);
+    case 642:  return launch_bf16<64, 2, 1, 2>(a, p, st);
+    case 644:  return launch_bf16<64, 4, 1, 2>(a, p, st);
+    case 1281: return launch_bf16_q1<128>(a, p, st);
+    case 1282: return launch_bf16<128, 2, 1, 2>(a, p, st);
+    case 1284: return launch_bf16<128, 4, 1, 2>(a, p, st);
+    case 2561: return launch_bf16_q1<256>(a, p, st);
+    case 2562: return launch_bf16<256, 2, 1, 2>(a, p, st);
     default:   return fail(DREAM_ERR_UNSUPPORTED, "%s: no kernel for head_dim %d with %d query tiles per wave", who, d->head_dim, p.qg);
     }
 }
@@ -620,6 +818,20 @@ size_t workspace_for(const dream_attn_desc *d, int n_q, int64_t max_kv_len)
 }  // namespace
 
 extern "C" {
+
+#ifdef DREAM_TIMESTAMPS
+unsigned long long *dream_debug_ts(void)
+{
+    static unsigned long long *buf = nullptr;
+    if (!buf) {
+        (void)hipHostMalloc(reinterpret_cast<void **>(&buf), 4 * 64 * 8, 0);
+        for (int i = 0; i < 256; i++)
+            buf[i] = 0;
+        (void)hipMemcpyToSymbol(HIP_SYMBOL(g_dev_ts), &buf, sizeof(buf));
+    }
+    return buf;
+}
+#endif
 
 size_t dream_tree_verify_attn_workspace(const dream_attn_desc *desc, int32_t n_tree, int64_t max_kv_len)
 {
