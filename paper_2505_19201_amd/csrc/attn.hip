@@ -462,6 +462,169 @@ __global__ __launch_bounds__(256, (QG == 1 && D <= 128) ? DREAM_Q1_WAVES : 1) vo
     }
 }
 
+// s <- s (+) state at src, the associative merge of two online-softmax states
+template <int QG, int NDT>
+__device__ __forceinline__ void state_merge(WaveState<QG, NDT> &s, const float *src, int lane)
+{
+#pragma unroll
+    for (int qt = 0; qt < QG; qt++) {
+        float mo = src[QG * NDT * 256 + (qt * 2) * 64 + lane];
+        float lo = src[QG * NDT * 256 + (qt * 2 + 1) * 64 + lane];
+        float mn = fmaxf(s.m[qt], mo);
+        float ms = (mn == -INFINITY) ? 0.0f : mn;
+        float a1 = __builtin_amdgcn_exp2f(s.m[qt] - ms), a2 = __builtin_amdgcn_exp2f(mo - ms);
+        s.l[qt] = s.l[qt] * a1 + lo * a2;
+        s.m[qt] = mn;
+#pragma unroll
+        for (int dt = 0; dt < NDT; dt++) {
+            f32x4 oo = reinterpret_cast<const f32x4 *>(src)[(qt * NDT + dt) * 64 + lane];
+            s.o[qt][dt] = s.o[qt][dt] * a1 + oo * a2;
+        }
+    }
+}
+
+// LDS traffic inside one wave needs no barrier, only program order.
+__device__ __forceinline__ void wave_lds_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Short streams with few query tiles (one sequence, MHA): a workgroup serves ONE 16-row query tile of one
+// head over the whole key range, its 4 waves stream disjoint 32-key tiles (each through a private LDS
+// area, no workgroup barrier in the loop) and merge their states through LDS at the end, in a fixed
+// order.  No key split, so no second launch; the query tiles of a head re-read its K/V through the L2 of
+// one XCD.  a.n_qg holds the number of query tiles per KV head here.
+template <int D>
+__global__ __launch_bounds__(256) void attn_wave_kernel(AttnArgs a)
+{
+    using G = Geom<D, 1, 1>;
+    constexpr int KSTR = G::KSTR, VSTR = G::VSTR, NDT = G::NDT, NKS = G::NKS;
+    constexpr int CH = 32 * D / 8 / 64;   // 16-byte chunks per lane per tensor per tile
+    constexpr int STATE = StateGeom<D, 1>::STATE_FLOATS;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    uint16_t *lds = reinterpret_cast<uint16_t *>(smem_raw);
+    int32_t *lds_parent = reinterpret_cast<int32_t *>(smem_raw + (size_t)4 * G::TILE_ELEMS * 2);
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int c = lane & 15, g = lane >> 4;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int stream = (slot / a.n_qg) * 8 + xcd, tq = slot % a.n_qg;
+    if (stream >= a.n_streams)
+        return;
+    const int kvh = stream % a.n_kv_heads, b = stream / a.n_kv_heads;
+
+    int32_t my_parent = -1;
+    if (!a.tree_mask && tid < a.n_tree)
+        my_parent = a.parent[(int64_t)b * a.n_tree + tid];
+    const int P = a.prefix_len[b];
+    const int kv_len = P + a.n_tree;
+    const int t_end = (kv_len + 31) / 32;
+    const uint16_t *kbase = reinterpret_cast<const uint16_t *>(a.k) + ((int64_t)b * a.n_kv_heads + kvh) * a.s_max * D;
+    const uint16_t *vbase = reinterpret_cast<const uint16_t *>(a.v) + ((int64_t)b * a.n_kv_heads + kvh) * a.s_max * D;
+
+    u32x4 kreg[CH], vreg[CH];
+    const int ld_row = lane / (D / 8), ld_col = lane % (D / 8);
+    auto load_tile = [&](int t) {
+        t = min(t, t_end - 1);
+#pragma unroll
+        for (int j = 0; j < CH; j++) {
+            const int key = min(t * 32 + ld_row + j * (512 / D), kv_len - 1);
+            kreg[j] = *reinterpret_cast<const u32x4 *>(kbase + (int64_t)key * D + ld_col * 8);
+            vreg[j] = *reinterpret_cast<const u32x4 *>(vbase + (int64_t)key * D + ld_col * 8);
+        }
+    };
+    int t = wave;
+    const bool has_work = t < t_end;
+    if (has_work)
+        load_tile(t);
+
+    // the query tile: head hh of the group, rows nt*16 .. nt*16+15
+    const int hh = tq / a.tiles_per_head, nt = tq % a.tiles_per_head;
+    const int row = nt * 16 + c, head = kvh * a.group + hh;
+    const bool valid = row < a.n_q;
+    bf16x8 qf[1][NKS];
+    const int rr = valid ? row : 0;
+    const int node = a.q_node ? a.q_node[(int64_t)b * a.n_q + rr] : rr;
+    {
+        const uint16_t *qp = reinterpret_cast<const uint16_t *>(a.q) + (((int64_t)b * a.n_q + rr) * a.n_q_heads + head) * D + g * 8;
+#pragma unroll
+        for (int ks = 0; ks < NKS; ks++)
+            qf[0][ks] = *reinterpret_cast<const bf16x8 *>(qp + ks * 32);
+    }
+    if (!a.tree_mask && tid < a.n_tree)
+        lds_parent[tid] = my_parent;
+    __syncthreads();
+    uint64_t qmask[1];
+    qmask[0] = valid ? visible_nodes(a, b, node, lds_parent) : 0ull;
+    if (!valid) {
+#pragma unroll
+        for (int ks = 0; ks < NKS; ks++)
+#pragma unroll
+            for (int i = 0; i < 8; i++)
+                qf[0][ks][i] = (__bf16)0.0f;
+    }
+    WaveState<1, NDT> st;
+    st.m[0] = -INFINITY;
+    st.l[0] = 0.0f;
+#pragma unroll
+    for (int dt = 0; dt < NDT; dt++)
+        st.o[0][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    uint16_t *wt = lds + wave * G::TILE_ELEMS;
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): only tile prefetches are counted inside the loop
+    if (has_work) {
+        for (; t < t_end; t += 4) {
+            uint16_t *dk = wt + ld_row * KSTR + ld_col * 8, *dv = wt + 32 * KSTR + ld_row * VSTR + ld_col * 8;
+#pragma unroll
+            for (int j = 0; j < CH; j++) {
+                *reinterpret_cast<u32x4 *>(dk + j * (512 / D) * KSTR) = kreg[j];
+                *reinterpret_cast<u32x4 *>(dv + j * (512 / D) * VSTR) = vreg[j];
+            }
+            wave_lds_fence();
+            load_tile(t + 4);
+            tiles_compute<D, 1, 1>(wt, t * 32, P, kv_len, a.n_tree, a.scale_log2, qf, qmask, st, c, g);
+            wave_lds_fence();
+        }
+    }
+    {
+        float l = st.l[0];
+        l += __shfl_xor(l, 16);
+        l += __shfl_xor(l, 32);
+        st.l[0] = l;
+    }
+    // merge the 4 waves through LDS, fixed order: (0<-2, 1<-3), then 0<-1
+    float *mbuf = reinterpret_cast<float *>(smem_raw);
+    __syncthreads();
+    if (wave >= 2)
+        state_store<1, NDT>(st, mbuf + (wave - 2) * STATE, lane);
+    __syncthreads();
+    if (wave < 2)
+        state_merge<1, NDT>(st, mbuf + wave * STATE, lane);
+    __syncthreads();
+    if (wave == 1)
+        state_store<1, NDT>(st, mbuf, lane);
+    __syncthreads();
+    if (wave != 0 || !valid)
+        return;
+    state_merge<1, NDT>(st, mbuf, lane);
+    const float l = st.l[0];
+    const float inv = l > 0.0f ? 1.0f / l : 0.0f;
+    uint16_t *op = reinterpret_cast<uint16_t *>(a.out) + (((int64_t)b * a.n_q + row) * a.n_q_heads + head) * D + g * 4;
+#pragma unroll
+    for (int dt = 0; dt < NDT; dt++) {
+        bf16x4 ob;
+#pragma unroll
+        for (int r = 0; r < 4; r++)
+            ob[r] = (__bf16)(st.o[0][dt][r] * inv);
+        *reinterpret_cast<bf16x4 *>(op + dt * 16) = ob;
+    }
+    if (a.lse && g == 0)
+        a.lse[((int64_t)b * a.n_q_heads + head) * a.n_q + row] = l > 0.0f ? (st.m[0] + log2f(l)) * 0.6931471805599453f : -INFINITY;
+}
+
 // Merge the split states of one (group, wave, query tile) in split order and write the rows.  One
 // workgroup of 4 waves per state; wave w owns the 16-wide output column tiles w, w+4, ...; loads of
 // up to 8 splits are in flight at once.
@@ -629,6 +792,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(AttnArgs a, int D)
 // ------------------------------------------------------------------------------------------------
 struct Plan {
     int tiles_per_head, qg, n_qg, n_splits, n_streams, grid, n_groups, kt, pfd;
+    bool wave_mode;   // one query tile per workgroup, waves split the keys, no key split (attn_wave_kernel)
     size_t state_floats, off_part, total;
 };
 
@@ -649,6 +813,24 @@ int make_plan(const dream_attn_desc *d, int n_q, int64_t max_kv_len, Plan *p)
     p->n_qg = ceil_div(n_qtiles, 4 * qg);
     const int64_t base = (int64_t)d->batch * d->n_kv_heads;
     const int tiles = ceil_div(max_kv_len, 32);
+    // few, short streams with at most 4 query tiles each: a workgroup per query tile fills half the chip
+    // without splitting keys, which saves the merge launch
+    p->wave_mode = q_tiles_override() == 0 && kv_splits_override() == 0 && !getenv("DREAM_NO_WAVE_MODE") &&
+                   d->dtype == DREAM_BF16 && n_qtiles <= 4 && base * n_qtiles <= 256 && base * n_qtiles >= 64 && tiles <= 64;
+    if (p->wave_mode) {
+        p->qg = 1;
+        p->n_qg = n_qtiles;
+        p->n_splits = 1;
+        p->n_groups = (int)base;
+        p->n_streams = (int)base;
+        p->grid = ceil_div(p->n_streams, 8) * 8 * n_qtiles;
+        p->kt = 1;
+        p->pfd = 1;
+        p->state_floats = 0;
+        p->off_part = DREAM_WORKSPACE_HEADER_BYTES;
+        p->total = DREAM_WORKSPACE_HEADER_BYTES;
+        return 0;
+    }
     int s = kv_splits_override();
     if (s <= 0)
         s = ceil_div(256, base * p->n_qg);   // one workgroup per CU before anything is split further
@@ -724,6 +906,24 @@ int launch_bf16(const AttnArgs &a, const Plan &p, hipStream_t st)
     return check_launch("attn_merge_kernel");
 }
 
+template <int D>
+int launch_wave(const AttnArgs &a, const Plan &p, hipStream_t st)
+{
+    using G = Geom<D, 1, 1>;
+    constexpr size_t tile_bytes = (size_t)4 * G::TILE_ELEMS * 2, merge_bytes = (size_t)2 * StateGeom<D, 1>::STATE_FLOATS * 4;
+    constexpr size_t lds_bytes = (tile_bytes > merge_bytes ? tile_bytes : merge_bytes) + DREAM_MAX_TREE * sizeof(int32_t);
+    static_assert(merge_bytes <= tile_bytes, "the wave merge buffers reuse the tile area");
+    static bool attr_set = false;
+    if (!attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_wave_kernel<D>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds_bytes) != hipSuccess)
+            return fail(DREAM_ERR_HIP, "attention: cannot reserve %zu bytes of LDS", lds_bytes);
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((attn_wave_kernel<D>), dim3(p.grid), dim3(256), lds_bytes, st, a);
+    return check_launch("attn_wave_kernel");
+}
+
 // query group of one 16-row tile per wave: several tiles per step
 template <int D>
 int launch_bf16_q1(const AttnArgs &a, const Plan &p, hipStream_t st)
@@ -792,6 +992,13 @@ int run_attention(const char *who, const dream_attn_desc *d, const void *q, cons
         return check_launch("attn_f32_kernel");
     }
 
+    if (p.wave_mode) {
+        switch (d->head_dim) {
+        case 64:  return launch_wave<64>(a, p, st);
+        case 128: return launch_wave<128>(a, p, st);
+        default:  return launch_wave<256>(a, p, st);
+        }
+    }
     switch (d->head_dim * 10 + p.qg) {
     case 641:  return launch_bf16_q1<64>(a, p, st);
     case 642:  return launch_bf16<64, 2, 1, 2>(a, p, st);
