@@ -60,6 +60,8 @@ def main() -> int:
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--splits", type=int, default=0, help="force the number of key-range splits (0 = automatic)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run plain device copies of a known size (reference for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); --gpus must be 1", file=sys.stderr)
@@ -73,6 +75,8 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     dream.load()
+    if args.copy_calibration:
+        return copy_calibration(torch)
     cfg = di.CONFIGS[args.config]
     L = args.layers or cfg.n_layers
     dev = torch.device("cuda:0")
@@ -206,10 +210,65 @@ def main() -> int:
         "roofline": roofline,
     }
 
+    out["streaming_regime"] = streaming_regime(torch, dream, di, cfg)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(cfg, L, tokens_per_step)
     print(json.dumps(out))
     return 0
+
+
+def copy_calibration(torch):
+    """Plain device-to-device copies of 256 MiB: each launch reads 256 MiB and writes 256 MiB, which is what
+    rocprofv3's FETCH_SIZE / WRITE_SIZE should report for it; the ratio scales the counters of other kernels."""
+    n = 256 << 20
+    src = torch.empty(n, dtype=torch.uint8, device="cuda")
+    src.random_(0, 255)
+    dst = torch.empty_like(src)
+    for _ in range(5):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    print(json.dumps({"copy_calibration": True, "bytes_read_per_launch": n, "bytes_written_per_launch": n, "launches": 5}))
+    return 0
+
+
+def streaming_regime(torch, dream, di, cfg, batch=32, iters=20):
+    """The same verification kernel on the same shape with `batch` sequences per launch: one launch then
+    moves hundreds of MB, so its duration measures streaming efficiency rather than launch latency.
+    Two cache sets are alternated so that nothing is served from the last-level cache."""
+    big = cfg.with_batch(batch) if cfg.batch < batch else cfg
+    B, T, Hq, Hkv, D, P = big.batch, big.n_tree, big.n_q_heads, big.n_kv_heads, big.head_dim, big.prefix
+    S = P + T
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(big.seed + 77)
+    rn = lambda *s: torch.randn(*s, generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)  # noqa: E731
+    import numpy as np
+    parent = dream.to_device(np.stack([di.config_tree(big, b) for b in range(B)]))
+    pl = torch.full((B,), P, dtype=torch.int32, device=dev)
+    sets = [(rn(B, T, Hq, D), rn(B, Hkv, S, D), rn(B, Hkv, S, D)) for _ in range(2)]
+    out = torch.empty(B, T, Hq, D, dtype=torch.bfloat16, device=dev)
+    desc = dream.attn_desc(B, Hq, Hkv, D, dream.BF16, S)
+    ws = dream.alloc_workspace(dream.dream_tree_verify_attn_workspace(desc, T, S))
+
+    def run(i):
+        q, k, v = sets[i & 1]
+        dream.dream_tree_verify_attn(desc, q, k, v, pl, T, parent, None, S, out, None, ws)
+
+    for i in range(4):
+        run(i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(iters):
+        run(i)
+    e1.record()
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / iters
+    nbytes = verify_bytes_per_launch(big)
+    gbs = nbytes / us / 1e3
+    return {"workload": f"{big.name}: same shape, {B} sequences per launch", "bytes_per_launch": nbytes,
+            "launch_us": round(us, 2), "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": round(gbs / HBM_PEAK_GBS, 4)}
 
 
 def cpu_baseline(cfg, L, tokens_per_step):

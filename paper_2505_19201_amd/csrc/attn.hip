@@ -29,8 +29,6 @@
 // sequence), used for float32 tensors (the small correctness configuration).
 #include "common.h"
 #include <math.h>
-#include <stdlib.h>
-#include <string.h>
 
 using namespace dream;
 
@@ -802,20 +800,28 @@ int make_plan(const dream_attn_desc *d, int n_q, int64_t max_kv_len, Plan *p)
     p->tiles_per_head = ceil_div(n_q, 16);
     const int n_qtiles = G * p->tiles_per_head;
     const int qg_max = d->head_dim == 256 ? 2 : 4;   // accumulator registers bound the query tiles per wave
+    const int64_t base = (int64_t)d->batch * d->n_kv_heads;
+    const int tiles = ceil_div(max_kv_len, 32);
+    // throughput regime: as many query tiles per wave as registers allow, so that a K/V byte read from
+    // LDS serves the most rows.  Latency regime (too few streams to fill the chip): one tile per wave keeps
+    // the per-workgroup state small; the query groups of a KV head then re-read its K/V through L2.
     int qg = q_tiles_override();
-    if (qg <= 0)
+    if (qg <= 0) {
         qg = n_qtiles <= 4 ? 1 : n_qtiles <= 8 ? 2 : 4;
+        if (qg > qg_max)
+            qg = qg_max;
+        if (base * ceil_div(n_qtiles, 4 * qg) < 256)
+            qg = 1;
+    }
     if (qg > qg_max)
         qg = qg_max;
     if (qg != 1 && qg != 2 && qg != 4)
         qg = 1;
     p->qg = qg;
     p->n_qg = ceil_div(n_qtiles, 4 * qg);
-    const int64_t base = (int64_t)d->batch * d->n_kv_heads;
-    const int tiles = ceil_div(max_kv_len, 32);
     // few, short streams with at most 4 query tiles each: a workgroup per query tile fills half the chip
     // without splitting keys, which saves the merge launch
-    p->wave_mode = q_tiles_override() == 0 && kv_splits_override() == 0 && !getenv("DREAM_NO_WAVE_MODE") &&
+    p->wave_mode = q_tiles_override() == 0 && kv_splits_override() == 0 &&
                    d->dtype == DREAM_BF16 && n_qtiles <= 4 && base * n_qtiles <= 256 && base * n_qtiles >= 64 && tiles <= 64;
     if (p->wave_mode) {
         p->qg = 1;
@@ -832,8 +838,11 @@ int make_plan(const dream_attn_desc *d, int n_q, int64_t max_kv_len, Plan *p)
         return 0;
     }
     int s = kv_splits_override();
-    if (s <= 0)
+    if (s <= 0) {
         s = ceil_div(256, base * p->n_qg);   // one workgroup per CU before anything is split further
+        if (s > 8)
+            s = 8;                           // more splits cost more in the merge than they save
+    }
     if (s > tiles)
         s = tiles;
     if (s < 1)
@@ -846,22 +855,15 @@ int make_plan(const dream_attn_desc *d, int n_q, int64_t max_kv_len, Plan *p)
     p->n_streams = (int)(base * s);
     p->grid = ceil_div(p->n_streams, 8) * 8 * p->n_qg;
     // short streams (latency regime): the whole share of a workgroup is one step, everything in flight at once;
-    // long streams: two tiles per step, two steps in flight
+    // long streams: one tile per step (two at head_dim 64, whose tiles are half the bytes), two steps in flight
     const int tps = ceil_div(tiles, s);
     if (qg == 1 && d->head_dim <= 128 && tps <= 4) {
         p->kt = tps < 2 ? 2 : tps;
         p->pfd = 1;
-    } else if (qg == 1) {
-        p->kt = 2;
-        p->pfd = 2;
     } else {
-        p->kt = 1;
+        p->kt = (qg == 1 && d->head_dim == 64) ? 2 : 1;
         p->pfd = 2;
     }
-    if (getenv("DREAM_KT") && qg == 1)
-        p->kt = atoi(getenv("DREAM_KT"));
-    if (getenv("DREAM_PFD") && qg == 1)
-        p->pfd = atoi(getenv("DREAM_PFD"));
     p->state_floats = (size_t)qg * (d->head_dim / 16) * 256 + (size_t)qg * 2 * 64;
     p->off_part = DREAM_WORKSPACE_HEADER_BYTES;
     p->total = p->off_part + (s > 1 ? (size_t)groups * s * 4 * p->state_floats * sizeof(float) : 0);
@@ -924,27 +926,21 @@ int launch_wave(const AttnArgs &a, const Plan &p, hipStream_t st)
     return check_launch("attn_wave_kernel");
 }
 
-// query group of one 16-row tile per wave: several tiles per step
+// one 16-row query tile per wave: the plan picks (tiles per step, steps in flight)
 template <int D>
 int launch_bf16_q1(const AttnArgs &a, const Plan &p, hipStream_t st)
 {
-    switch (p.kt * 10 + p.pfd) {
-    case 11: return launch_bf16<D, 1, 1, 1>(a, p, st);
-    case 12: return launch_bf16<D, 1, 1, 2>(a, p, st);
-    case 13: return launch_bf16<D, 1, 1, 3>(a, p, st);
-    case 21: return launch_bf16<D, 1, 2, 1>(a, p, st);
-    case 22: return launch_bf16<D, 1, 2, 2>(a, p, st);
-    default: break;
-    }
     if constexpr (D <= 128) {
-        switch (p.kt * 10 + p.pfd) {
-        case 23: return launch_bf16<D, 1, 2, 3>(a, p, st);
-        case 31: return launch_bf16<D, 1, 3, 1>(a, p, st);
-        case 41: return launch_bf16<D, 1, 4, 1>(a, p, st);
-        case 42: return launch_bf16<D, 1, 4, 2>(a, p, st);
-        default: break;
+        if (p.pfd == 1) {
+            switch (p.kt) {
+            case 2:  return launch_bf16<D, 1, 2, 1>(a, p, st);
+            case 3:  return launch_bf16<D, 1, 3, 1>(a, p, st);
+            default: return launch_bf16<D, 1, 4, 1>(a, p, st);
+            }
         }
     }
+    if constexpr (D == 64)
+        return launch_bf16<D, 1, 2, 2>(a, p, st);
     return launch_bf16<D, 1, 1, 2>(a, p, st);
 }
 
