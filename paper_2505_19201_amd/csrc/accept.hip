@@ -90,7 +90,9 @@ __global__ __launch_bounds__(256) void argmax_partial_kernel(const void *logits,
     }
 }
 
-// One workgroup (64 lanes) per sequence.
+// One wave per sequence.  Every node checks its own root path in parallel (a node is accepted iff every
+// edge above it matches the target's arg-max and it is not deeper than max_depth); the deepest accepted
+// node, lowest index among equals, wins a wave reduction; lane 0 writes its path.
 __global__ __launch_bounds__(64) void accept_walk_kernel(const float *part_val, const int32_t *part_idx, int n_chunks,
                                                          int n_tree, const int32_t *token, const int32_t *parent,
                                                          int max_depth, int32_t *node_argmax, int32_t *accept_len,
@@ -99,8 +101,6 @@ __global__ __launch_bounds__(64) void accept_walk_kernel(const float *part_val, 
     __shared__ int32_t s_am[DREAM_MAX_TREE_ACCEPT];
     __shared__ int32_t s_par[DREAM_MAX_TREE_ACCEPT];
     __shared__ int32_t s_tok[DREAM_MAX_TREE_ACCEPT];
-    __shared__ int16_t s_depth[DREAM_MAX_TREE_ACCEPT];
-    __shared__ uint8_t s_acc[DREAM_MAX_TREE_ACCEPT];
     const int b = blockIdx.x, lane = threadIdx.x;
     for (int i = lane; i < n_tree; i += 64) {
         int64_t row = (int64_t)b * n_tree + i;
@@ -114,26 +114,36 @@ __global__ __launch_bounds__(64) void accept_walk_kernel(const float *part_val, 
         node_argmax[row] = idx;
     }
     __syncthreads();
-    if (lane == 0) {
-        s_depth[0] = 0;
-        s_acc[0] = 1;
-        int best = 0;
-        for (int i = 1; i < n_tree; i++) {
-            int p = s_par[i];
-            int d = s_depth[p] + 1;
-            s_depth[i] = (int16_t)d;
-            uint8_t ok = s_acc[p] && s_tok[i] == s_am[p] && d <= max_depth;
-            s_acc[i] = ok;
-            if (ok && d > s_depth[best])
-                best = i;
+    int best_d = -1, best_i = 0x7fffffff;
+    for (int i = lane; i < n_tree; i += 64) {
+        int d = 0;
+        bool ok = true;
+        for (int a = i; a > 0 && ok; d++) {
+            const int p = s_par[a];
+            ok = s_tok[a] == s_am[p];
+            a = p;
         }
-        accept_len[b] = s_depth[best];
+        if (ok && d <= max_depth && d > best_d) {   // nodes are visited in increasing index: strict '>' keeps the lowest
+            best_d = d;
+            best_i = i;
+        }
+    }
+    for (int off = 32; off > 0; off >>= 1) {
+        const int od = __shfl_xor(best_d, off), oi = __shfl_xor(best_i, off);
+        if (od > best_d || (od == best_d && oi < best_i)) {
+            best_d = od;
+            best_i = oi;
+        }
+    }
+    if (lane == 0) {
+        accept_len[b] = best_d;
         int32_t *path = accept_path + (int64_t)b * (max_depth + 1);
-        for (int t = 0; t <= max_depth; t++)
+        for (int t = best_d + 1; t <= max_depth; t++)
             path[t] = -1;
-        for (int n = best; n >= 0; n = s_par[n])
-            path[s_depth[n]] = n;
-        bonus_token[b] = s_am[best];
+        int d = best_d;
+        for (int n = best_i; n >= 0 && d >= 0; n = s_par[n])
+            path[d--] = n;
+        bonus_token[b] = s_am[best_i];
     }
 }
 

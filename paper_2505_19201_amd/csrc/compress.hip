@@ -4,13 +4,14 @@
 // heads of the last-layer causal attention matrix.  The probabilities need each row's softmax
 // normaliser first, so stage A runs two passes over q k^T (both on v_mfma_f32_16x16x32_bf16, no
 // attention matrix is ever stored):
-//   scores_lse_*     one wave per 16 query rows: log-sum-exp of every causal row;
-//   scores_colsum_*  one wave per 16 visual keys: sum over rows of exp(score - lse), per head.
+//   scores_lse_*     one workgroup per 64 query rows, K streamed through LDS: log-sum-exp of every causal row;
+//   scores_colsum_*  one workgroup per 64 visual keys, query rows streamed through LDS: sum over rows of
+//                    exp(score - lse), per head.
 // Each (sequence, head, key) partial sum is produced by exactly one wave in a fixed order, and the
 // sum over heads is taken in head order by the selection kernel, so scores are reproducible
-// bit for bit.  Stage B ranks every visual token by counting the tokens that beat it under
-// (higher score, then lower index), keeps ranks below k and compacts the survivors in position
-// order; the optional gather copies the surviving rows of a [rows, row_elems] matrix.
+// bit for bit.  Stage B finds the k-th largest score with a radix select, keeps everything above it
+// plus the first ties in position order, and compacts the survivors in position order; the optional
+// gather copies the surviving rows of a [rows, row_elems] matrix.
 #include "common.h"
 
 using namespace dream;
@@ -27,75 +28,105 @@ struct ScoreArgs {
     float scale, scale_log2;
 };
 
+// Pass 1: log-sum-exp of every causal row.  One workgroup per (64 query rows, head, sequence); wave w owns
+// rows w*16..w*16+15.  All 256 threads stream K in 32-key tiles (two tiles ahead in registers, two LDS stages,
+// one barrier per tile); scores are formed transposed (lane = query column), so a lane keeps a private running
+// (max, sum) over its own key rows and the four row groups are combined once at the end.
 template <int D>
 __global__ __launch_bounds__(256) void scores_lse_bf16_kernel(ScoreArgs a)
 {
-    constexpr int NKS = D / 32;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    constexpr int NKS = D / 32, STR = D + 8, CH = 32 * D / 8 / 256;
+    __shared__ __attribute__((aligned(16))) uint16_t lds[2][32 * STR];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = lane & 15, g = lane >> 4;
-    const int row0 = (blockIdx.x * 4 + wave) * 16, h = blockIdx.y, b = blockIdx.z;
-    if (row0 >= a.n_q)
-        return;
+    const int blk = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int kvh = h / (a.n_q_heads / a.n_kv_heads);
-    const int row = row0 + c;
+    const int row = blk * 64 + wave * 16 + c;
     const bool valid = row < a.n_q;
     const int pos = valid ? (a.q_pos ? a.q_pos[(int64_t)b * a.n_q + row] : row) : -1;
-    bf16x8 qf[NKS];
-    const uint16_t *qp = reinterpret_cast<const uint16_t *>(a.q) + (((int64_t)b * a.n_q + (valid ? row : 0)) * a.n_q_heads + h) * D + g * 8;
-#pragma unroll
-    for (int ks = 0; ks < NKS; ks++) {
-        qf[ks] = *reinterpret_cast<const bf16x8 *>(qp + ks * 32);
-        if (!valid)
-#pragma unroll
-            for (int i = 0; i < 8; i++)
-                qf[ks][i] = (__bf16)0.0f;
-    }
-    int lim = pos + 1;
+    // keys this workgroup has to see: without explicit positions, up to its last row
+    const int key_lim = a.q_pos ? a.n_keys : min(min(blk * 64 + 64, a.n_q), a.n_keys);
+    const int n_tiles = (key_lim + 31) / 32;
+    int wave_max_pos = pos;
     for (int off = 32; off > 0; off >>= 1)
-        lim = max(lim, __shfl_xor(lim, off));
-    lim = min(lim, a.n_keys);
-    const uint16_t *kb = reinterpret_cast<const uint16_t *>(a.k) + ((int64_t)b * a.n_kv_heads + kvh) * a.s_max * D + g * 8;
+        wave_max_pos = max(wave_max_pos, __shfl_xor(wave_max_pos, off));
+    wave_max_pos = __builtin_amdgcn_readfirstlane(wave_max_pos);
+
+    const uint16_t *kb = reinterpret_cast<const uint16_t *>(a.k) + ((int64_t)b * a.n_kv_heads + kvh) * a.s_max * D;
+    u32x4 kreg[2][CH];
+    const int ld_row = tid / (D / 8), ld_col = tid % (D / 8);
+    auto load_tile = [&](int t, u32x4(&kr)[CH]) {
+        t = min(t, n_tiles - 1);
+#pragma unroll
+        for (int j = 0; j < CH; j++) {
+            const int key = min(t * 32 + ld_row + j * (2048 / D), a.n_keys - 1);
+            kr[j] = *reinterpret_cast<const u32x4 *>(kb + (int64_t)key * D + ld_col * 8);
+        }
+    };
+    load_tile(0, kreg[0]);
+    load_tile(1, kreg[1]);
+    bf16x8 qf[NKS];
+    {
+        const uint16_t *qp = reinterpret_cast<const uint16_t *>(a.q) + (((int64_t)b * a.n_q + (valid ? row : 0)) * a.n_q_heads + h) * D + g * 8;
+#pragma unroll
+        for (int ks = 0; ks < NKS; ks++)
+            qf[ks] = *reinterpret_cast<const bf16x8 *>(qp + ks * 32);
+    }
     float m = -INFINITY, l = 0.0f;
-    for (int key0 = 0; key0 < lim; key0 += 16) {
-        const int key = key0 + c;
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-        if (key < a.n_keys) {
-            const uint16_t *kp = kb + (int64_t)key * D;
-            bf16x8 kf[NKS];
+    auto step = [&](int t, u32x4(&kr)[CH]) {
+        uint16_t *st = lds[t & 1];
 #pragma unroll
-            for (int ks = 0; ks < NKS; ks++)
-                kf[ks] = *reinterpret_cast<const bf16x8 *>(kp + ks * 32);
+        for (int j = 0; j < CH; j++)
+            *reinterpret_cast<u32x4 *>(st + (ld_row + j * (2048 / D)) * STR + ld_col * 8) = kr[j];
+        __syncthreads();
+        load_tile(t + 2, kr);
+        const int key0 = t * 32;
+        if (key0 > wave_max_pos)
+            return;   // causal: nothing in this tile is visible to this wave's rows
+        bf16x8 kfr[2][NKS];
 #pragma unroll
-            for (int ks = 0; ks < NKS; ks++)
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[ks], qf[ks], acc, 0, 0, 0);
-        } else {
-            bf16x8 z;
-#pragma unroll
-            for (int i = 0; i < 8; i++)
-                z[i] = (__bf16)0.0f;
-#pragma unroll
-            for (int ks = 0; ks < NKS; ks++)
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(z, qf[ks], acc, 0, 0, 0);
+        for (int ks = 0; ks < NKS; ks++) {
+            kfr[0][ks] = *reinterpret_cast<const bf16x8 *>(st + c * STR + ks * 32 + g * 8);
+            kfr[1][ks] = *reinterpret_cast<const bf16x8 *>(st + (16 + c) * STR + ks * 32 + g * 8);
         }
-        float x[4], mx = -INFINITY;
+        f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int r = 0; r < 4; r++) {
-            int kk = key0 + g * 4 + r;
-            x[r] = (kk <= pos && kk < a.n_keys) ? acc[r] * a.scale_log2 : -INFINITY;
-            mx = fmaxf(mx, x[r]);
+        for (int ks = 0; ks < NKS; ks++) {
+            acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kfr[0][ks], qf[ks], acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kfr[1][ks], qf[ks], acc1, 0, 0, 0);
         }
-        float m_new = fmaxf(m, mx);
-        float m_safe = (m_new == -INFINITY) ? 0.0f : m_new;
-        float s = 0.0f;
+        float x[8], mx = -INFINITY;
+        const int lim = min(pos, a.n_keys - 1);
 #pragma unroll
-        for (int r = 0; r < 4; r++)
-            s += __builtin_amdgcn_exp2f(x[r] - m_safe);
-        l = l * __builtin_amdgcn_exp2f(m - m_safe) + s;
+        for (int e = 0; e < 8; e++) {
+            const int kk = key0 + (e >> 2) * 16 + g * 4 + (e & 3);
+            const float v = (e < 4 ? acc0[e & 3] : acc1[e & 3]) * a.scale_log2;
+            x[e] = kk <= lim ? v : -INFINITY;
+            mx = fmaxf(mx, x[e]);
+        }
+        const float m_new = fmaxf(m, mx);
+        const float m_safe = (m_new == -INFINITY) ? 0.0f : m_new;
+        float sum = 0.0f;
+#pragma unroll
+        for (int e = 0; e < 8; e++)
+            sum += __builtin_amdgcn_exp2f(x[e] - m_safe);
+        l = l * __builtin_amdgcn_exp2f(m - m_safe) + sum;
         m = m_new;
+    };
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): only tile prefetches are counted inside the loop
+    {
+        int t = 0;
+        for (; t + 2 <= n_tiles; t += 2) {
+            step(t, kreg[0]);
+            step(t + 1, kreg[1]);
+        }
+        if (t < n_tiles)
+            step(t, kreg[0]);
     }
     float mt = fmaxf(m, __shfl_xor(m, 16));
     mt = fmaxf(mt, __shfl_xor(mt, 32));
-    float ms = (mt == -INFINITY) ? 0.0f : mt;
+    const float ms = (mt == -INFINITY) ? 0.0f : mt;
     float lw = l * __builtin_amdgcn_exp2f(m - ms);
     lw += __shfl_xor(lw, 16);
     lw += __shfl_xor(lw, 32);
@@ -103,61 +134,109 @@ __global__ __launch_bounds__(256) void scores_lse_bf16_kernel(ScoreArgs a)
         a.lse2[((int64_t)b * a.n_q_heads + h) * a.n_q_pad + row] = lw > 0.0f ? mt + log2f(lw) : INFINITY;
 }
 
+// Pass 2: column sums of the probabilities.  One workgroup per (64 visual keys, head, sequence); wave w keeps
+// the K fragments of its 16 keys in registers and all 256 threads stream the query rows (with their
+// log-sum-exp and positions) in 32-row tiles through LDS.  A lane sums its key column over the rows it
+// holds; the four row groups are combined at the end, so every (head, key) sum has one fixed order.
 template <int D>
 __global__ __launch_bounds__(256) void scores_colsum_bf16_kernel(ScoreArgs a)
 {
-    constexpr int NKS = D / 32;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    constexpr int NKS = D / 32, STR = D + 8, CH = 32 * D / 8 / 256;
+    __shared__ __attribute__((aligned(16))) uint16_t lds[2][32 * STR];
+    __shared__ __attribute__((aligned(16))) float lds_lse[2][32];
+    __shared__ __attribute__((aligned(16))) int32_t lds_pos[2][32];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = lane & 15, g = lane >> 4;
     const int vis_end = a.vis_start + a.vis_len;
-    const int j0 = a.vis_start + (blockIdx.x * 4 + wave) * 16, h = blockIdx.y, b = blockIdx.z;
-    if (j0 >= vis_end)
-        return;
+    const int blk0 = a.vis_start + blockIdx.x * 64, h = blockIdx.y, b = blockIdx.z;
     const int kvh = h / (a.n_q_heads / a.n_kv_heads);
+    const int j0 = blk0 + wave * 16;
     const int key = j0 + c;
     const bool kvalid = key < vis_end && key < a.n_keys;
     bf16x8 kf[NKS];
-    const uint16_t *kp = reinterpret_cast<const uint16_t *>(a.k) + (((int64_t)b * a.n_kv_heads + kvh) * a.s_max + (kvalid ? key : 0)) * D + g * 8;
-#pragma unroll
-    for (int ks = 0; ks < NKS; ks++) {
-        kf[ks] = *reinterpret_cast<const bf16x8 *>(kp + ks * 32);
-        if (!kvalid)
-#pragma unroll
-            for (int i = 0; i < 8; i++)
-                kf[ks][i] = (__bf16)0.0f;
-    }
-    const int n_rt = (a.n_q + 15) / 16;
-    const int rt_begin = a.q_pos ? 0 : j0 / 16;   // without explicit positions row r sits at position r: rows below j0 see none of these keys
-    const uint16_t *qb = reinterpret_cast<const uint16_t *>(a.q) + ((int64_t)b * a.n_q * a.n_q_heads + h) * D + g * 8;
-    const float *lrow = a.lse2 + ((int64_t)b * a.n_q_heads + h) * a.n_q_pad;
-    float cs = 0.0f;
-    for (int rt = rt_begin; rt < n_rt; rt++) {
-        const int row_a = rt * 16 + c;
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-        bf16x8 qf[NKS];
-        const uint16_t *qp = qb + (int64_t)(row_a < a.n_q ? row_a : 0) * a.n_q_heads * D;
-#pragma unroll
-        for (int ks = 0; ks < NKS; ks++) {
-            qf[ks] = *reinterpret_cast<const bf16x8 *>(qp + ks * 32);
-            if (row_a >= a.n_q)
-#pragma unroll
-                for (int i = 0; i < 8; i++)
-                    qf[ks][i] = (__bf16)0.0f;
-        }
+    {
+        const uint16_t *kp = reinterpret_cast<const uint16_t *>(a.k) + (((int64_t)b * a.n_kv_heads + kvh) * a.s_max + (kvalid ? key : 0)) * D + g * 8;
 #pragma unroll
         for (int ks = 0; ks < NKS; ks++)
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf[ks], kf[ks], acc, 0, 0, 0);
-        const int rbase = rt * 16 + g * 4;
-        f32x4 L = *reinterpret_cast<const f32x4 *>(lrow + rbase);
+            kf[ks] = *reinterpret_cast<const bf16x8 *>(kp + ks * 32);
+    }
+    // row tiles: without explicit positions row r sits at position r, so rows below the block's first key see nothing
+    const int n_tiles_all = (a.n_q + 31) / 32;
+    const int t_first = a.q_pos ? 0 : min(blk0 / 32, n_tiles_all);
+    const int n_tiles = n_tiles_all - t_first;
+    const uint16_t *qb = reinterpret_cast<const uint16_t *>(a.q) + ((int64_t)b * a.n_q * a.n_q_heads + h) * D;
+    const float *lrow = a.lse2 + ((int64_t)b * a.n_q_heads + h) * a.n_q_pad;
+    u32x4 qreg[2][CH];
+    float lreg[2];
+    int32_t preg[2];
+    const int ld_row = tid / (D / 8), ld_col = tid % (D / 8);
+    auto load_tile = [&](int i, u32x4(&qr)[CH], float &lr, int32_t &pr) {
+        const int t = t_first + min(i, n_tiles - 1);
+#pragma unroll
+        for (int j = 0; j < CH; j++) {
+            const int r = min(t * 32 + ld_row + j * (2048 / D), a.n_q - 1);
+            qr[j] = *reinterpret_cast<const u32x4 *>(qb + (int64_t)r * a.n_q_heads * D + ld_col * 8);
+        }
+        if (tid < 32) {
+            const int r = t * 32 + tid;
+            const bool live = r < a.n_q;
+            lr = live ? lrow[r] : INFINITY;   // +inf makes the probability of a padding row zero
+            pr = live ? (a.q_pos ? a.q_pos[(int64_t)b * a.n_q + r] : r) : -1;
+        }
+    };
+    if (n_tiles > 0) {
+        load_tile(0, qreg[0], lreg[0], preg[0]);
+        load_tile(1, qreg[1], lreg[1], preg[1]);
+    }
+    float cs = 0.0f;
+    auto step = [&](int i, u32x4(&qr)[CH], float &lr, int32_t &pr) {
+        const int sidx = i & 1;
+        uint16_t *st = lds[sidx];
+#pragma unroll
+        for (int j = 0; j < CH; j++)
+            *reinterpret_cast<u32x4 *>(st + (ld_row + j * (2048 / D)) * STR + ld_col * 8) = qr[j];
+        if (tid < 32) {
+            lds_lse[sidx][tid] = lr;
+            lds_pos[sidx][tid] = pr;
+        }
+        __syncthreads();
+        load_tile(i + 2, qr, lr, pr);
+        const int r0 = (t_first + i) * 32;
+        if (!a.q_pos && r0 + 31 < j0)
+            return;   // causal: these rows sit before this wave's keys
+        bf16x8 qfr[2][NKS];
+#pragma unroll
+        for (int ks = 0; ks < NKS; ks++) {
+            qfr[0][ks] = *reinterpret_cast<const bf16x8 *>(st + c * STR + ks * 32 + g * 8);
+            qfr[1][ks] = *reinterpret_cast<const bf16x8 *>(st + (16 + c) * STR + ks * 32 + g * 8);
+        }
+        const f32x4 L0 = *reinterpret_cast<const f32x4 *>(&lds_lse[sidx][g * 4]);
+        const f32x4 L1 = *reinterpret_cast<const f32x4 *>(&lds_lse[sidx][16 + g * 4]);
+        const int32_t *pp = &lds_pos[sidx][g * 4];
+        f32x4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < NKS; ks++) {
+            acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qfr[0][ks], kf[ks], acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qfr[1][ks], kf[ks], acc1, 0, 0, 0);
+        }
 #pragma unroll
         for (int r = 0; r < 4; r++) {
-            int row = rbase + r;
-            if (row < a.n_q) {
-                int pos = a.q_pos ? a.q_pos[(int64_t)b * a.n_q + row] : row;
-                if (key <= pos)
-                    cs += __builtin_amdgcn_exp2f(acc[r] * a.scale_log2 - L[r]);
-            }
+            const float p0 = __builtin_amdgcn_exp2f(acc0[r] * a.scale_log2 - L0[r]);
+            const float p1 = __builtin_amdgcn_exp2f(acc1[r] * a.scale_log2 - L1[r]);
+            cs += key <= pp[r] ? p0 : 0.0f;
+            cs += key <= pp[16 + r] ? p1 : 0.0f;
         }
+    };
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
+    {
+        int i = 0;
+        for (; i + 2 <= n_tiles; i += 2) {
+            step(i, qreg[0], lreg[0], preg[0]);
+            step(i + 1, qreg[1], lreg[1], preg[1]);
+        }
+        if (i < n_tiles)
+            step(i, qreg[0], lreg[0], preg[0]);
     }
     cs += __shfl_xor(cs, 16);
     cs += __shfl_xor(cs, 32);
@@ -239,58 +318,142 @@ __global__ __launch_bounds__(64) void scores_colsum_f32_kernel(ScoreArgs a, int 
 }
 
 // ---- stage B ----------------------------------------------------------------------------------
-// One workgroup of 1024 threads per sequence.  Dynamic LDS: vis_len floats + vis_len bytes + 1024 ints.
+// One workgroup of 1024 threads per sequence; everything lives in LDS.  Scores are mapped to unsigned keys
+// whose order is the order of the floats; the k-th largest key is found by a most-significant-digit radix
+// select (4 passes of 256-bin histograms built with integer LDS atomics, so nothing depends on scheduling).
+// A token is kept iff its key is above the threshold, or equal to it and among the first `need` such tokens
+// in position order (equal scores resolve toward the lower index); survivors are compacted in position order.
+// Dynamic LDS: vis_len keys, then 256 histogram bins, 32 wave totals and 4 control words.
+__device__ __forceinline__ uint32_t order_key(float x)
+{
+    x += 0.0f;   // -0 and +0 are equal scores: give them one key
+    const uint32_t u = __float_as_uint(x);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
 __global__ __launch_bounds__(1024) void topk_keep_kernel(const float *part, int n_heads, const float *scores_in,
                                                          float *scores_out, int vis_start, int vis_len, int k,
                                                          int32_t *kept_idx)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    float *s = reinterpret_cast<float *>(smem_raw);
-    int32_t *cnt = reinterpret_cast<int32_t *>(s + vis_len);
-    uint8_t *keep = reinterpret_cast<uint8_t *>(cnt + 1024);
-    const int b = blockIdx.x, tid = threadIdx.x;
+    uint32_t *key = reinterpret_cast<uint32_t *>(smem_raw);
+    int32_t *hist = reinterpret_cast<int32_t *>(key + vis_len);
+    int32_t *wave_tot = hist + 256;   // [2][16]
+    int32_t *ctl = wave_tot + 32;     // [0] chosen bin, [1] remaining need
+    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     for (int j = tid; j < vis_len; j += 1024) {
         float x;
         if (scores_in) {
             x = scores_in[(int64_t)b * vis_len + j];
         } else {
             x = 0.0f;
-            for (int h = 0; h < n_heads; h++)
-                x += part[((int64_t)b * n_heads + h) * vis_len + j];
+            for (int h0 = 0; h0 < n_heads; h0 += 32) {   // up to 32 loads in flight, added in head order
+                float t32[32];
+#pragma unroll
+                for (int i = 0; i < 32; i++)
+                    t32[i] = h0 + i < n_heads ? part[((int64_t)b * n_heads + h0 + i) * vis_len + j] : 0.0f;
+#pragma unroll
+                for (int i = 0; i < 32; i++)
+                    x += t32[i];
+            }
         }
-        s[j] = x;
         if (scores_out)
             scores_out[(int64_t)b * vis_len + j] = x;
+        key[j] = order_key(x);
     }
-    __syncthreads();
-    for (int j = tid; j < vis_len; j += 1024) {
-        const float x = s[j];
-        int rank = 0;
-        for (int i = 0; i < vis_len; i++) {
-            float y = s[i];
-            rank += (y > x) || (y == x && i < j);
+    if (k <= 0)
+        return;
+    // ---- radix select of the k-th largest key
+    uint32_t prefix = 0, mask = 0;
+    int need = k;
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        if (tid < 256)
+            hist[tid] = 0;
+        __syncthreads();
+        for (int j = tid; j < vis_len; j += 1024) {
+            const uint32_t u = key[j];
+            if ((u & mask) == prefix)
+                atomicAdd(&hist[(u >> shift) & 255u], 1);
         }
-        keep[j] = rank < k;
+        __syncthreads();
+        if (wave == 0) {
+            // lane l owns bins 4l..4l+3; walk down from the top bin until `need` keys are covered
+            int c4[4], tot = 0;
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                c4[i] = hist[4 * lane + i];
+                tot += c4[i];
+            }
+            // suffix scan over lanes: keys in bins owned by higher lanes
+            int incl = tot;
+            for (int off = 1; off < 64; off <<= 1) {
+                int v = __shfl_down(incl, off);
+                if (lane + off < 64)
+                    incl += v;
+            }
+            const int above = incl - tot;
+            if (above < need && need <= above + tot) {
+                int rem = need - above, bin = 4 * lane + 3;
+#pragma unroll
+                for (int i = 3; i >= 0; i--) {
+                    if (rem > 0) {
+                        bin = 4 * lane + i;
+                        if (rem <= c4[i]) {
+                            ctl[0] = bin;
+                            ctl[1] = rem;
+                            rem = 0;
+                        } else {
+                            rem -= c4[i];
+                        }
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        prefix |= (uint32_t)ctl[0] << shift;
+        mask |= 255u << shift;
+        need = ctl[1];
+        __syncthreads();
     }
-    __syncthreads();
-    // ordered compaction: thread t owns the contiguous slice [t*per, (t+1)*per)
+    const uint32_t tau = prefix;   // key of the k-th largest; `need` of the keys equal to it are kept
+    // ---- ordered compaction: thread t owns the contiguous slice [t*per, (t+1)*per)
     const int per = (vis_len + 1023) / 1024;
     const int lo = min(tid * per, vis_len), hi = min(lo + per, vis_len);
-    int mine = 0;
-    for (int j = lo; j < hi; j++)
-        mine += keep[j];
-    cnt[tid] = mine;
-    __syncthreads();
-    for (int off = 1; off < 1024; off <<= 1) {   // inclusive scan
-        int v = tid >= off ? cnt[tid - off] : 0;
-        __syncthreads();
-        cnt[tid] += v;
-        __syncthreads();
+    int gt = 0, eq = 0;
+    for (int j = lo; j < hi; j++) {
+        const uint32_t u = key[j];
+        gt += u > tau;
+        eq += u == tau;
     }
-    int out = cnt[tid] - mine;
-    for (int j = lo; j < hi; j++)
-        if (keep[j])
+    int gi = gt, ei = eq;   // inclusive scans inside the wave
+    for (int off = 1; off < 64; off <<= 1) {
+        int a = __shfl_up(gi, off), c = __shfl_up(ei, off);
+        if (lane >= off) {
+            gi += a;
+            ei += c;
+        }
+    }
+    if (lane == 63) {
+        wave_tot[wave] = gi;
+        wave_tot[16 + wave] = ei;
+    }
+    __syncthreads();
+    int g_before = gi - gt, e_before = ei - eq;
+    for (int w = 0; w < wave; w++) {
+        g_before += wave_tot[w];
+        e_before += wave_tot[16 + w];
+    }
+    int out = g_before + min(e_before, need);
+    for (int j = lo; j < hi; j++) {
+        const uint32_t u = key[j];
+        bool keep = u > tau;
+        if (u == tau) {
+            keep = e_before < need;
+            e_before++;
+        }
+        if (keep)
             kept_idx[(int64_t)b * k + out++] = vis_start + j;
+    }
 }
 
 __global__ __launch_bounds__(256) void gather_rows_kernel(const unsigned char *src, int64_t n_rows_src, int64_t row_bytes,
@@ -420,11 +583,11 @@ int dream_visual_compress(const dream_attn_desc *desc, const void *q, const int3
     if (n_kept_host)
         *n_kept_host = k;
     if (vis_len > 0 && (k > 0 || scores_out)) {
-        size_t lds = (size_t)vis_len * 4 + 1024 * 4 + (size_t)vis_len;
+        size_t lds = (size_t)vis_len * 4 + (256 + 32 + 4) * 4;
         static bool attr_set = false;
         if (!attr_set) {
             if (hipFuncSetAttribute(reinterpret_cast<const void *>(&topk_keep_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    DREAM_MAX_VISUAL * 5 + 4096) != hipSuccess)
+                                    DREAM_MAX_VISUAL * 4 + (256 + 32 + 4) * 4) != hipSuccess)
                 return fail(DREAM_ERR_HIP, "%s: cannot reserve LDS for the selection kernel", who);
             attr_set = true;
         }
