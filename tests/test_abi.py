@@ -61,8 +61,9 @@ def test_host_side_argument_errors(lib):
     assert f(*args(d, n_tree=65)) == -2
     assert f(*args(d, n_tree=0)) == -2
     assert f(*args(d, maxkv=129)) == -1                                           # beyond s_max
-    big = dream.attn_desc(1, 32, 32, 128, dream.BF16, 800)
-    assert f(*args(big, n_tree=60, maxkv=764, wsb=65536)) == -3                    # workspace too small
+    big = dream.attn_desc(1, 32, 8, 128, dream.BF16, 1400)                        # few KV heads: key splits need a workspace
+    assert dream.dream_tree_verify_attn_workspace(big, 60, 1340) > 65536
+    assert f(*args(big, n_tree=60, maxkv=1340, wsb=65536)) == -3                   # workspace too small
     assert "workspace" in dream.dream_last_error()
     g = lib.dream_accept_path
     assert g(one, C.c_int32(1), C.c_int32(1), C.c_int32(2000), C.c_int32(100), one, one, C.c_int32(6), one, one, one, one,
@@ -86,5 +87,10 @@ def test_workspace_sizes_are_monotone(lib):
     d = dream.attn_desc(1, 32, 32, 128, dream.BF16, 800)
     a = dream.dream_tree_verify_attn_workspace(d, 60, 764)
     assert a >= 65536
+    dream.dream_set_kv_splits(4)
+    try:
+        assert dream.dream_tree_verify_attn_workspace(d, 60, 764) > a            # forced splits need room for their states
+    finally:
+        dream.dream_set_kv_splits(0)
     assert dream.dream_accept_path_workspace(1, 60, 32000) >= 65536 + 2 * 60 * 4 * 4
     assert dream.dream_visual_compress_workspace(d, 704, 576) >= 65536 + 32 * 704 * 4 + 32 * 576 * 4
