@@ -117,6 +117,9 @@ __device__ __forceinline__ RowOwner row_owner(const AttnArgs &a, int kvh, int qg
 // The softmax reference of a column is only raised when a score exceeds it by more than this many
 // octaves, so exp2(score - reference) stays below 2^8 and the accumulators are seldom rescaled.
 #define DREAM_SOFTMAX_SLACK 8.0f
+#ifndef DREAM_NW8_TILES
+#define DREAM_NW8_TILES 32
+#endif
 #ifndef DREAM_Q1_WAVES
 #define DREAM_Q1_WAVES 2
 #endif
@@ -490,12 +493,17 @@ __device__ __forceinline__ void wave_lds_fence()
 }
 
 // Short streams with few query tiles (one sequence, MHA): a workgroup serves ONE 16-row query tile of one
-// head over the whole key range, its 4 waves stream disjoint 32-key tiles (each through a private LDS
+// head over the whole key range, its NW waves stream disjoint 32-key tiles (each through a private LDS
 // area, no workgroup barrier in the loop) and merge their states through LDS at the end, in a fixed
 // order.  No key split, so no second launch; the query tiles of a head re-read its K/V through the L2 of
-// one XCD.  a.n_qg holds the number of query tiles per KV head here.
-template <int D>
-__global__ __launch_bounds__(256) void attn_wave_kernel(AttnArgs a)
+// one XCD.  Grid: x = query tile * 8 + XCD slot, y = KV head / 8, z = sequence, so that the workgroups of
+// one K/V stream share an XCD and the index arithmetic needs no division.  a.n_qg holds the number of
+// query tiles per KV head.
+//
+// Each wave keeps one tile in flight in registers: a CU holds about 64 KB of outstanding loads whatever is
+// asked of it, so a second tile in flight per wave only queues behind the first.
+template <int D, int NW>
+__global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a)
 {
     using G = Geom<D, 1, 1>;
     constexpr int KSTR = G::KSTR, VSTR = G::VSTR, NDT = G::NDT, NKS = G::NKS;
@@ -503,16 +511,28 @@ __global__ __launch_bounds__(256) void attn_wave_kernel(AttnArgs a)
     constexpr int STATE = StateGeom<D, 1>::STATE_FLOATS;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     uint16_t *lds = reinterpret_cast<uint16_t *>(smem_raw);
-    int32_t *lds_parent = reinterpret_cast<int32_t *>(smem_raw + (size_t)4 * G::TILE_ELEMS * 2);
+    int32_t *lds_parent = reinterpret_cast<int32_t *>(smem_raw + (size_t)NW * G::TILE_ELEMS * 2);
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = lane & 15, g = lane >> 4;
-    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    const int stream = (slot / a.n_qg) * 8 + xcd, tq = slot % a.n_qg;
-    if (stream >= a.n_streams)
+    const int kvh = blockIdx.y * 8 + (blockIdx.x & 7), tq = blockIdx.x >> 3, b = blockIdx.z;
+    if (kvh >= a.n_kv_heads)
         return;
-    const int kvh = stream % a.n_kv_heads, b = stream / a.n_kv_heads;
+    TS(0);
+    const uint16_t *kbase = reinterpret_cast<const uint16_t *>(a.k) + ((int64_t)b * a.n_kv_heads + kvh) * a.s_max * D;
+    const uint16_t *vbase = reinterpret_cast<const uint16_t *>(a.v) + ((int64_t)b * a.n_kv_heads + kvh) * a.s_max * D;
+
+    u32x4 kr[CH], vr[CH];
+    const int ld_row = lane / (D / 8), ld_col = lane % (D / 8);
+    auto issue = [&](int t, int last_row) {
+#pragma unroll
+        for (int j = 0; j < CH; j++) {
+            const int key = min(t * 32 + ld_row + j * (512 / D), last_row);
+            kr[j] = *reinterpret_cast<const u32x4 *>(kbase + key * D + ld_col * 8);
+            vr[j] = *reinterpret_cast<const u32x4 *>(vbase + key * D + ld_col * 8);
+        }
+    };
 
     int32_t my_parent = -1;
     if (!a.tree_mask && tid < a.n_tree)
@@ -520,27 +540,14 @@ __global__ __launch_bounds__(256) void attn_wave_kernel(AttnArgs a)
     const int P = a.prefix_len[b];
     const int kv_len = P + a.n_tree;
     const int t_end = (kv_len + 31) / 32;
-    const uint16_t *kbase = reinterpret_cast<const uint16_t *>(a.k) + ((int64_t)b * a.n_kv_heads + kvh) * a.s_max * D;
-    const uint16_t *vbase = reinterpret_cast<const uint16_t *>(a.v) + ((int64_t)b * a.n_kv_heads + kvh) * a.s_max * D;
+    const int n = t_end > wave ? (t_end - wave + NW - 1) / NW : 0;   // tiles of this wave: wave, wave + NW, ...
+    if (kv_len > 0) TS(1);
+    issue(min(wave, t_end - 1), kv_len - 1);
+    TS(2);
 
-    u32x4 kreg[CH], vreg[CH];
-    const int ld_row = lane / (D / 8), ld_col = lane % (D / 8);
-    auto load_tile = [&](int t) {
-        t = min(t, t_end - 1);
-#pragma unroll
-        for (int j = 0; j < CH; j++) {
-            const int key = min(t * 32 + ld_row + j * (512 / D), kv_len - 1);
-            kreg[j] = *reinterpret_cast<const u32x4 *>(kbase + (int64_t)key * D + ld_col * 8);
-            vreg[j] = *reinterpret_cast<const u32x4 *>(vbase + (int64_t)key * D + ld_col * 8);
-        }
-    };
-    int t = wave;
-    const bool has_work = t < t_end;
-    if (has_work)
-        load_tile(t);
-
-    // the query tile: head hh of the group, rows nt*16 .. nt*16+15
-    const int hh = tq / a.tiles_per_head, nt = tq % a.tiles_per_head;
+    // the query tile: head hh of the group, rows nt*16 .. nt*16+15 (tq < 4, so no division)
+    const int tph = a.tiles_per_head;
+    const int hh = (tq >= tph) + (tq >= 2 * tph) + (tq >= 3 * tph), nt = tq - hh * tph;
     const int row = nt * 16 + c, head = kvh * a.group + hh;
     const bool valid = row < a.n_q;
     bf16x8 qf[1][NKS];
@@ -555,6 +562,7 @@ __global__ __launch_bounds__(256) void attn_wave_kernel(AttnArgs a)
     if (!a.tree_mask && tid < a.n_tree)
         lds_parent[tid] = my_parent;
     __syncthreads();
+    TS(3);
     uint64_t qmask[1];
     qmask[0] = valid ? visible_nodes(a, b, node, lds_parent) : 0ull;
     if (!valid) {
@@ -570,22 +578,25 @@ __global__ __launch_bounds__(256) void attn_wave_kernel(AttnArgs a)
 #pragma unroll
     for (int dt = 0; dt < NDT; dt++)
         st.o[0][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    TS(4);
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): from here on only tile prefetches are in flight
+    TS(5);
 
     uint16_t *wt = lds + wave * G::TILE_ELEMS;
-    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): only tile prefetches are counted inside the loop
-    if (has_work) {
-        for (; t < t_end; t += 4) {
-            uint16_t *dk = wt + ld_row * KSTR + ld_col * 8, *dv = wt + 32 * KSTR + ld_row * VSTR + ld_col * 8;
+    for (int i = 0; i < n; i++) {
+        const int t = wave + i * NW;
+        uint16_t *dk = wt + ld_row * KSTR + ld_col * 8, *dv = wt + 32 * KSTR + ld_row * VSTR + ld_col * 8;
 #pragma unroll
-            for (int j = 0; j < CH; j++) {
-                *reinterpret_cast<u32x4 *>(dk + j * (512 / D) * KSTR) = kreg[j];
-                *reinterpret_cast<u32x4 *>(dv + j * (512 / D) * VSTR) = vreg[j];
-            }
-            wave_lds_fence();
-            load_tile(t + 4);
-            tiles_compute<D, 1, 1>(wt, t * 32, P, kv_len, a.n_tree, a.scale_log2, qf, qmask, st, c, g);
-            wave_lds_fence();
+        for (int j = 0; j < CH; j++) {
+            *reinterpret_cast<u32x4 *>(dk + j * (512 / D) * KSTR) = kr[j];
+            *reinterpret_cast<u32x4 *>(dv + j * (512 / D) * VSTR) = vr[j];
         }
+        wave_lds_fence();
+        TS(8 + i * 2);
+        issue(min(t + NW, t_end - 1), kv_len - 1);   // unconditional; past the last tile it re-reads that tile
+        tiles_compute<D, 1, 1>(wt, t * 32, P, kv_len, a.n_tree, a.scale_log2, qf, qmask, st, c, g);
+        wave_lds_fence();
+        if (st.l[0] != 12345.f) TS(9 + i * 2);
     }
     {
         float l = st.l[0];
@@ -593,34 +604,49 @@ __global__ __launch_bounds__(256) void attn_wave_kernel(AttnArgs a)
         l += __shfl_xor(l, 32);
         st.l[0] = l;
     }
-    // merge the 4 waves through LDS, fixed order: (0<-2, 1<-3), then 0<-1
+    // merge the waves through LDS (the tile areas are free by then) in one round: every wave parks its
+    // state, then wave w sums the 16-wide output column tiles w, w+NW, ... over the states in wave order
     float *mbuf = reinterpret_cast<float *>(smem_raw);
+    TS(6);
     __syncthreads();
-    if (wave >= 2)
-        state_store<1, NDT>(st, mbuf + (wave - 2) * STATE, lane);
+    state_store<1, NDT>(st, mbuf + wave * STATE, lane);
     __syncthreads();
-    if (wave < 2)
-        state_merge<1, NDT>(st, mbuf + wave * STATE, lane);
-    __syncthreads();
-    if (wave == 1)
-        state_store<1, NDT>(st, mbuf, lane);
-    __syncthreads();
-    if (wave != 0 || !valid)
+    if (!valid)
         return;
-    state_merge<1, NDT>(st, mbuf, lane);
-    const float l = st.l[0];
+    float mj[NW], m = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < NW; j++) {
+        mj[j] = mbuf[j * STATE + NDT * 256 + lane];
+        m = fmaxf(m, mj[j]);
+    }
+    const float ms = (m == -INFINITY) ? 0.0f : m;
+    float l = 0.0f;
+#pragma unroll
+    for (int j = 0; j < NW; j++) {
+        mj[j] = __builtin_amdgcn_exp2f(mj[j] - ms);
+        l += mj[j] * mbuf[j * STATE + NDT * 256 + 64 + lane];
+    }
     const float inv = l > 0.0f ? 1.0f / l : 0.0f;
     uint16_t *op = reinterpret_cast<uint16_t *>(a.out) + (((int64_t)b * a.n_q + row) * a.n_q_heads + head) * D + g * 4;
+    for (int dt = wave; dt < NDT; dt += NW) {
+        f32x4 o = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int dt = 0; dt < NDT; dt++) {
+        for (int j = 0; j < NW; j++)
+            o += reinterpret_cast<const f32x4 *>(mbuf + j * STATE)[dt * 64 + lane] * mj[j];
         bf16x4 ob;
 #pragma unroll
         for (int r = 0; r < 4; r++)
-            ob[r] = (__bf16)(st.o[0][dt][r] * inv);
+            ob[r] = (__bf16)(o[r] * inv);
         *reinterpret_cast<bf16x4 *>(op + dt * 16) = ob;
     }
-    if (a.lse && g == 0)
-        a.lse[((int64_t)b * a.n_q_heads + head) * a.n_q + row] = l > 0.0f ? (st.m[0] + log2f(l)) * 0.6931471805599453f : -INFINITY;
+    if (wave == 0 && a.lse && g == 0)
+        a.lse[((int64_t)b * a.n_q_heads + head) * a.n_q + row] = l > 0.0f ? (m + log2f(l)) * 0.6931471805599453f : -INFINITY;
+#ifdef DREAM_TIMESTAMPS
+    if (wave == 0) {
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        TS(63);
+    }
+#endif
 }
 
 // Merge the split states of one (group, wave, query tile) in split order and write the rows.  One
@@ -791,6 +817,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(AttnArgs a, int D)
 struct Plan {
     int tiles_per_head, qg, n_qg, n_splits, n_streams, grid, n_groups, kt, pfd;
     bool wave_mode;   // one query tile per workgroup, waves split the keys, no key split (attn_wave_kernel)
+    int wave_nw;      // waves per workgroup in that mode
     size_t state_floats, off_part, total;
 };
 
@@ -822,10 +849,14 @@ int make_plan(const dream_attn_desc *d, int n_q, int64_t max_kv_len, Plan *p)
     // few, short streams with at most 4 query tiles each: a workgroup per query tile fills half the chip
     // without splitting keys, which saves the merge launch
     p->wave_mode = q_tiles_override() == 0 && kv_splits_override() == 0 &&
-                   d->dtype == DREAM_BF16 && n_qtiles <= 4 && base * n_qtiles <= 256 && base * n_qtiles >= 64 && tiles <= 64;
+                   d->dtype == DREAM_BF16 && n_qtiles <= 4 && base * n_qtiles <= 256 && base * n_qtiles >= 64 && tiles <= 64 &&
+                   d->s_max * d->head_dim < (1ll << 31);
     if (p->wave_mode) {
         p->qg = 1;
         p->n_qg = n_qtiles;
+        // 8 waves (two per SIMD) once 4 would each stream more than 8 tiles; fewer tiles per wave than
+        // that and the longer merge costs more than the extra loads in flight bring
+        p->wave_nw = (d->head_dim <= 128 && tiles > DREAM_NW8_TILES) ? 8 : 4;
         p->n_splits = 1;
         p->n_groups = (int)base;
         p->n_streams = (int)base;
@@ -908,21 +939,24 @@ int launch_bf16(const AttnArgs &a, const Plan &p, hipStream_t st)
     return check_launch("attn_merge_kernel");
 }
 
-template <int D>
+template <int D, int NW>
 int launch_wave(const AttnArgs &a, const Plan &p, hipStream_t st)
 {
     using G = Geom<D, 1, 1>;
-    constexpr size_t tile_bytes = (size_t)4 * G::TILE_ELEMS * 2, merge_bytes = (size_t)2 * StateGeom<D, 1>::STATE_FLOATS * 4;
+    constexpr size_t tile_bytes = (size_t)NW * G::TILE_ELEMS * 2, merge_bytes = (size_t)NW * StateGeom<D, 1>::STATE_FLOATS * 4;
     constexpr size_t lds_bytes = (tile_bytes > merge_bytes ? tile_bytes : merge_bytes) + DREAM_MAX_TREE * sizeof(int32_t);
     static_assert(merge_bytes <= tile_bytes, "the wave merge buffers reuse the tile area");
     static bool attr_set = false;
     if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_wave_kernel<D>), hipFuncAttributeMaxDynamicSharedMemorySize,
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_wave_kernel<D, NW>), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)lds_bytes) != hipSuccess)
             return fail(DREAM_ERR_HIP, "attention: cannot reserve %zu bytes of LDS", lds_bytes);
         attr_set = true;
     }
-    hipLaunchKernelGGL((attn_wave_kernel<D>), dim3(p.grid), dim3(256), lds_bytes, st, a);
+    if (a.n_qg > 4)
+        return fail(DREAM_ERR_INVALID_ARG, "attention: the wave kernel serves at most 4 query tiles per KV head");
+    const dim3 grid(8 * a.n_qg, ceil_div(a.n_kv_heads, 8), p.n_streams / a.n_kv_heads);
+    hipLaunchKernelGGL((attn_wave_kernel<D, NW>), grid, dim3(64 * NW), lds_bytes, st, a);
     return check_launch("attn_wave_kernel");
 }
 
@@ -990,9 +1024,9 @@ int run_attention(const char *who, const dream_attn_desc *d, const void *q, cons
 
     if (p.wave_mode) {
         switch (d->head_dim) {
-        case 64:  return launch_wave<64>(a, p, st);
-        case 128: return launch_wave<128>(a, p, st);
-        default:  return launch_wave<256>(a, p, st);
+        case 64:  return p.wave_nw == 8 ? launch_wave<64, 8>(a, p, st) : launch_wave<64, 4>(a, p, st);
+        case 128: return p.wave_nw == 8 ? launch_wave<128, 8>(a, p, st) : launch_wave<128, 4>(a, p, st);
+        default:  return launch_wave<256, 4>(a, p, st);
         }
     }
     switch (d->head_dim * 10 + p.qg) {
