@@ -61,13 +61,14 @@ __device__ __forceinline__ uint64_t visible_nodes(const AttnArgs &a, int b, int 
     return m;
 }
 
-template <int D, int QG, int KT>
+// D: head dimension (K rows, Q); DV: V columns handled (D, or a slice of it when the output columns are split)
+template <int D, int QG, int KT, int DV = D>
 struct Geom {
     static constexpr int KSTR = D + 8;    // K row stride in LDS (elements): 16-byte pad, b128 reads spread over all banks
-    static constexpr int VSTR = D + 16;   // V row stride in LDS (elements): 4 consecutive rows land 8 banks apart
+    static constexpr int VSTR = DV + 16;  // V row stride in LDS (elements): 4 consecutive rows land 8 banks apart
     static constexpr int TILE_ELEMS = 32 * (KSTR + VSTR);   // one 32-key K tile followed by its V tile
     static constexpr int STAGE_ELEMS = KT * TILE_ELEMS;     // a step handles KT tiles
-    static constexpr int NDT = D / 16;
+    static constexpr int NDT = DV / 16;
     static constexpr int NKS = D / 32;
     static constexpr int CH = 32 * D / 8 / 256;             // 16-byte chunks per thread per tensor per tile
     static constexpr size_t LDS_BYTES = (size_t)2 * STAGE_ELEMS * 2 + DREAM_MAX_TREE * sizeof(int32_t);
@@ -117,6 +118,12 @@ __device__ __forceinline__ RowOwner row_owner(const AttnArgs &a, int kvh, int qg
 // The softmax reference of a column is only raised when a score exceeds it by more than this many
 // octaves, so exp2(score - reference) stays below 2^8 and the accumulators are seldom rescaled.
 #define DREAM_SOFTMAX_SLACK 8.0f
+#ifndef DREAM_DS_MAX
+#define DREAM_DS_MAX 4
+#endif
+#ifndef DREAM_WAVE_MIN_WGS
+#define DREAM_WAVE_MIN_WGS 32
+#endif
 #ifndef DREAM_NW8_TILES
 #define DREAM_NW8_TILES 32
 #endif
@@ -135,12 +142,12 @@ __device__ unsigned long long *g_dev_ts = nullptr;
 
 // QK^T, online softmax and PV for KT consecutive 32-key tiles held in LDS at `stage` (K tile, then V tile,
 // per 32 keys), for the QG query tiles of this wave.  key0 is the global key index of the first row.
-template <int D, int QG, int KT>
+template <int D, int QG, int KT, int DV = D>
 __device__ __forceinline__ void tiles_compute(const uint16_t *stage, int key0, int P, int key_end, int n_tree, float scale_log2,
                                               const bf16x8 (&qf)[QG][D / 32], const uint64_t (&qmask)[QG],
-                                              WaveState<QG, D / 16> &st, int c, int g)
+                                              WaveState<QG, DV / 16> &st, int c, int g)
 {
-    using G = Geom<D, QG, KT>;
+    using G = Geom<D, QG, KT, DV>;
     constexpr int KSTR = G::KSTR, VSTR = G::VSTR, NDT = G::NDT, NKS = G::NKS;
     const bool needs_mask = key0 + KT * 32 > min(P, key_end);   // step touches tree rows, the ragged end or the next split
 
@@ -172,7 +179,7 @@ __device__ __forceinline__ void tiles_compute(const uint16_t *stage, int key0, i
     __builtin_amdgcn_sched_barrier(0);
     // ---- V^T fragments of the first tile (first half of the head dimension for D = 256) are requested
     // now, so their LDS latency hides behind the softmax arithmetic
-    constexpr int VH = D == 256 ? 2 : 1, NDH = NDT / VH;
+    constexpr int VH = DV == 256 ? 2 : 1, NDH = NDT / VH;
     s16x4 vfr[NDH][2];
     const int v_off = 32 * KSTR + (g * 4 + (c >> 2)) * VSTR + (c & 3) * 4;
     auto read_v = [&](int kt, int h) {
@@ -495,20 +502,24 @@ __device__ __forceinline__ void wave_lds_fence()
 // Short streams with few query tiles (one sequence, MHA): a workgroup serves ONE 16-row query tile of one
 // head over the whole key range, its NW waves stream disjoint 32-key tiles (each through a private LDS
 // area, no workgroup barrier in the loop) and merge their states through LDS at the end, in a fixed
-// order.  No key split, so no second launch; the query tiles of a head re-read its K/V through the L2 of
-// one XCD.  Grid: x = query tile * 8 + XCD slot, y = KV head / 8, z = sequence, so that the workgroups of
-// one K/V stream share an XCD and the index arithmetic needs no division.  a.n_qg holds the number of
-// query tiles per KV head.
+// order.  No key split, so no second launch; the workgroups of a head re-read its K/V through the L2 of
+// one XCD.  With DS > 1 the output columns are split over DS workgroups: each computes all the scores
+// (reads all of K) but only its slice of V and of the output, which multiplies the CUs that pull data when
+// there are few query tiles and needs no merge across workgroups.
+// Grid: x = (query tile * DS + column slice) * 8 + XCD slot, y = KV head / 8, z = sequence, so that the
+// workgroups of one K/V stream share an XCD and the index arithmetic needs no division.  a.n_qg holds
+// the number of query tiles per KV head.
 //
 // Each wave keeps one tile in flight in registers: a CU holds about 64 KB of outstanding loads whatever is
 // asked of it, so a second tile in flight per wave only queues behind the first.
-template <int D, int NW>
+template <int D, int NW, int DS>
 __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a)
 {
-    using G = Geom<D, 1, 1>;
+    constexpr int DV = D / DS;
+    using G = Geom<D, 1, 1, DV>;
     constexpr int KSTR = G::KSTR, VSTR = G::VSTR, NDT = G::NDT, NKS = G::NKS;
-    constexpr int CH = 32 * D / 8 / 64;   // 16-byte chunks per lane per tensor per tile
-    constexpr int STATE = StateGeom<D, 1>::STATE_FLOATS;
+    constexpr int CHK = 32 * D / 8 / 64, CHV = 32 * DV / 8 / 64;   // 16-byte chunks per lane per tile of K, V
+    constexpr int STATE = StateGeom<DV, 1>::STATE_FLOATS;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     uint16_t *lds = reinterpret_cast<uint16_t *>(smem_raw);
     int32_t *lds_parent = reinterpret_cast<int32_t *>(smem_raw + (size_t)NW * G::TILE_ELEMS * 2);
@@ -516,23 +527,13 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = lane & 15, g = lane >> 4;
-    const int kvh = blockIdx.y * 8 + (blockIdx.x & 7), tq = blockIdx.x >> 3, b = blockIdx.z;
+    const int unit = blockIdx.x >> 3;
+    const int kvh = blockIdx.y * 8 + (blockIdx.x & 7), tq = unit / DS, ds = unit % DS, b = blockIdx.z;
     if (kvh >= a.n_kv_heads)
         return;
     TS(0);
     const uint16_t *kbase = reinterpret_cast<const uint16_t *>(a.k) + ((int64_t)b * a.n_kv_heads + kvh) * a.s_max * D;
-    const uint16_t *vbase = reinterpret_cast<const uint16_t *>(a.v) + ((int64_t)b * a.n_kv_heads + kvh) * a.s_max * D;
-
-    u32x4 kr[CH], vr[CH];
-    const int ld_row = lane / (D / 8), ld_col = lane % (D / 8);
-    auto issue = [&](int t, int last_row) {
-#pragma unroll
-        for (int j = 0; j < CH; j++) {
-            const int key = min(t * 32 + ld_row + j * (512 / D), last_row);
-            kr[j] = *reinterpret_cast<const u32x4 *>(kbase + key * D + ld_col * 8);
-            vr[j] = *reinterpret_cast<const u32x4 *>(vbase + key * D + ld_col * 8);
-        }
-    };
+    const uint16_t *vbase = reinterpret_cast<const uint16_t *>(a.v) + ((int64_t)b * a.n_kv_heads + kvh) * a.s_max * D + ds * DV;
 
     int32_t my_parent = -1;
     if (!a.tree_mask && tid < a.n_tree)
@@ -542,7 +543,25 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a)
     const int t_end = (kv_len + 31) / 32;
     const int n = t_end > wave ? (t_end - wave + NW - 1) / NW : 0;   // tiles of this wave: wave, wave + NW, ...
     if (kv_len > 0) TS(1);
-    issue(min(wave, t_end - 1), kv_len - 1);
+
+    u32x4 kr[CHK], vr[CHV];
+    const int k_row = lane / (D / 8), k_col = lane % (D / 8), v_row = lane / (DV / 8), v_col = lane % (DV / 8);
+    // Unconditional (the tile index is clamped), so the number of loads in flight does not depend on
+    // control flow; the prefetch past the last tile re-reads it and is dropped.
+    auto issue = [&](int t) {
+        t = min(t, t_end - 1);
+#pragma unroll
+        for (int j = 0; j < CHK; j++) {
+            const int key = min(t * 32 + k_row + j * (512 / D), kv_len - 1);
+            kr[j] = *reinterpret_cast<const u32x4 *>(kbase + key * D + k_col * 8);
+        }
+#pragma unroll
+        for (int j = 0; j < CHV; j++) {
+            const int key = min(t * 32 + v_row + j * (512 / DV), kv_len - 1);
+            vr[j] = *reinterpret_cast<const u32x4 *>(vbase + key * D + v_col * 8);
+        }
+    };
+    issue(wave);
     TS(2);
 
     // the query tile: head hh of the group, rows nt*16 .. nt*16+15 (tq < 4, so no division)
@@ -585,16 +604,17 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a)
     uint16_t *wt = lds + wave * G::TILE_ELEMS;
     for (int i = 0; i < n; i++) {
         const int t = wave + i * NW;
-        uint16_t *dk = wt + ld_row * KSTR + ld_col * 8, *dv = wt + 32 * KSTR + ld_row * VSTR + ld_col * 8;
+        uint16_t *dk = wt + k_row * KSTR + k_col * 8, *dv = wt + 32 * KSTR + v_row * VSTR + v_col * 8;
 #pragma unroll
-        for (int j = 0; j < CH; j++) {
+        for (int j = 0; j < CHK; j++)
             *reinterpret_cast<u32x4 *>(dk + j * (512 / D) * KSTR) = kr[j];
-            *reinterpret_cast<u32x4 *>(dv + j * (512 / D) * VSTR) = vr[j];
-        }
+#pragma unroll
+        for (int j = 0; j < CHV; j++)
+            *reinterpret_cast<u32x4 *>(dv + j * (512 / DV) * VSTR) = vr[j];
         wave_lds_fence();
         TS(8 + i * 2);
-        issue(min(t + NW, t_end - 1), kv_len - 1);   // unconditional; past the last tile it re-reads that tile
-        tiles_compute<D, 1, 1>(wt, t * 32, P, kv_len, a.n_tree, a.scale_log2, qf, qmask, st, c, g);
+        issue(t + NW);
+        tiles_compute<D, 1, 1, DV>(wt, t * 32, P, kv_len, a.n_tree, a.scale_log2, qf, qmask, st, c, g);
         wave_lds_fence();
         if (st.l[0] != 12345.f) TS(9 + i * 2);
     }
@@ -627,7 +647,7 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a)
         l += mj[j] * mbuf[j * STATE + NDT * 256 + 64 + lane];
     }
     const float inv = l > 0.0f ? 1.0f / l : 0.0f;
-    uint16_t *op = reinterpret_cast<uint16_t *>(a.out) + (((int64_t)b * a.n_q + row) * a.n_q_heads + head) * D + g * 4;
+    uint16_t *op = reinterpret_cast<uint16_t *>(a.out) + (((int64_t)b * a.n_q + row) * a.n_q_heads + head) * D + ds * DV + g * 4;
     for (int dt = wave; dt < NDT; dt += NW) {
         f32x4 o = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -639,7 +659,7 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a)
             ob[r] = (__bf16)(o[r] * inv);
         *reinterpret_cast<bf16x4 *>(op + dt * 16) = ob;
     }
-    if (wave == 0 && a.lse && g == 0)
+    if (wave == 0 && ds == 0 && a.lse && g == 0)
         a.lse[((int64_t)b * a.n_q_heads + head) * a.n_q + row] = l > 0.0f ? (m + log2f(l)) * 0.6931471805599453f : -INFINITY;
 #ifdef DREAM_TIMESTAMPS
     if (wave == 0) {
@@ -818,6 +838,7 @@ struct Plan {
     int tiles_per_head, qg, n_qg, n_splits, n_streams, grid, n_groups, kt, pfd;
     bool wave_mode;   // one query tile per workgroup, waves split the keys, no key split (attn_wave_kernel)
     int wave_nw;      // waves per workgroup in that mode
+    int wave_ds;      // workgroups that share the output columns of a query tile in that mode (1, 2 or 4)
     size_t state_floats, off_part, total;
 };
 
@@ -849,7 +870,7 @@ int make_plan(const dream_attn_desc *d, int n_q, int64_t max_kv_len, Plan *p)
     // few, short streams with at most 4 query tiles each: a workgroup per query tile fills half the chip
     // without splitting keys, which saves the merge launch
     p->wave_mode = q_tiles_override() == 0 && kv_splits_override() == 0 &&
-                   d->dtype == DREAM_BF16 && n_qtiles <= 4 && base * n_qtiles <= 256 && base * n_qtiles >= 64 && tiles <= 64 &&
+                   d->dtype == DREAM_BF16 && n_qtiles <= 4 && base * n_qtiles <= 256 && base * n_qtiles >= DREAM_WAVE_MIN_WGS && tiles <= 64 &&
                    d->s_max * d->head_dim < (1ll << 31);
     if (p->wave_mode) {
         p->qg = 1;
@@ -857,6 +878,10 @@ int make_plan(const dream_attn_desc *d, int n_q, int64_t max_kv_len, Plan *p)
         // 8 waves (two per SIMD) once 4 would each stream more than 8 tiles; fewer tiles per wave than
         // that and the longer merge costs more than the extra loads in flight bring
         p->wave_nw = (d->head_dim <= 128 && tiles > DREAM_NW8_TILES) ? 8 : 4;
+        // half the output columns per workgroup while that still leaves at most one workgroup per CU
+        p->wave_ds = 1;
+        while (p->wave_ds < DREAM_DS_MAX && base * n_qtiles * p->wave_ds * 2 <= 256 && d->head_dim / (p->wave_ds * 2) >= 32)
+            p->wave_ds *= 2;
         p->n_splits = 1;
         p->n_groups = (int)base;
         p->n_streams = (int)base;
@@ -939,25 +964,44 @@ int launch_bf16(const AttnArgs &a, const Plan &p, hipStream_t st)
     return check_launch("attn_merge_kernel");
 }
 
-template <int D, int NW>
+template <int D, int NW, int DS>
 int launch_wave(const AttnArgs &a, const Plan &p, hipStream_t st)
 {
-    using G = Geom<D, 1, 1>;
-    constexpr size_t tile_bytes = (size_t)NW * G::TILE_ELEMS * 2, merge_bytes = (size_t)NW * StateGeom<D, 1>::STATE_FLOATS * 4;
+    using G = Geom<D, 1, 1, D / DS>;
+    constexpr size_t tile_bytes = (size_t)NW * G::TILE_ELEMS * 2, merge_bytes = (size_t)NW * StateGeom<D / DS, 1>::STATE_FLOATS * 4;
     constexpr size_t lds_bytes = (tile_bytes > merge_bytes ? tile_bytes : merge_bytes) + DREAM_MAX_TREE * sizeof(int32_t);
     static_assert(merge_bytes <= tile_bytes, "the wave merge buffers reuse the tile area");
     static bool attr_set = false;
     if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_wave_kernel<D, NW>), hipFuncAttributeMaxDynamicSharedMemorySize,
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_wave_kernel<D, NW, DS>), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)lds_bytes) != hipSuccess)
             return fail(DREAM_ERR_HIP, "attention: cannot reserve %zu bytes of LDS", lds_bytes);
         attr_set = true;
     }
     if (a.n_qg > 4)
         return fail(DREAM_ERR_INVALID_ARG, "attention: the wave kernel serves at most 4 query tiles per KV head");
-    const dim3 grid(8 * a.n_qg, ceil_div(a.n_kv_heads, 8), p.n_streams / a.n_kv_heads);
-    hipLaunchKernelGGL((attn_wave_kernel<D, NW>), grid, dim3(64 * NW), lds_bytes, st, a);
+    const dim3 grid(8 * a.n_qg * DS, ceil_div(a.n_kv_heads, 8), p.n_streams / a.n_kv_heads);
+    hipLaunchKernelGGL((attn_wave_kernel<D, NW, DS>), grid, dim3(64 * NW), lds_bytes, st, a);
     return check_launch("attn_wave_kernel");
+}
+
+template <int D>
+int launch_wave_d(const AttnArgs &a, const Plan &p, hipStream_t st)
+{
+    if constexpr (D <= 128) {
+        if (p.wave_nw == 8) {
+            if constexpr (D >= 128) {
+                if (p.wave_ds == 4)
+                    return launch_wave<D, 8, 4>(a, p, st);
+            }
+            return p.wave_ds == 2 ? launch_wave<D, 8, 2>(a, p, st) : launch_wave<D, 8, 1>(a, p, st);
+        }
+    }
+    if constexpr (D >= 128) {
+        if (p.wave_ds == 4)
+            return launch_wave<D, 4, 4>(a, p, st);
+    }
+    return p.wave_ds == 2 ? launch_wave<D, 4, 2>(a, p, st) : launch_wave<D, 4, 1>(a, p, st);
 }
 
 // one 16-row query tile per wave: the plan picks (tiles per step, steps in flight)
@@ -1024,9 +1068,9 @@ int run_attention(const char *who, const dream_attn_desc *d, const void *q, cons
 
     if (p.wave_mode) {
         switch (d->head_dim) {
-        case 64:  return p.wave_nw == 8 ? launch_wave<64, 8>(a, p, st) : launch_wave<64, 4>(a, p, st);
-        case 128: return p.wave_nw == 8 ? launch_wave<128, 8>(a, p, st) : launch_wave<128, 4>(a, p, st);
-        default:  return launch_wave<256, 4>(a, p, st);
+        case 64:  return launch_wave_d<64>(a, p, st);
+        case 128: return launch_wave_d<128>(a, p, st);
+        default:  return launch_wave_d<256>(a, p, st);
         }
     }
     switch (d->head_dim * 10 + p.qg) {
