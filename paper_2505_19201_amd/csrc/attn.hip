@@ -118,15 +118,6 @@ __device__ __forceinline__ RowOwner row_owner(const AttnArgs &a, int kvh, int qg
 // The softmax reference of a column is only raised when a score exceeds it by more than this many
 // octaves, so exp2(score - reference) stays below 2^8 and the accumulators are seldom rescaled.
 #define DREAM_SOFTMAX_SLACK 8.0f
-#ifndef DREAM_DS_MAX
-#define DREAM_DS_MAX 4
-#endif
-#ifndef DREAM_WAVE_MIN_WGS
-#define DREAM_WAVE_MIN_WGS 32
-#endif
-#ifndef DREAM_NW8_TILES
-#define DREAM_NW8_TILES 32
-#endif
 #ifndef DREAM_Q1_WAVES
 #define DREAM_Q1_WAVES 2
 #endif
@@ -135,7 +126,7 @@ __device__ __forceinline__ RowOwner row_owner(const AttnArgs &a, int kvh, int qg
 // the shader clock at a few points into a host-visible buffer.  Compiled out of the product build.
 #ifdef DREAM_TIMESTAMPS
 __device__ unsigned long long *g_dev_ts = nullptr;
-#define TS(i) do { if (g_dev_ts && blockIdx.x == 8 && lane == 0) g_dev_ts[wave * 64 + (i)] = clock64(); } while (0)
+#define TS(i) do { if (g_dev_ts && blockIdx.x == 8 && blockIdx.y + blockIdx.z == 0 && lane == 0) g_dev_ts[wave * 64 + (i)] = clock64(); } while (0)
 #else
 #define TS(i) do { } while (0)
 #endif
@@ -870,18 +861,17 @@ int make_plan(const dream_attn_desc *d, int n_q, int64_t max_kv_len, Plan *p)
     // few, short streams with at most 4 query tiles each: a workgroup per query tile fills half the chip
     // without splitting keys, which saves the merge launch
     p->wave_mode = q_tiles_override() == 0 && kv_splits_override() == 0 &&
-                   d->dtype == DREAM_BF16 && n_qtiles <= 4 && base * n_qtiles <= 256 && base * n_qtiles >= DREAM_WAVE_MIN_WGS && tiles <= 64 &&
+                   d->dtype == DREAM_BF16 && n_qtiles <= 4 && base * n_qtiles <= 256 && base * n_qtiles >= 32 && tiles <= 64 &&
                    d->s_max * d->head_dim < (1ll << 31);
     if (p->wave_mode) {
         p->qg = 1;
         p->n_qg = n_qtiles;
-        // 8 waves (two per SIMD) once 4 would each stream more than 8 tiles; fewer tiles per wave than
-        // that and the longer merge costs more than the extra loads in flight bring
-        p->wave_nw = (d->head_dim <= 128 && tiles > DREAM_NW8_TILES) ? 8 : 4;
-        // half the output columns per workgroup while that still leaves at most one workgroup per CU
+        // output columns split over 2 or 4 workgroups while that still leaves at most one workgroup per CU
         p->wave_ds = 1;
-        while (p->wave_ds < DREAM_DS_MAX && base * n_qtiles * p->wave_ds * 2 <= 256 && d->head_dim / (p->wave_ds * 2) >= 32)
+        while (p->wave_ds < 4 && base * n_qtiles * p->wave_ds * 2 <= 256 && d->head_dim / (p->wave_ds * 2) >= 32)
             p->wave_ds *= 2;
+        // 8 waves (two per SIMD) where the registers allow it and each wave still gets a few tiles
+        p->wave_nw = (d->head_dim <= 128 && (tiles > 32 || p->wave_ds > 1)) ? 8 : 4;
         p->n_splits = 1;
         p->n_groups = (int)base;
         p->n_streams = (int)base;
