@@ -21,15 +21,18 @@ namespace {
 struct ScoreArgs {
     const void *q, *k;
     const int32_t *q_pos;
-    float *lse2;   // [B, Hq, n_q_pad]  log2-domain log-sum-exp of each row
-    float *part;   // [B, Hq, vis_len]  per-head column sums
+    float *lse2;   // [ns1, B, Hq, n_q_pad]  log2-domain log-sum-exp of each row over the keys of split s (-inf: none)
+    float *part;   // [B, Hq, ns2, vis_len]  column sums per head and row split
     int32_t n_q, n_q_pad, n_keys, n_q_heads, n_kv_heads, vis_start, vis_len;
+    int32_t ns1, ns2;   // splits of the streamed axis: keys in pass 1, query rows in pass 2
+    int64_t lse_split_stride;   // B * Hq * n_q_pad
     int64_t s_max;
     float scale, scale_log2;
 };
 
-// Pass 1: log-sum-exp of every causal row.  One workgroup per (64 query rows, head, sequence); wave w owns
-// rows w*16..w*16+15.  All 256 threads stream K in 32-key tiles (two tiles ahead in registers, two LDS stages,
+// Pass 1: log-sum-exp of every causal row.  One workgroup per (64 query rows, head, sequence, key split); wave w
+// owns rows w*16..w*16+15; with ns1 > 1 the block's key tiles are divided evenly over ns1 workgroups, each of
+// which writes a partial log-sum-exp that pass 2 combines.  All 256 threads stream K in 32-key tiles (two tiles ahead in registers, two LDS stages,
 // one barrier per tile); scores are formed transposed (lane = query column), so a lane keeps a private running
 // (max, sum) over its own key rows and the four row groups are combined once at the end.
 template <int D>
@@ -40,14 +43,16 @@ __global__ __launch_bounds__(256) void scores_lse_bf16_kernel(ScoreArgs a)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = lane & 15, g = lane >> 4;
-    const int blk = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int blk = blockIdx.x, h = blockIdx.y, b = blockIdx.z / a.ns1, split = blockIdx.z % a.ns1;
     const int kvh = h / (a.n_q_heads / a.n_kv_heads);
     const int row = blk * 64 + wave * 16 + c;
     const bool valid = row < a.n_q;
     const int pos = valid ? (a.q_pos ? a.q_pos[(int64_t)b * a.n_q + row] : row) : -1;
     // keys this workgroup has to see: without explicit positions, up to its last row
     const int key_lim = a.q_pos ? a.n_keys : min(min(blk * 64 + 64, a.n_q), a.n_keys);
-    const int n_tiles = (key_lim + 31) / 32;
+    const int n_tiles_all = (key_lim + 31) / 32;
+    const int tps = (n_tiles_all + a.ns1 - 1) / a.ns1;
+    const int t0 = split * tps, n_tiles = max(min(tps, n_tiles_all - t0), 0);   // tiles t0 .. t0 + n_tiles - 1
     int wave_max_pos = pos;
     for (int off = 32; off > 0; off >>= 1)
         wave_max_pos = max(wave_max_pos, __shfl_xor(wave_max_pos, off));
@@ -56,8 +61,8 @@ __global__ __launch_bounds__(256) void scores_lse_bf16_kernel(ScoreArgs a)
     const uint16_t *kb = reinterpret_cast<const uint16_t *>(a.k) + ((int64_t)b * a.n_kv_heads + kvh) * a.s_max * D;
     u32x4 kreg[2][CH];
     const int ld_row = tid / (D / 8), ld_col = tid % (D / 8);
-    auto load_tile = [&](int t, u32x4(&kr)[CH]) {
-        t = min(t, n_tiles - 1);
+    auto load_tile = [&](int i, u32x4(&kr)[CH]) {
+        const int t = t0 + max(min(i, n_tiles - 1), 0);
 #pragma unroll
         for (int j = 0; j < CH; j++) {
             const int key = min(t * 32 + ld_row + j * (2048 / D), a.n_keys - 1);
@@ -74,14 +79,14 @@ __global__ __launch_bounds__(256) void scores_lse_bf16_kernel(ScoreArgs a)
             qf[ks] = *reinterpret_cast<const bf16x8 *>(qp + ks * 32);
     }
     float m = -INFINITY, l = 0.0f;
-    auto step = [&](int t, u32x4(&kr)[CH]) {
-        uint16_t *st = lds[t & 1];
+    auto step = [&](int i, u32x4(&kr)[CH]) {
+        uint16_t *st = lds[i & 1];
 #pragma unroll
         for (int j = 0; j < CH; j++)
             *reinterpret_cast<u32x4 *>(st + (ld_row + j * (2048 / D)) * STR + ld_col * 8) = kr[j];
         __syncthreads();
-        load_tile(t + 2, kr);
-        const int key0 = t * 32;
+        load_tile(i + 2, kr);
+        const int key0 = (t0 + i) * 32;
         if (key0 > wave_max_pos)
             return;   // causal: nothing in this tile is visible to this wave's rows
         bf16x8 kfr[2][NKS];
@@ -131,14 +136,15 @@ __global__ __launch_bounds__(256) void scores_lse_bf16_kernel(ScoreArgs a)
     lw += __shfl_xor(lw, 16);
     lw += __shfl_xor(lw, 32);
     if (g == 0 && valid)
-        a.lse2[((int64_t)b * a.n_q_heads + h) * a.n_q_pad + row] = lw > 0.0f ? mt + log2f(lw) : INFINITY;
+        a.lse2[split * a.lse_split_stride + ((int64_t)b * a.n_q_heads + h) * a.n_q_pad + row] = lw > 0.0f ? mt + log2f(lw) : -INFINITY;
 }
 
-// Pass 2: column sums of the probabilities.  One workgroup per (64 visual keys, head, sequence); wave w keeps
+// Pass 2: column sums of the probabilities.  One workgroup per (64 visual keys, head, sequence, row split); wave w keeps
 // the K fragments of its 16 keys in registers and all 256 threads stream the query rows (with their
 // log-sum-exp and positions) in 32-row tiles through LDS.  A lane sums its key column over the rows it
-// holds; the four row groups are combined at the end, so every (head, key) sum has one fixed order.
-template <int D>
+// holds; the four row groups are combined at the end, so every (head, row split, key) sum has one fixed order.
+// The row's log-sum-exp is combined from pass 1's ns1 partial values when its tile is loaded.
+template <int D, int NS1>
 __global__ __launch_bounds__(256) void scores_colsum_bf16_kernel(ScoreArgs a)
 {
     constexpr int NKS = D / 32, STR = D + 8, CH = 32 * D / 8 / 256;
@@ -149,7 +155,7 @@ __global__ __launch_bounds__(256) void scores_colsum_bf16_kernel(ScoreArgs a)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = lane & 15, g = lane >> 4;
     const int vis_end = a.vis_start + a.vis_len;
-    const int blk0 = a.vis_start + blockIdx.x * 64, h = blockIdx.y, b = blockIdx.z;
+    const int blk0 = a.vis_start + blockIdx.x * 64, h = blockIdx.y, b = blockIdx.z / a.ns2, split = blockIdx.z % a.ns2;
     const int kvh = h / (a.n_q_heads / a.n_kv_heads);
     const int j0 = blk0 + wave * 16;
     const int key = j0 + c;
@@ -163,16 +169,17 @@ __global__ __launch_bounds__(256) void scores_colsum_bf16_kernel(ScoreArgs a)
     }
     // row tiles: without explicit positions row r sits at position r, so rows below the block's first key see nothing
     const int n_tiles_all = (a.n_q + 31) / 32;
-    const int t_first = a.q_pos ? 0 : min(blk0 / 32, n_tiles_all);
-    const int n_tiles = n_tiles_all - t_first;
+    const int t_begin = a.q_pos ? 0 : min(blk0 / 32, n_tiles_all);
+    const int tps = (n_tiles_all - t_begin + a.ns2 - 1) / a.ns2;
+    const int t_first = t_begin + split * tps, n_tiles = max(min(tps, n_tiles_all - t_first), 0);
     const uint16_t *qb = reinterpret_cast<const uint16_t *>(a.q) + ((int64_t)b * a.n_q * a.n_q_heads + h) * D;
     const float *lrow = a.lse2 + ((int64_t)b * a.n_q_heads + h) * a.n_q_pad;
     u32x4 qreg[2][CH];
-    float lreg[2];
+    float lreg[2][NS1];
     int32_t preg[2];
     const int ld_row = tid / (D / 8), ld_col = tid % (D / 8);
-    auto load_tile = [&](int i, u32x4(&qr)[CH], float &lr, int32_t &pr) {
-        const int t = t_first + min(i, n_tiles - 1);
+    auto load_tile = [&](int i, u32x4(&qr)[CH], float(&lr)[NS1], int32_t &pr) {
+        const int t = t_first + max(min(i, n_tiles - 1), 0);
 #pragma unroll
         for (int j = 0; j < CH; j++) {
             const int r = min(t * 32 + ld_row + j * (2048 / D), a.n_q - 1);
@@ -181,7 +188,9 @@ __global__ __launch_bounds__(256) void scores_colsum_bf16_kernel(ScoreArgs a)
         if (tid < 32) {
             const int r = t * 32 + tid;
             const bool live = r < a.n_q;
-            lr = live ? lrow[r] : INFINITY;   // +inf makes the probability of a padding row zero
+#pragma unroll
+            for (int s = 0; s < NS1; s++)
+                lr[s] = live ? lrow[s * a.lse_split_stride + r] : -INFINITY;
             pr = live ? (a.q_pos ? a.q_pos[(int64_t)b * a.n_q + r] : r) : -1;
         }
     };
@@ -190,14 +199,28 @@ __global__ __launch_bounds__(256) void scores_colsum_bf16_kernel(ScoreArgs a)
         load_tile(1, qreg[1], lreg[1], preg[1]);
     }
     float cs = 0.0f;
-    auto step = [&](int i, u32x4(&qr)[CH], float &lr, int32_t &pr) {
+    auto step = [&](int i, u32x4(&qr)[CH], float(&lr)[NS1], int32_t &pr) {
         const int sidx = i & 1;
         uint16_t *st = lds[sidx];
 #pragma unroll
         for (int j = 0; j < CH; j++)
             *reinterpret_cast<u32x4 *>(st + (ld_row + j * (2048 / D)) * STR + ld_col * 8) = qr[j];
         if (tid < 32) {
-            lds_lse[sidx][tid] = lr;
+            // log-sum-exp over all keys from pass 1's per-split values; a single split is taken as it is
+            float mx = lr[0];
+#pragma unroll
+            for (int s = 1; s < NS1; s++)
+                mx = fmaxf(mx, lr[s]);
+            float L = mx;
+            if (NS1 > 1) {
+                float sum = 0.0f;
+#pragma unroll
+                for (int s = 0; s < NS1; s++)
+                    sum += __builtin_amdgcn_exp2f(lr[s] - (mx == -INFINITY ? 0.0f : mx));
+                L = mx + log2f(sum);
+            }
+            // +inf makes the probability zero: padding rows and rows that see no key
+            lds_lse[sidx][tid] = mx == -INFINITY ? INFINITY : L;
             lds_pos[sidx][tid] = pr;
         }
         __syncthreads();
@@ -241,7 +264,7 @@ __global__ __launch_bounds__(256) void scores_colsum_bf16_kernel(ScoreArgs a)
     cs += __shfl_xor(cs, 16);
     cs += __shfl_xor(cs, 32);
     if (g == 0 && key < vis_end)
-        a.part[((int64_t)b * a.n_q_heads + h) * a.vis_len + (key - a.vis_start)] = kvalid ? cs : 0.0f;
+        a.part[(((int64_t)b * a.n_q_heads + h) * a.ns2 + split) * a.vis_len + (key - a.vis_start)] = kvalid ? cs : 0.0f;
 }
 
 // ---- float32 tensors: plain vector-ALU versions of the two passes -------------------------------
@@ -472,18 +495,51 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(const unsigned char *s
     }
 }
 
+template <int D>
+void launch_colsum(int ns1, dim3 grid, hipStream_t st, const ScoreArgs &a)
+{
+    switch (ns1) {
+    case 1:  hipLaunchKernelGGL((scores_colsum_bf16_kernel<D, 1>), grid, dim3(256), 0, st, a); break;
+    case 2:  hipLaunchKernelGGL((scores_colsum_bf16_kernel<D, 2>), grid, dim3(256), 0, st, a); break;
+    case 4:  hipLaunchKernelGGL((scores_colsum_bf16_kernel<D, 4>), grid, dim3(256), 0, st, a); break;
+    default: hipLaunchKernelGGL((scores_colsum_bf16_kernel<D, 8>), grid, dim3(256), 0, st, a); break;
+    }
+}
+
 struct CompressPlan {
-    int n_q_pad;
+    int n_q_pad, ns1, ns2;
     size_t off_lse, off_part, total;
 };
 
-CompressPlan compress_plan(int batch, int n_heads, int n_q, int vis_len)
+// Splits of the streamed axis of a score pass: enough that a workgroup walks about 8 tiles, at most 8 splits,
+// and only while the grid stays near 2048 workgroups (beyond that the chip is busy anyway and more, shorter
+// workgroups only add start-up cost).
+int score_splits(int64_t grid, int tiles)
+{
+    int ns = ceil_div(tiles, 8);
+    if (ns > 8)
+        ns = 8;
+    const int64_t room = 2048 / (grid > 0 ? grid : 1);
+    if (ns > room)
+        ns = (int)room;
+    int pow2 = 1;   // 1, 2, 4 or 8: pass 2 is compiled for these counts of pass-1 splits
+    while (pow2 * 2 <= ns)
+        pow2 *= 2;
+    return pow2;
+}
+
+CompressPlan compress_plan(int batch, int n_heads, int n_q, int vis_len, int dtype)
 {
     CompressPlan p;
     p.n_q_pad = (n_q + 15) / 16 * 16;
+    p.ns1 = p.ns2 = 1;
+    if (dtype == DREAM_BF16) {
+        p.ns1 = score_splits((int64_t)ceil_div(n_q, 64) * n_heads * batch, ceil_div(n_q, 32));
+        p.ns2 = score_splits((int64_t)ceil_div(vis_len > 0 ? vis_len : 1, 64) * n_heads * batch, ceil_div(n_q, 32));
+    }
     p.off_lse = DREAM_WORKSPACE_HEADER_BYTES;
-    p.off_part = align_up(p.off_lse + (size_t)batch * n_heads * p.n_q_pad * sizeof(float), 256);
-    p.total = align_up(p.off_part + (size_t)batch * n_heads * (vis_len > 0 ? vis_len : 1) * sizeof(float), 256);
+    p.off_part = align_up(p.off_lse + (size_t)p.ns1 * batch * n_heads * p.n_q_pad * sizeof(float), 256);
+    p.total = align_up(p.off_part + (size_t)p.ns2 * batch * n_heads * (vis_len > 0 ? vis_len : 1) * sizeof(float), 256);
     return p;
 }
 
@@ -495,7 +551,7 @@ size_t dream_visual_compress_workspace(const dream_attn_desc *desc, int32_t n_q,
 {
     if (!desc || desc->batch < 1 || desc->n_q_heads < 1 || n_q < 1)
         return DREAM_WORKSPACE_HEADER_BYTES;
-    return compress_plan(desc->batch, desc->n_q_heads, n_q, vis_len).total;
+    return compress_plan(desc->batch, desc->n_q_heads, n_q, vis_len, desc->dtype).total;
 }
 
 int dream_visual_compress(const dream_attn_desc *desc, const void *q, const int32_t *q_pos, int32_t n_q,
@@ -540,7 +596,7 @@ int dream_visual_compress(const dream_attn_desc *desc, const void *q, const int3
             return fail(DREAM_ERR_INVALID_ARG, "%s: %d rows at positions 0..n_q-1 but only %d keys", who, n_q, n_keys);
         if ((int64_t)vis_start + vis_len > n_keys)
             return fail(DREAM_ERR_INVALID_ARG, "%s: visual span [%d, %d) exceeds the %d live keys", who, vis_start, vis_start + vis_len, n_keys);
-        CompressPlan p = compress_plan(desc->batch, desc->n_q_heads, n_q, vis_len);
+        CompressPlan p = compress_plan(desc->batch, desc->n_q_heads, n_q, vis_len, desc->dtype);
         if (!workspace || workspace_bytes < p.total)
             return fail(DREAM_ERR_WORKSPACE, "%s: workspace of %zu bytes, %zu needed", who, workspace_bytes, p.total);
         ScoreArgs a;
@@ -548,24 +604,28 @@ int dream_visual_compress(const dream_attn_desc *desc, const void *q, const int3
         a.lse2 = reinterpret_cast<float *>(static_cast<char *>(workspace) + p.off_lse);
         a.part = reinterpret_cast<float *>(static_cast<char *>(workspace) + p.off_part);
         a.n_q = n_q; a.n_q_pad = p.n_q_pad; a.n_keys = n_keys;
+        a.ns1 = p.ns1; a.ns2 = p.ns2;
+        a.lse_split_stride = (int64_t)desc->batch * desc->n_q_heads * p.n_q_pad;
         a.n_q_heads = desc->n_q_heads; a.n_kv_heads = desc->n_kv_heads;
         a.vis_start = vis_start; a.vis_len = vis_len; a.s_max = desc->s_max;
         a.scale = desc->scale != 0.0f ? desc->scale : 1.0f / sqrtf((float)desc->head_dim);
         a.scale_log2 = a.scale * 1.4426950408889634f;
         if (desc->dtype == DREAM_BF16) {
-            dim3 g1(ceil_div(n_q, 64), desc->n_q_heads, desc->batch), g2(ceil_div(vis_len, 64), desc->n_q_heads, desc->batch);
+            if ((int64_t)desc->batch * (p.ns1 > p.ns2 ? p.ns1 : p.ns2) > 65535)
+                return fail(DREAM_ERR_UNSUPPORTED, "%s: batch %d too large for the score grids", who, desc->batch);
+            dim3 g1(ceil_div(n_q, 64), desc->n_q_heads, desc->batch * p.ns1), g2(ceil_div(vis_len, 64), desc->n_q_heads, desc->batch * p.ns2);
             switch (desc->head_dim) {
             case 64:
                 hipLaunchKernelGGL(scores_lse_bf16_kernel<64>, g1, dim3(256), 0, st, a);
-                hipLaunchKernelGGL(scores_colsum_bf16_kernel<64>, g2, dim3(256), 0, st, a);
+                launch_colsum<64>(p.ns1, g2, st, a);
                 break;
             case 128:
                 hipLaunchKernelGGL(scores_lse_bf16_kernel<128>, g1, dim3(256), 0, st, a);
-                hipLaunchKernelGGL(scores_colsum_bf16_kernel<128>, g2, dim3(256), 0, st, a);
+                launch_colsum<128>(p.ns1, g2, st, a);
                 break;
             default:
                 hipLaunchKernelGGL(scores_lse_bf16_kernel<256>, g1, dim3(256), 0, st, a);
-                hipLaunchKernelGGL(scores_colsum_bf16_kernel<256>, g2, dim3(256), 0, st, a);
+                launch_colsum<256>(p.ns1, g2, st, a);
                 break;
             }
         } else {
@@ -578,7 +638,7 @@ int dream_visual_compress(const dream_attn_desc *desc, const void *q, const int3
         if (rc)
             return rc;
         part = a.part;
-        n_heads = desc->n_q_heads;
+        n_heads = desc->n_q_heads * p.ns2;
     }
     if (n_kept_host)
         *n_kept_host = k;
