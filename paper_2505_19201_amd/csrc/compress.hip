@@ -43,8 +43,10 @@ __global__ __launch_bounds__(256) void scores_lse_bf16_kernel(ScoreArgs a)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = lane & 15, g = lane >> 4;
-    const int blk = blockIdx.x, h = blockIdx.y, b = blockIdx.z / a.ns1, split = blockIdx.z % a.ns1;
-    const int kvh = h / (a.n_q_heads / a.n_kv_heads);
+    // x walks the heads with the KV head fastest: workgroup ids that share a KV head are congruent mod 8
+    // (when there are 8 or more KV heads), so its K is fetched into one XCD's L2 only
+    const int kvh = blockIdx.x % a.n_kv_heads, h = kvh * (a.n_q_heads / a.n_kv_heads) + blockIdx.x / a.n_kv_heads;
+    const int blk = blockIdx.y, b = blockIdx.z / a.ns1, split = blockIdx.z % a.ns1;
     const int row = blk * 64 + wave * 16 + c;
     const bool valid = row < a.n_q;
     const int pos = valid ? (a.q_pos ? a.q_pos[(int64_t)b * a.n_q + row] : row) : -1;
@@ -155,8 +157,9 @@ __global__ __launch_bounds__(256) void scores_colsum_bf16_kernel(ScoreArgs a)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = lane & 15, g = lane >> 4;
     const int vis_end = a.vis_start + a.vis_len;
-    const int blk0 = a.vis_start + blockIdx.x * 64, h = blockIdx.y, b = blockIdx.z / a.ns2, split = blockIdx.z % a.ns2;
-    const int kvh = h / (a.n_q_heads / a.n_kv_heads);
+    // x walks the heads with the KV head fastest (see pass 1): the query rows of a head stay in one XCD's L2
+    const int kvh = blockIdx.x % a.n_kv_heads, h = kvh * (a.n_q_heads / a.n_kv_heads) + blockIdx.x / a.n_kv_heads;
+    const int blk0 = a.vis_start + blockIdx.y * 64, b = blockIdx.z / a.ns2, split = blockIdx.z % a.ns2;
     const int j0 = blk0 + wave * 16;
     const int key = j0 + c;
     const bool kvalid = key < vis_end && key < a.n_keys;
@@ -611,9 +614,9 @@ int dream_visual_compress(const dream_attn_desc *desc, const void *q, const int3
         a.scale = desc->scale != 0.0f ? desc->scale : 1.0f / sqrtf((float)desc->head_dim);
         a.scale_log2 = a.scale * 1.4426950408889634f;
         if (desc->dtype == DREAM_BF16) {
-            if ((int64_t)desc->batch * (p.ns1 > p.ns2 ? p.ns1 : p.ns2) > 65535)
-                return fail(DREAM_ERR_UNSUPPORTED, "%s: batch %d too large for the score grids", who, desc->batch);
-            dim3 g1(ceil_div(n_q, 64), desc->n_q_heads, desc->batch * p.ns1), g2(ceil_div(vis_len, 64), desc->n_q_heads, desc->batch * p.ns2);
+            if ((int64_t)desc->batch * (p.ns1 > p.ns2 ? p.ns1 : p.ns2) > 65535 || ceil_div(n_q, 64) > 65535)
+                return fail(DREAM_ERR_UNSUPPORTED, "%s: batch %d or n_q %d too large for the score grids", who, desc->batch, n_q);
+            dim3 g1(desc->n_q_heads, ceil_div(n_q, 64), desc->batch * p.ns1), g2(desc->n_q_heads, ceil_div(vis_len, 64), desc->batch * p.ns2);
             switch (desc->head_dim) {
             case 64:
                 hipLaunchKernelGGL(scores_lse_bf16_kernel<64>, g1, dim3(256), 0, st, a);
