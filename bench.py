@@ -191,7 +191,8 @@ def main() -> int:
     launch_us = phase_ms[0] * 1e3 / L
     bytes_launch = verify_bytes_per_launch(cfg)
     achieved = bytes_launch / (launch_us * 1e-6) / 1e9
-    roofline = {"bound": "hbm", "kernel": "attn_bf16_kernel (dream_tree_verify_attn)", "achieved": round(achieved, 1),
+    plan = dream.dream_attn_plan_describe(desc, T, S)
+    roofline = {"bound": "hbm", "kernel": "dream_tree_verify_attn: " + plan, "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": read_traffic(cfg.name), "bytes_per_launch": bytes_launch,
                 "launch_us": round(launch_us, 3), "launches_per_step": L}

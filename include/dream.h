@@ -171,6 +171,13 @@ int dream_tree_validate_host(const int32_t *parent_host, int32_t n_tree, int32_t
 /* Text of the calling thread's last error ("" if none); static storage, never NULL. */
 const char *dream_last_error(void);
 
+/* Host-only: writes a short description of the launch plan the attention calls would use for n_q query
+ * rows per sequence and keys up to max_kv_len (kernel and its template arguments, workgroups, key splits,
+ * whether a merge launch follows) into buf (NUL-terminated, truncated to buf_bytes).  Needs no GPU.
+ * DREAM_OK, or DREAM_ERR_INVALID_ARG / DREAM_ERR_UNSUPPORTED for a descriptor the attention calls reject. */
+int dream_attn_plan_describe(const dream_attn_desc *desc, int32_t n_q, int64_t max_kv_len, char *buf,
+                             size_t buf_bytes);
+
 /* Launch-shape overrides for experiments (0 = choose automatically): number of key-range splits
  * the attention calls use, and number of 16-row query tiles one workgroup serves (1, 2 or 4).
  * Results are identical up to floating-point summation order.  Query the workspace size again

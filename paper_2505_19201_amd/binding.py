@@ -22,6 +22,7 @@ EXPORTED_SYMBOLS = (
     "dream_draft_xattn_workspace", "dream_draft_xattn", "dream_visual_compress_workspace",
     "dream_visual_compress", "dream_accept_path_workspace", "dream_accept_path",
     "dream_tree_validate_host", "dream_last_error", "dream_set_kv_splits", "dream_set_q_tiles",
+    "dream_attn_plan_describe",
 )
 
 
@@ -98,6 +99,12 @@ def dream_set_kv_splits(n_splits: int) -> None:
 
 def dream_set_q_tiles(q_tiles: int) -> None:
     load().dream_set_q_tiles(C.c_int32(q_tiles))
+
+
+def dream_attn_plan_describe(desc: "AttnDesc", n_q: int, max_kv_len: int) -> str:
+    buf = C.create_string_buffer(256)
+    _check(load().dream_attn_plan_describe(C.byref(desc), C.c_int32(n_q), C.c_int64(max_kv_len), buf, C.c_size_t(256)))
+    return buf.value.decode()
 
 
 def dream_workspace_init(workspace: torch.Tensor, stream=None) -> None:

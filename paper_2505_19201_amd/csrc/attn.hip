@@ -1104,6 +1104,29 @@ unsigned long long *dream_debug_ts(void)
 }
 #endif
 
+int dream_attn_plan_describe(const dream_attn_desc *desc, int32_t n_q, int64_t max_kv_len, char *buf, size_t buf_bytes)
+{
+    const char *who = "dream_attn_plan_describe";
+    if (!buf || buf_bytes == 0)
+        return fail(DREAM_ERR_INVALID_ARG, "%s: no buffer", who);
+    int rc = validate_desc(desc, who);
+    if (rc)
+        return rc;
+    if (n_q < 1 || max_kv_len < 1 || max_kv_len > desc->s_max)
+        return fail(DREAM_ERR_INVALID_ARG, "%s: need n_q >= 1 and 1 <= max_kv_len <= s_max", who);
+    Plan p;
+    make_plan(desc, n_q, max_kv_len, &p);
+    if (desc->dtype == DREAM_F32)
+        snprintf(buf, buf_bytes, "attn_f32_kernel workgroups=%lld", (long long)desc->batch * desc->n_q_heads * n_q);
+    else if (p.wave_mode)
+        snprintf(buf, buf_bytes, "attn_wave_kernel<%d,%d,%d> workgroups=%d splits=1 merge_launch=0", desc->head_dim, p.wave_nw,
+                 p.wave_ds, p.n_qg * p.wave_ds * desc->n_kv_heads * desc->batch);
+    else
+        snprintf(buf, buf_bytes, "attn_bf16_kernel<%d,%d,%d,%d> workgroups=%d splits=%d merge_launch=%d", desc->head_dim, p.qg, p.kt,
+                 p.pfd, p.n_groups * p.n_splits, p.n_splits, p.n_splits > 1 ? 1 : 0);
+    return DREAM_OK;
+}
+
 size_t dream_tree_verify_attn_workspace(const dream_attn_desc *desc, int32_t n_tree, int64_t max_kv_len)
 {
     return workspace_for(desc, n_tree, max_kv_len);

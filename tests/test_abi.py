@@ -94,3 +94,22 @@ def test_workspace_sizes_are_monotone(lib):
         dream.dream_set_kv_splits(0)
     assert dream.dream_accept_path_workspace(1, 60, 32000) >= 65536 + 2 * 60 * 4 * 4
     assert dream.dream_visual_compress_workspace(d, 704, 576) >= 65536 + 32 * 704 * 4 + 32 * 576 * 4
+
+
+def test_launch_plans_of_the_paper_shapes(lib):
+    """The plan is host logic: one sequence of an MHA model takes the single-launch wave kernel with its output
+    columns split over workgroups, a GQA model or a batch of sequences takes the shared-tile kernel."""
+    def plan(B, hq, hkv, d, n_q, s):
+        return dream.dream_attn_plan_describe(dream.attn_desc(B, hq, hkv, d, dream.BF16, s), n_q, s)
+    llava = plan(1, 32, 32, 128, 60, 764)
+    assert llava.startswith("attn_wave_kernel<128,8,2>") and "workgroups=256" in llava and "merge_launch=0" in llava
+    level = plan(1, 32, 32, 128, 16, 764)            # one drafted tree level: a single query tile per head
+    assert level.startswith("attn_wave_kernel<128,8,4>") and "workgroups=128" in level
+    pixtral = plan(1, 32, 8, 128, 60, 1340)
+    assert pixtral.startswith("attn_bf16_kernel<128,1,") and "splits=8" in pixtral and "merge_launch=1" in pixtral
+    batch = plan(32, 32, 32, 64, 60, 1660)
+    assert batch.startswith("attn_bf16_kernel<64,1,") and "splits=1 " in batch and "merge_launch=0" in batch
+    f32 = dream.dream_attn_plan_describe(dream.attn_desc(1, 4, 4, 64, dream.F32, 104), 8, 104)
+    assert f32.startswith("attn_f32_kernel")
+    with pytest.raises(dream.DreamError):
+        dream.dream_attn_plan_describe(dream.attn_desc(1, 32, 32, 96, dream.BF16, 764), 60, 764)
