@@ -211,11 +211,47 @@ def main() -> int:
         "roofline": roofline,
     }
 
+    out["read_ceiling"] = read_ceiling(torch, dream, bytes_launch, L)
     out["streaming_regime"] = streaming_regime(torch, dream, di, cfg)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(cfg, L, tokens_per_step)
     print(json.dumps(out))
     return 0
+
+
+def read_ceiling(torch, dream, bytes_launch, L):
+    """What a launch that only READS the verification kernel's algorithmic bytes costs: L back-to-back launches
+    of the library's plain 16-byte-load read kernel over L distinct buffers, replayed as a HIP graph like the
+    verification phase.  The attention kernel cannot beat this; it is the ceiling the roofline fraction of a
+    single-sequence launch should be read against."""
+    n = (bytes_launch + 15) // 16 * 16
+    buf = torch.empty(L * n, dtype=torch.uint8, device="cuda").random_(0, 255)
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    stream = torch.cuda.Stream()
+
+    def run():
+        for l in range(L):
+            dream.dream_stream_read(buf, n, sink, offset_bytes=l * n)
+    run()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=stream):
+        run()
+    reps = 20
+    with torch.cuda.stream(stream):
+        for _ in range(3):
+            g.replay()
+        stream.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            g.replay()
+        e1.record()
+        stream.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / (reps * L)
+    gbs = n / (us * 1e-6) / 1e9
+    return {"kernel": "stream_read_kernel (16-byte loads, no writes)", "bytes_per_launch": n, "launch_us": round(us, 3),
+            "achieved": round(gbs, 1), "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4)}
 
 
 def copy_calibration(torch):

@@ -178,6 +178,11 @@ const char *dream_last_error(void);
 int dream_attn_plan_describe(const dream_attn_desc *desc, int32_t n_q, int64_t max_kv_len, char *buf,
                              size_t buf_bytes);
 
+/* Measurement aid, not a step of the method: reads `bytes` (rounded down to 16) from the device pointer src
+ * once with 16-byte loads and writes nothing (sink: 4 device bytes, almost never stored to).  The time of
+ * this call is the floor for any kernel that has to read that many bytes in one launch.  src 16-byte aligned. */
+int dream_stream_read(const void *src, size_t bytes, void *sink, void *stream);
+
 /* Launch-shape overrides for experiments (0 = choose automatically): number of key-range splits
  * the attention calls use, and number of 16-row query tiles one workgroup serves (1, 2 or 4).
  * Results are identical up to floating-point summation order.  Query the workspace size again

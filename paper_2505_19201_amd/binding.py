@@ -22,7 +22,7 @@ EXPORTED_SYMBOLS = (
     "dream_draft_xattn_workspace", "dream_draft_xattn", "dream_visual_compress_workspace",
     "dream_visual_compress", "dream_accept_path_workspace", "dream_accept_path",
     "dream_tree_validate_host", "dream_last_error", "dream_set_kv_splits", "dream_set_q_tiles",
-    "dream_attn_plan_describe",
+    "dream_attn_plan_describe", "dream_stream_read",
 )
 
 
@@ -99,6 +99,12 @@ def dream_set_kv_splits(n_splits: int) -> None:
 
 def dream_set_q_tiles(q_tiles: int) -> None:
     load().dream_set_q_tiles(C.c_int32(q_tiles))
+
+
+def dream_stream_read(src: torch.Tensor, nbytes: int, sink: torch.Tensor, offset_bytes: int = 0, stream=None) -> None:
+    if offset_bytes < 0 or offset_bytes + nbytes > src.numel() * src.element_size():
+        raise ValueError("range outside the source tensor")
+    _check(load().dream_stream_read(C.c_void_p(src.data_ptr() + offset_bytes), C.c_size_t(nbytes), _dev(sink), _stream(stream)))
 
 
 def dream_attn_plan_describe(desc: "AttnDesc", n_q: int, max_kv_len: int) -> str:

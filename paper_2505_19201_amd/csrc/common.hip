@@ -37,6 +37,19 @@ __global__ void zero_words_kernel(uint32_t *p, int n)
         p[i] = 0u;
 }
 
+// Reads n16 16-byte words once, grid-stride, and folds them into one word per thread; the fold is stored only
+// if it equals a value the caller does not expect, which keeps the loads alive without a write stream.
+__global__ __launch_bounds__(256) void stream_read_kernel(const u32x4 *src, size_t n16, uint32_t *sink, uint32_t never)
+{
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride)
+        acc ^= src[i];
+    const uint32_t fold = acc.x ^ acc.y ^ acc.z ^ acc.w;
+    if (fold == never)
+        *sink = fold;
+}
+
 }  // namespace dream
 
 using namespace dream;
@@ -60,6 +73,19 @@ int dream_workspace_init(void *workspace, size_t workspace_bytes, void *stream)
     hipLaunchKernelGGL(zero_words_kernel, dim3((n + 255) / 256), dim3(256), 0, as_stream(stream),
                        reinterpret_cast<uint32_t *>(workspace), n);
     return check_launch("dream_workspace_init");
+}
+
+int dream_stream_read(const void *src, size_t bytes, void *sink, void *stream)
+{
+    if (!src || !sink || bytes < 16 || (reinterpret_cast<uintptr_t>(src) & 15))
+        return fail(DREAM_ERR_INVALID_ARG, "dream_stream_read: need a 16-byte aligned source of at least 16 bytes and a sink");
+    const size_t n16 = bytes / 16;
+    size_t wgs = (n16 + 255) / 256;
+    if (wgs > 2048)
+        wgs = 2048;   // 8 workgroups per CU, grid-stride beyond that
+    hipLaunchKernelGGL(stream_read_kernel, dim3((unsigned)wgs), dim3(256), 0, as_stream(stream),
+                       reinterpret_cast<const u32x4 *>(src), n16, reinterpret_cast<uint32_t *>(sink), 0x9e3779b9u);
+    return check_launch("dream_stream_read");
 }
 
 int dream_tree_validate_host(const int32_t *parent_host, int32_t n_tree, int32_t *max_depth_out)
