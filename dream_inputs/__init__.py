@@ -243,6 +243,20 @@ def path_to(parent: np.ndarray, node: int) -> List[int]:
     return out[::-1]
 
 
+def accepted_paths(parents: np.ndarray, depths: Sequence[int], max_depth: int, seed: int) -> Tuple[np.ndarray, np.ndarray]:
+    """For every sequence a root-to-node path to a seeded node at the asked depth, in the layout the
+    acceptance step emits: path [B, max_depth+1] root first and -1 padded, accept_len [B]."""
+    B = parents.shape[0]
+    path = np.full((B, max_depth + 1), -1, dtype=np.int32)
+    alen = np.zeros(B, dtype=np.int32)
+    for b in range(B):
+        node = node_at_depth(parents[b], int(depths[b]), seed, sub=b)
+        p = path_to(parents[b], node)
+        path[b, :len(p)] = p
+        alen[b] = len(p) - 1
+    return path, alen
+
+
 def node_at_depth(parent: np.ndarray, depth: int, seed: int, sub: int = 0) -> int:
     d = tree_depths(parent)
     cand = np.nonzero(d == depth)[0]

@@ -167,3 +167,18 @@ def accept_path(logits, dtype: str, token, parent, max_depth: int):
                                   _ptr(parent), C.c_int(max_depth), _ptr(am), _ptr(alen), _ptr(path), _ptr(bonus))
     assert rc == 0
     return am, alen, path, bonus
+
+
+def kv_commit(cache, dtype: str, prefix_len, n_tree: int, path, accept_len):
+    """cache [B,Hkv,s_max,D] -> (committed copy, new_len [B]); path [B, stride] root first."""
+    cache = _check(cache, dtype).copy()
+    B, Hkv, s_max, D = cache.shape
+    prefix_len, accept_len = _i32(prefix_len), _i32(accept_len)
+    path = _i32(path).reshape(B, -1)
+    new_len = np.zeros(B, dtype=np.int32)
+    rc = lib().oracle_kv_commit(_ptr(cache), C.c_int(_DT[dtype]), C.c_int(B), C.c_int(Hkv), C.c_int64(s_max), C.c_int(D),
+                                _ptr(prefix_len), C.c_int(n_tree), _ptr(path), C.c_int(path.shape[1]), _ptr(accept_len),
+                                _ptr(new_len))
+    if rc != 0:
+        raise ValueError("kv_commit: path entry or length out of range")
+    return cache, new_len

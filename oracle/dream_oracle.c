@@ -27,10 +27,19 @@
  *       everything after the first mismatch on a path is discarded; the target's own token at
  *       the last accepted node is the bonus token (Section 4: up to depth + 1 tokens a round).
  *
+ *   oracle_kv_commit
+ *       what Section 2.1 says happens after verification: the tokens after the first rejection
+ *       are discarded and decoding continues from the accepted prefix; with KV caching
+ *       (Section 4, setup) that means the cache rows of the accepted root-to-node path become
+ *       the next rows of the prefix and every other tree row is dropped.
+ *
  * Parity pins (tests/test_oracle_*.py, no GPU needed): chain tree == dense causal attention
  * (library SDPA in float64), Q = 0 closed forms (mean of V rows; harmonic-number column sums),
  * dense-mask brute force, mask-leak detectors, exhaustive subset search for top-k, root-to-leaf
- * path enumeration and planted paths/ties for acceptance.  No function here is unpinned.
+ * path enumeration and planted paths/ties for acceptance; for the commit, hand-written row markers
+ * (including a path whose destination rows are other entries' source rows), the no-op chain path and
+ * "attention over the committed cache == tree-masked attention of the accepted node".  No function
+ * here is unpinned.
  *
  * Tensor layouts (C order): q [B,Tq,Hq,D]; k,v [B,Hkv,s_max,D]; logits [B,T,V].
  * dtype: 0 = IEEE float32, 1 = bfloat16 bit patterns (uint16); both are widened exactly to double.
@@ -328,5 +337,43 @@ int oracle_accept_path(const void *logits, int dtype, int B, int T, int V,
     }
     free(depth);
     free(acc);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------------------------ */
+/* KV-cache commit after acceptance (Section 2.1; KV caching: Section 4).                     */
+/* cache [B,Hkv,s_max,D] of the given dtype, tree rows at [P_b, P_b+T).  For every sequence   */
+/* and KV head: new row P_b + j = old row P_b + path[b][j] for j = 0 .. accept_len[b]          */
+/* (path[b][0] is the root); every other row keeps its content.  new_len[b] = P_b +           */
+/* accept_len[b] + 1.  The old tree rows are copied aside first, so the result is the          */
+/* definition itself and does not depend on any order of moves.                                */
+/* Returns -1 (cache untouched) if a path entry is outside [0,T) or a length does not fit.     */
+/* ------------------------------------------------------------------------------------------ */
+int oracle_kv_commit(void *cache, int dtype, int B, int Hkv, int64_t s_max, int D,
+                     const int32_t *prefix_len, int T, const int32_t *path, int path_stride,
+                     const int32_t *accept_len, int32_t *new_len)
+{
+    size_t rb = (size_t)D * elem_size(dtype);
+    for (int b = 0; b < B; b++) {
+        if (accept_len[b] < 0 || accept_len[b] >= path_stride || accept_len[b] >= T)
+            return -1;
+        if (prefix_len[b] < 0 || (int64_t)prefix_len[b] + T > s_max)
+            return -1;
+        for (int j = 0; j <= accept_len[b]; j++)
+            if (path[(int64_t)b * path_stride + j] < 0 || path[(int64_t)b * path_stride + j] >= T)
+                return -1;
+    }
+    char *old_rows = (char *)malloc(rb * (size_t)T);
+    for (int b = 0; b < B; b++) {
+        for (int h = 0; h < Hkv; h++) {
+            char *tree = (char *)cache + (((size_t)b * Hkv + h) * (size_t)s_max + (size_t)prefix_len[b]) * rb;
+            memcpy(old_rows, tree, rb * (size_t)T);
+            for (int j = 0; j <= accept_len[b]; j++)
+                memcpy(tree + (size_t)j * rb, old_rows + (size_t)path[(int64_t)b * path_stride + j] * rb, rb);
+        }
+        if (new_len)
+            new_len[b] = prefix_len[b] + accept_len[b] + 1;
+    }
+    free(old_rows);
     return 0;
 }
