@@ -6,9 +6,11 @@ One step = one pass over the whole hot path on one batch of synthetic input:
   + 6 x dream_draft_xattn (one call per drafted tree level)
   + dream_visual_compress (scores over all prefill rows, top-k keep, row gather)
   + dream_accept_path.
-All inputs are resident in HBM before the timed region.  The four phases are captured as HIP graphs
-(no memset nodes) and replayed; HIP events between the graph launches, on the launching stream, give
-the time of the verification block, from which the roofline figure of the dominant kernel is derived.
+All inputs are resident in HBM before the timed region.  The timed step is ONE HIP graph holding the four
+phases (no memset nodes), replayed K times.  After the timed region the same work runs once more as one
+graph per phase with HIP events between the graph launches, on the launching stream: that gives the phase
+breakdown and the time of the verification block, from which the roofline figure of the dominant kernel
+is derived.
 
 Prints ONE JSON line (see README for the fields).
 """
@@ -152,34 +154,47 @@ def main() -> int:
     runners = []
     if args.no_graph:
         runners = [f for _, f in phases]
+
+        def whole_step():
+            for f in runners:
+                f()
     else:
         for _, f in phases:
             g = torch.cuda.CUDAGraph()
             with torch.cuda.graph(g, stream=stream):
                 f()
             runners.append(g.replay)
+        # the timed step is ONE graph holding all four phases; the per-phase graphs above only serve the breakdown
+        step_graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(step_graph, stream=stream):
+            for _, f in phases:
+                f()
+        whole_step = step_graph.replay
     torch.cuda.synchronize()
 
-    def one_step(evs=None):
+    def one_step(evs):
         for i, r in enumerate(runners):
-            if evs is not None:
-                evs[i].record()
+            evs[i].record()
             r()
-        if evs is not None:
-            evs[len(runners)].record()
+        evs[len(runners)].record()
 
     with torch.cuda.stream(stream):
         for _ in range(args.warmup):
-            one_step()
+            whole_step()
         stream.synchronize()
         torch.cuda.synchronize()
-        all_evs = [[torch.cuda.Event(enable_timing=True) for _ in range(len(runners) + 1)] for _ in range(args.steps)]
         t0 = time.perf_counter()
+        for s in range(args.steps):
+            whole_step()
+        stream.synchronize()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        # phase breakdown (outside the timed region): the same work as one graph per phase with events between
+        all_evs = [[torch.cuda.Event(enable_timing=True) for _ in range(len(runners) + 1)] for _ in range(args.steps)]
         for s in range(args.steps):
             one_step(all_evs[s])
         stream.synchronize()
         torch.cuda.synchronize()
-        t1 = time.perf_counter()
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     phase_ms = [float(np.mean([all_evs[s][i].elapsed_time(all_evs[s][i + 1]) for s in range(args.steps)]))
@@ -212,6 +227,7 @@ def main() -> int:
     }
 
     out["read_ceiling"] = read_ceiling(torch, dream, bytes_launch, L)
+    out["next_rows"] = {"kv_commit": kv_commit_leg(torch, dream, desc, vk + vv, prefix_len, T, accept_path, accept_len, cfg)}
     out["streaming_regime"] = streaming_regime(torch, dream, di, cfg)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(cfg, L, tokens_per_step)
@@ -252,6 +268,38 @@ def read_ceiling(torch, dream, bytes_launch, L):
     gbs = n / (us * 1e-6) / 1e9
     return {"kernel": "stream_read_kernel (16-byte loads, no writes)", "bytes_per_launch": n, "launch_us": round(us, 3),
             "achieved": round(gbs, 1), "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4)}
+
+
+def kv_commit_leg(torch, dream, desc, caches, prefix_len, T, accept_path, accept_len, cfg):
+    """The step that follows acceptance (not part of `value`): one dream_kv_commit launch moves the accepted
+    path's rows in the K and V caches of every layer.  Timed as a replayed graph; it runs last because it
+    rewrites the tree rows of the caches."""
+    new_len = torch.empty_like(prefix_len)
+    stream = torch.cuda.Stream()
+    dream.dream_kv_commit(desc, caches, prefix_len, T, accept_path, accept_len, new_len)
+    torch.cuda.synchronize()
+    per_graph = 16   # a lone kernel per graph would time the graph launch, not the kernel
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=stream):
+        for _ in range(per_graph):
+            dream.dream_kv_commit(desc, caches, prefix_len, T, accept_path, accept_len, new_len)
+    reps = 20
+    with torch.cuda.stream(stream):
+        for _ in range(3):
+            g.replay()
+        stream.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            g.replay()
+        e1.record()
+        stream.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / (reps * per_graph)
+    rows = int((accept_len + 1).sum().item())
+    nbytes = 2 * len(caches) * cfg.n_kv_heads * rows * cfg.head_dim * 2   # read + write of the path rows
+    assert new_len.cpu().tolist() == (prefix_len + accept_len + 1).cpu().tolist()
+    return {"caches": len(caches), "launch_us": round(us, 3), "bytes": nbytes,
+            "achieved_GBs": round(nbytes / (us * 1e-6) / 1e9, 1), "bound": "hbm"}
 
 
 def copy_calibration(torch):

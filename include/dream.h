@@ -164,6 +164,29 @@ int dream_accept_path(const void *logits, int32_t logits_dtype, int32_t batch, i
                       int32_t *accept_path, int32_t *bonus_token, void *workspace,
                       size_t workspace_bytes, void *stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * KV-cache commit of the accepted path (Section 2.1: the tokens after the first rejected one are
+ * discarded and decoding continues from the accepted prefix; Section 4: KV caching).
+ *   caches_host    HOST array of n_caches DEVICE pointers, each a cache [B, Hkv, s_max, D] of
+ *                  desc->dtype (K and V of every layer, the draft's feature caches, ...),
+ *                  16-byte aligned, modified in place
+ *   prefix_len     [B] int32   the tree rows of sequence b sit at [prefix_len[b], +n_tree)
+ *   accept_path    [B, path_stride] int32   root first (as dream_accept_path writes it)
+ *   accept_len     [B] int32   number of accepted nodes below the root, < min(path_stride, n_tree)
+ *   prefix_len_out nullable [B] int32, must not alias prefix_len
+ * In every cache, for every KV head: row prefix_len[b] + j receives the old content of row
+ * prefix_len[b] + accept_path[b][j] for j = 0 .. accept_len[b]; all other rows keep their content.
+ * prefix_len_out[b] = prefix_len[b] + accept_len[b] + 1 (prefix, root and accepted nodes; the bonus
+ * token's row is written by the next round).  Uses desc->batch, n_kv_heads, head_dim, dtype, s_max.
+ * The call needs no workspace; the pointers are read on the host before it returns.
+ * DREAM_ERR_UNSUPPORTED if min(path_stride, n_tree) rows exceed 64 KB or a row is not a multiple
+ * of 16 bytes.  Device metadata is trusted but clamped to the tree rows.
+ * ------------------------------------------------------------------------------------------- */
+int dream_kv_commit(const dream_attn_desc *desc, void *const *caches_host, int32_t n_caches,
+                    const int32_t *prefix_len, int32_t n_tree, const int32_t *accept_path,
+                    int32_t path_stride, const int32_t *accept_len, int32_t *prefix_len_out,
+                    void *stream);
+
 /* Host-side check of one parent array: parent_host[0] == -1 and 0 <= parent_host[i] < i.
  * Writes the maximum depth to *max_depth_out (nullable).  DREAM_OK or DREAM_ERR_INVALID_ARG. */
 int dream_tree_validate_host(const int32_t *parent_host, int32_t n_tree, int32_t *max_depth_out);

@@ -8,7 +8,7 @@ from __future__ import annotations
 
 import ctypes as C
 import os
-from typing import Optional
+from typing import Optional, Sequence
 
 import numpy as np
 import torch
@@ -22,7 +22,7 @@ EXPORTED_SYMBOLS = (
     "dream_draft_xattn_workspace", "dream_draft_xattn", "dream_visual_compress_workspace",
     "dream_visual_compress", "dream_accept_path_workspace", "dream_accept_path",
     "dream_tree_validate_host", "dream_last_error", "dream_set_kv_splits", "dream_set_q_tiles",
-    "dream_attn_plan_describe", "dream_stream_read",
+    "dream_attn_plan_describe", "dream_stream_read", "dream_kv_commit",
 )
 
 
@@ -187,6 +187,15 @@ def dream_accept_path(logits, logits_dtype: int, batch: int, n_tree: int, vocab:
                                     _dev(node_argmax), _dev(accept_len), _dev(accept_path), _dev(bonus_token),
                                     _dev(workspace), C.c_size_t(workspace.numel() * workspace.element_size()),
                                     _stream(stream)))
+
+
+def dream_kv_commit(desc: AttnDesc, caches: Sequence[torch.Tensor], prefix_len: torch.Tensor, n_tree: int,
+                    accept_path: torch.Tensor, accept_len: torch.Tensor, prefix_len_out: Optional[torch.Tensor] = None,
+                    stream=None) -> None:
+    ptrs = (C.c_void_p * len(caches))(*[_dev(c).value for c in caches])
+    _check(load().dream_kv_commit(C.byref(desc), ptrs, C.c_int32(len(caches)), _dev(prefix_len), C.c_int32(n_tree),
+                                  _dev(accept_path), C.c_int32(accept_path.shape[-1]), _dev(accept_len),
+                                  _dev(prefix_len_out), _stream(stream)))
 
 
 def dream_tree_validate_host(parent_host: np.ndarray) -> int:

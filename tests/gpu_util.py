@@ -112,3 +112,18 @@ def run_compress(dtype: str, q, k, n_keys, vis_start, vis_len, keep_num, keep_de
         g = gdst[:, :k_keep]
         g = g.view(torch.int16).cpu().numpy().view(np.uint16) if dtype == "bf16" else g.cpu().numpy()
     return scores, kept.cpu().numpy()[:, :k_keep], g
+
+
+def run_commit(caches, dtype: str, prefix_len, n_tree: int, path, accept_len):
+    """caches: list of numpy [B,Hkv,s_max,D]; returns (list of committed numpy caches as raw bit views, new_len)."""
+    B, Hkv, s_max, D = caches[0].shape
+    desc = dream.attn_desc(B, 1, Hkv, D, DT[dtype], s_max)
+    dev = [dream.to_device(c, dtype) for c in caches]
+    pl = dream.to_device(np.ascontiguousarray(prefix_len, dtype=np.int32))
+    pth = dream.to_device(np.ascontiguousarray(path, dtype=np.int32))
+    al = dream.to_device(np.ascontiguousarray(accept_len, dtype=np.int32))
+    new_len = torch.full((B,), -7, dtype=torch.int32, device="cuda")
+    dream.dream_kv_commit(desc, dev, pl, n_tree, pth, al, new_len)
+    torch.cuda.synchronize()
+    view = torch.int32 if dtype == "f32" else torch.int16
+    return [t.view(view).cpu().numpy() for t in dev], new_len.cpu().numpy()

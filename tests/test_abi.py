@@ -113,3 +113,28 @@ def test_launch_plans_of_the_paper_shapes(lib):
     assert f32.startswith("attn_f32_kernel")
     with pytest.raises(dream.DreamError):
         dream.dream_attn_plan_describe(dream.attn_desc(1, 32, 32, 96, dream.BF16, 764), 60, 764)
+
+
+def test_kv_commit_argument_errors(lib):
+    """Host-side checks of dream_kv_commit return before any launch."""
+    import ctypes as C
+    desc = dream.attn_desc(1, 4, 4, 128, dream.BF16, 100)
+    ptrs = (C.c_void_p * 1)(0x1000)
+    fake = C.c_void_p(0x2000)
+
+    def call(d=desc, caches=ptrs, n=1, pl=fake, n_tree=8, path=fake, stride=7, alen=fake, out=None):
+        return lib.dream_kv_commit(C.byref(d), caches, C.c_int32(n), pl, C.c_int32(n_tree), path, C.c_int32(stride), alen,
+                                   out, None)
+    assert call(caches=None) == -1
+    assert call(n=0) == -1
+    assert call(n_tree=0) == -1
+    assert call(n_tree=101) == -1                  # the tree rows must fit the cache
+    assert call(stride=0) == -1
+    assert call(out=fake) == -1                    # aliases prefix_len
+    assert "alias" in dream.dream_last_error()
+    assert call(caches=(C.c_void_p * 1)(0x1008)) == -1   # not 16-byte aligned
+    assert call(caches=(C.c_void_p * 1)(None)) == -1
+    wide = dream.attn_desc(1, 4, 4, 1024, dream.F32, 1000)   # 4 KB rows: 64 of them exceed 64 KB
+    assert call(d=wide, n_tree=64, stride=64) == -2
+    odd = dream.attn_desc(1, 4, 4, 60, dream.BF16, 100)      # 120-byte rows
+    assert call(d=odd) == -2
