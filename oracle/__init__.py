@@ -182,3 +182,6 @@ def kv_commit(cache, dtype: str, prefix_len, n_tree: int, path, accept_len):
     if rc != 0:
         raise ValueError("kv_commit: path entry or length out of range")
     return cache, new_len
+
+
+from .tree_build import expand_level, finalize_tree, build_tree  # noqa: E402,F401  (float64 numpy, same rules as the C part)
