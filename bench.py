@@ -227,7 +227,8 @@ def main() -> int:
     }
 
     out["read_ceiling"] = read_ceiling(torch, dream, bytes_launch, L)
-    out["next_rows"] = {"kv_commit": kv_commit_leg(torch, dream, desc, vk + vv, prefix_len, T, accept_path, accept_len, cfg)}
+    out["next_rows"] = {"tree_build": tree_build_leg(torch, dream, di, cfg),
+                        "kv_commit": kv_commit_leg(torch, dream, desc, vk + vv, prefix_len, T, accept_path, accept_len, cfg)}
     out["streaming_regime"] = streaming_regime(torch, dream, di, cfg)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(cfg, L, tokens_per_step)
@@ -268,6 +269,58 @@ def read_ceiling(torch, dream, bytes_launch, L):
     gbs = n / (us * 1e-6) / 1e9
     return {"kernel": "stream_read_kernel (16-byte loads, no writes)", "bytes_per_launch": n, "launch_us": round(us, 3),
             "achieved": round(gbs, 1), "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4)}
+
+
+def tree_build_leg(torch, dream, di, cfg):
+    """The step before verification (not part of `value`): the draft tree of the benchmarked shape is grown
+    level by level (root top-10, then the 10 best candidates of a level expand 10 children each: 60 nodes of
+    at most 510 candidates at depth 6) from synthetic draft logits already resident in HBM: `depth`
+    dream_tree_expand_level calls and one dream_tree_finalize, replayed as one HIP graph."""
+    B, V, depth, k = cfg.batch, cfg.vocab, cfg.depth, 10
+    budget = cfg.n_tree - 1
+    dev = "cuda"
+    levels = []
+    for lv in range(depth):
+        F = 1 if lv == 0 else k
+        lg, cum = di.draft_level_inputs(B, F, V, "bf16", cfg.seed, level=lv)
+        levels.append((dream.to_device(lg, "bf16"), dream.to_device(cum), F,
+                       torch.empty(B, F, k, dtype=torch.int32, device=dev), torch.empty(B, F, k, dtype=torch.float32, device=dev),
+                       torch.empty(B, min(k, F * k), dtype=torch.int32, device=dev)))
+    ws = dream.alloc_workspace(dream.dream_tree_expand_workspace(B, k, V, k))
+    n_pool = 1 + k + (depth - 1) * k * k
+    pool_score = torch.randn(B, n_pool, device=dev).abs().neg().cumsum(1)    # decreasing scores: any ranking works for timing
+    pool_parent = torch.arange(-1, n_pool - 1, dtype=torch.int32, device=dev).clamp(min=0).repeat(B, 1)
+    pool_parent[:, 0] = -1
+    pool_token = torch.randint(0, V, (B, n_pool), dtype=torch.int32, device=dev)
+    T = 1 + min(budget, n_pool - 1)
+    tp, tt, ti = (torch.empty(B, T, dtype=torch.int32, device=dev) for _ in range(3))
+
+    def run():
+        for lg, cum, F, tok, sc, nxt in levels:
+            dream.dream_tree_expand_level(lg, dream.BF16, B, F, V, cum, k, tok, sc, nxt, ws)
+        dream.dream_tree_finalize(pool_score, pool_parent, pool_token, B, n_pool, budget, tp, tt, ti)
+    run()
+    torch.cuda.synchronize()
+    stream = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=stream):
+        for _ in range(4):
+            run()
+    reps = 20
+    with torch.cuda.stream(stream):
+        for _ in range(3):
+            g.replay()
+        stream.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            g.replay()
+        e1.record()
+        stream.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / (reps * 4)
+    nbytes = sum(lv[0].numel() * 2 for lv in levels)
+    return {"levels": depth, "k": k, "budget": budget, "launches": 2 * depth + 1, "us": round(us, 2), "logit_bytes": nbytes,
+            "achieved_GBs": round(nbytes / (us * 1e-6) / 1e9, 1), "bound": "hbm (launch latency at one sequence)"}
 
 
 def kv_commit_leg(torch, dream, desc, caches, prefix_len, T, accept_path, accept_len, cfg):

@@ -28,6 +28,7 @@ BASE_SEED = 20250519
 STREAM_Q, STREAM_K, STREAM_V, STREAM_TREE, STREAM_TOKEN, STREAM_LOGITS = 1, 2, 3, 4, 5, 6
 STREAM_XQ, STREAM_XK, STREAM_XV, STREAM_PREFILL_Q, STREAM_ROWS, STREAM_SCORES = 7, 8, 9, 10, 11, 12
 STREAM_PLANT = 13
+STREAM_DRAFT_LOGITS, STREAM_CUM = 14, 15
 
 
 @dataclass(frozen=True)
@@ -391,3 +392,17 @@ def accept_inputs(cfg: Config, plant_depths: Optional[Sequence[int]] = None, see
         ends.append(end)
     return (np.stack(logits), np.stack(tokens).astype(np.int32),
             np.ascontiguousarray(parents, dtype=np.int32), np.asarray(ends, dtype=np.int32))
+
+
+def draft_level_inputs(batch: int, n_frontier: int, vocab: int, dtype: str, seed: int, level: int = 0,
+                       spread: float = 3.0) -> Tuple[np.ndarray, np.ndarray]:
+    """Draft logits [B,F,V] (N(0, spread^2), rounded once to `dtype`) of the frontier nodes of one tree level
+    and their cumulative scores [B,F] float32 (negative, decreasing along the frontier as after a ranking)."""
+    logits = normal((batch, n_frontier, vocab), "f32", seed, STREAM_DRAFT_LOGITS, level) * np.float32(spread)
+    if dtype == "bf16":
+        logits = f32_to_bf16_bits(logits)
+    g = rng(seed, STREAM_CUM, level)
+    cum = -np.sort(g.uniform(0.0, 3.0 * (level + 1), size=(batch, n_frontier)), axis=1).astype(np.float32)
+    if level == 0:
+        cum[:] = 0.0
+    return logits, np.ascontiguousarray(cum)

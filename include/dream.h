@@ -58,6 +58,8 @@ typedef enum {
 #define DREAM_WORKSPACE_HEADER_BYTES 65536
 #define DREAM_MAX_TREE 64       /* tree nodes per sequence handled by the attention calls      */
 #define DREAM_MAX_TREE_ACCEPT 1024 /* tree nodes per sequence handled by dream_accept_path     */
+#define DREAM_MAX_TREE_WIDTH 16     /* children per node / frontier rows of one tree-expansion level */
+#define DREAM_MAX_POOL 1024         /* candidates (root included) dream_tree_finalize ranks */
 #define DREAM_MAX_VISUAL 16384  /* visual tokens per sequence handled by dream_visual_compress */
 
 /* Attention geometry shared by the three attention-shaped calls. */
@@ -186,6 +188,38 @@ int dream_kv_commit(const dream_attn_desc *desc, void *const *caches_host, int32
                     const int32_t *prefix_len, int32_t n_tree, const int32_t *accept_path,
                     int32_t path_stride, const int32_t *accept_len, int32_t *prefix_len_out,
                     void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Draft-tree construction (Section 3.1, last paragraph: width-k tree expansion with the top-k
+ * reordering of EAGLE-2; Section 4: k children per node, a depth, a budget of drafted tokens).
+ * The draft model runs between the levels, so a level is one call:
+ *   logits        [B, F, V] draft logits of the F <= DREAM_MAX_TREE_WIDTH frontier nodes (f32 or bf16)
+ *   cum_in        [B, F] float32   score (log-probability of the whole path) of each frontier node
+ *   k             children per node, 1 <= k <= min(DREAM_MAX_TREE_WIDTH, V)
+ *   cand_token    [B, F, k] int32  the k most probable tokens of each row, most probable first;
+ *                                  equal logits resolve toward the lower token (the logits themselves
+ *                                  are compared, so this is exact)
+ *   cand_score    [B, F, k] float32  cum_in + logit - logsumexp(row)
+ *   next_frontier [B, min(k, F*k)] int32  flat indices f*k + j of the best candidates of the level by
+ *                                  cand_score (float32), best first, equal scores toward the lower index
+ * dream_tree_finalize ranks a pool of candidates gathered over all levels:
+ *   pool_score/pool_parent/pool_token [B, n_pool]; entry 0 is the root (its score is ignored), entry
+ *   i > 0 has parent pool_parent[b,i] < i; n_pool <= DREAM_MAX_POOL
+ *   keeps the root and the min(budget, n_pool-1) best other entries (score descending, equal scores
+ *   toward the lower index) and lists them in pool order, so a parent precedes its children:
+ *   tree_parent [B, T] (-1 for the root; -2 if the parent of a kept entry was dropped, which cannot
+ *   happen when scores do not increase along a path), tree_token [B, T], tree_pool_index [B, T],
+ *   T = 1 + min(budget, n_pool-1), also written to *n_tree_host (nullable, HOST).
+ * ------------------------------------------------------------------------------------------- */
+size_t dream_tree_expand_workspace(int32_t batch, int32_t n_frontier, int32_t vocab, int32_t k);
+int dream_tree_expand_level(const void *logits, int32_t logits_dtype, int32_t batch, int32_t n_frontier,
+                            int32_t vocab, const float *cum_in, int32_t k, int32_t *cand_token,
+                            float *cand_score, int32_t *next_frontier, void *workspace,
+                            size_t workspace_bytes, void *stream);
+int dream_tree_finalize(const float *pool_score, const int32_t *pool_parent, const int32_t *pool_token,
+                        int32_t batch, int32_t n_pool, int32_t budget, int32_t *tree_parent,
+                        int32_t *tree_token, int32_t *tree_pool_index, int32_t *n_tree_host,
+                        void *stream);
 
 /* Host-side check of one parent array: parent_host[0] == -1 and 0 <= parent_host[i] < i.
  * Writes the maximum depth to *max_depth_out (nullable).  DREAM_OK or DREAM_ERR_INVALID_ARG. */

@@ -82,6 +82,7 @@ def build_tree(draft_logits, root_token: int, k: int, depth: int, budget: int):
     (score, parent, token, level arrays) and the finalized tree."""
     pool_score, pool_parent, pool_token, pool_level = [0.0], [-1], [int(root_token)], [0]
     frontier = [0]
+    frontier_gap = np.inf   # smallest distance between a score that made a frontier and the best one that did not
     for level in range(depth):
         paths = []
         for f in frontier:
@@ -100,9 +101,12 @@ def build_tree(draft_logits, root_token: int, k: int, depth: int, budget: int):
                 pool_parent.append(f)
                 pool_token.append(int(tok[0, fi, j]))
                 pool_level.append(level + 1)
+        ranked = np.sort(score[0].reshape(-1))[::-1]
+        if ranked.shape[0] > len(nxt[0]):
+            frontier_gap = min(frontier_gap, float(ranked[len(nxt[0]) - 1] - ranked[len(nxt[0])]))
         frontier = [base + int(i) for i in nxt[0]]
     ps, pp, pt = (np.asarray(pool_score)[None], np.asarray(pool_parent, dtype=np.int32)[None],
                   np.asarray(pool_token, dtype=np.int32)[None])
     T, parent, token, pidx = finalize_tree(ps, pp, pt, budget)
     return {"pool_score": ps[0], "pool_parent": pp[0], "pool_token": pt[0], "pool_level": np.asarray(pool_level),
-            "n_tree": T, "parent": parent[0], "token": token[0], "pool_index": pidx[0]}
+            "n_tree": T, "parent": parent[0], "token": token[0], "pool_index": pidx[0], "frontier_gap": frontier_gap}

@@ -23,6 +23,7 @@ EXPORTED_SYMBOLS = (
     "dream_visual_compress", "dream_accept_path_workspace", "dream_accept_path",
     "dream_tree_validate_host", "dream_last_error", "dream_set_kv_splits", "dream_set_q_tiles",
     "dream_attn_plan_describe", "dream_stream_read", "dream_kv_commit",
+    "dream_tree_expand_workspace", "dream_tree_expand_level", "dream_tree_finalize",
 )
 
 
@@ -60,7 +61,7 @@ def load() -> C.CDLL:
         for name in EXPORTED_SYMBOLS:
             getattr(lib, name)
         for name in ("dream_tree_verify_attn_workspace", "dream_draft_xattn_workspace",
-                     "dream_visual_compress_workspace", "dream_accept_path_workspace"):
+                     "dream_visual_compress_workspace", "dream_accept_path_workspace", "dream_tree_expand_workspace"):
             getattr(lib, name).restype = C.c_size_t
         lib.dream_last_error.restype = C.c_char_p
         lib.dream_set_kv_splits.restype = None
@@ -196,6 +197,29 @@ def dream_kv_commit(desc: AttnDesc, caches: Sequence[torch.Tensor], prefix_len: 
     _check(load().dream_kv_commit(C.byref(desc), ptrs, C.c_int32(len(caches)), _dev(prefix_len), C.c_int32(n_tree),
                                   _dev(accept_path), C.c_int32(accept_path.shape[-1]), _dev(accept_len),
                                   _dev(prefix_len_out), _stream(stream)))
+
+
+def dream_tree_expand_workspace(batch: int, n_frontier: int, vocab: int, k: int) -> int:
+    return int(load().dream_tree_expand_workspace(C.c_int32(batch), C.c_int32(n_frontier), C.c_int32(vocab), C.c_int32(k)))
+
+
+def dream_tree_expand_level(logits: torch.Tensor, logits_dtype: int, batch: int, n_frontier: int, vocab: int,
+                            cum_in: torch.Tensor, k: int, cand_token: torch.Tensor, cand_score: torch.Tensor,
+                            next_frontier: torch.Tensor, workspace: torch.Tensor, stream=None) -> None:
+    _check(load().dream_tree_expand_level(_dev(logits), C.c_int32(logits_dtype), C.c_int32(batch), C.c_int32(n_frontier),
+                                          C.c_int32(vocab), _dev(cum_in), C.c_int32(k), _dev(cand_token), _dev(cand_score),
+                                          _dev(next_frontier), _dev(workspace),
+                                          C.c_size_t(workspace.numel() * workspace.element_size()), _stream(stream)))
+
+
+def dream_tree_finalize(pool_score: torch.Tensor, pool_parent: torch.Tensor, pool_token: torch.Tensor, batch: int, n_pool: int,
+                        budget: int, tree_parent: torch.Tensor, tree_token: torch.Tensor, tree_pool_index: torch.Tensor,
+                        stream=None) -> int:
+    n_tree = C.c_int32(0)
+    _check(load().dream_tree_finalize(_dev(pool_score), _dev(pool_parent), _dev(pool_token), C.c_int32(batch), C.c_int32(n_pool),
+                                      C.c_int32(budget), _dev(tree_parent), _dev(tree_token), _dev(tree_pool_index),
+                                      C.byref(n_tree), _stream(stream)))
+    return int(n_tree.value)
 
 
 def dream_tree_validate_host(parent_host: np.ndarray) -> int:

@@ -127,3 +127,31 @@ def run_commit(caches, dtype: str, prefix_len, n_tree: int, path, accept_len):
     torch.cuda.synchronize()
     view = torch.int32 if dtype == "f32" else torch.int16
     return [t.view(view).cpu().numpy() for t in dev], new_len.cpu().numpy()
+
+
+def run_expand(logits: np.ndarray, dtype: str, cum: np.ndarray, k: int):
+    """Returns (cand_token [B,F,k], cand_score [B,F,k] float32, next_frontier [B,min(k,F*k)])."""
+    B, F, V = logits.shape
+    lg = dream.to_device(logits, dtype)
+    cm = dream.to_device(np.ascontiguousarray(cum, dtype=np.float32))
+    kf = min(k, F * k)
+    tok = torch.full((B, F, k), -7, dtype=torch.int32, device="cuda")
+    sc = torch.full((B, F, k), float("nan"), dtype=torch.float32, device="cuda")
+    nxt = torch.full((B, kf), -7, dtype=torch.int32, device="cuda")
+    ws = dream.alloc_workspace(dream.dream_tree_expand_workspace(B, F, V, k))
+    dream.dream_tree_expand_level(lg, DT[dtype], B, F, V, cm, k, tok, sc, nxt, ws)
+    torch.cuda.synchronize()
+    return tok.cpu().numpy(), sc.cpu().numpy(), nxt.cpu().numpy()
+
+
+def run_finalize(pool_score: np.ndarray, pool_parent: np.ndarray, pool_token: np.ndarray, budget: int):
+    B, N = pool_score.shape
+    T = 1 + min(budget, N - 1)
+    par = torch.full((B, T), -7, dtype=torch.int32, device="cuda")
+    tok = torch.full((B, T), -7, dtype=torch.int32, device="cuda")
+    pidx = torch.full((B, T), -7, dtype=torch.int32, device="cuda")
+    n_tree = dream.dream_tree_finalize(dream.to_device(np.ascontiguousarray(pool_score, dtype=np.float32)),
+                                       dream.to_device(np.ascontiguousarray(pool_parent, dtype=np.int32)),
+                                       dream.to_device(np.ascontiguousarray(pool_token, dtype=np.int32)), B, N, budget, par, tok, pidx)
+    torch.cuda.synchronize()
+    return n_tree, par.cpu().numpy(), tok.cpu().numpy(), pidx.cpu().numpy()

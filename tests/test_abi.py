@@ -138,3 +138,28 @@ def test_kv_commit_argument_errors(lib):
     assert call(d=wide, n_tree=64, stride=64) == -2
     odd = dream.attn_desc(1, 4, 4, 60, dream.BF16, 100)      # 120-byte rows
     assert call(d=odd) == -2
+
+
+def test_tree_build_argument_errors(lib):
+    """Host-side checks of the tree-construction entry points return before any launch."""
+    import ctypes as C
+    fake = C.c_void_p(0x1000)
+
+    def expand(logits=fake, dt=dream.BF16, B=1, F=4, V=32000, cum=fake, k=4, tok=fake, sc=fake, nxt=fake, ws=fake, nb=1 << 30):
+        return lib.dream_tree_expand_level(logits, C.c_int32(dt), C.c_int32(B), C.c_int32(F), C.c_int32(V), cum, C.c_int32(k), tok, sc,
+                                           nxt, ws, C.c_size_t(nb), None)
+    assert expand(logits=None) == -1 and expand(cum=None) == -1 and expand(nxt=None) == -1
+    assert expand(dt=7) == -1
+    assert expand(F=0) == -1 and expand(F=17) == -1
+    assert expand(k=0) == -1 and expand(k=17) == -1 and expand(V=3, k=4) == -1
+    assert expand(B=0) == -1 and expand(B=5000, F=16) == -1
+    need = dream.dream_tree_expand_workspace(1, 4, 32000, 4)
+    assert need > 65536 and expand(nb=need - 1) == -3 and expand(ws=None) == -3
+    assert dream.dream_tree_expand_workspace(1, 4, 262144, 4) > need
+    assert dream.dream_tree_expand_workspace(2, 4, 32000, 4) > need
+
+    def finalize(score=fake, parent=fake, token=fake, B=1, N=85, budget=32, tp=fake, tt=fake, ti=fake):
+        n = C.c_int32(-1)
+        return lib.dream_tree_finalize(score, parent, token, C.c_int32(B), C.c_int32(N), C.c_int32(budget), tp, tt, ti, C.byref(n), None), n.value
+    assert finalize(score=None)[0] == -1 and finalize(ti=None)[0] == -1
+    assert finalize(N=0)[0] == -1 and finalize(N=1025)[0] == -1 and finalize(budget=-1)[0] == -1 and finalize(B=0)[0] == -1
