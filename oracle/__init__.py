@@ -43,6 +43,8 @@ def lib() -> C.CDLL:
         _lib.oracle_tree_attn.restype = C.c_int
         _lib.oracle_visual_scores.restype = C.c_int
         _lib.oracle_accept_path.restype = C.c_int
+        _lib.oracle_attention_entropy.restype = C.c_int
+        _lib.oracle_kv_commit.restype = C.c_int
         _lib.oracle_get_threads.restype = C.c_int
         _lib.oracle_hw_threads.restype = C.c_int
     return _lib
@@ -182,6 +184,21 @@ def kv_commit(cache, dtype: str, prefix_len, n_tree: int, path, accept_len):
     if rc != 0:
         raise ValueError("kv_commit: path entry or length out of range")
     return cache, new_len
+
+
+def attention_entropy(q, k, dtype: str, q_pos=None, scale: Optional[float] = None):
+    """q [B,Nq,Hq,D], k [B,Hkv,s_max,D] -> (row_entropy [B,Hq,Nq] f64, ae [B] f64), Eq. 2."""
+    q, k = _check(q, dtype), _check(k, dtype)
+    B, n_q, Hq, D = q.shape
+    _, Hkv, s_max, _ = k.shape
+    qp = None if q_pos is None else _i32(q_pos).reshape(B, n_q)
+    scale = 1.0 / np.sqrt(D) if scale is None else scale
+    row = np.zeros((B, Hq, n_q), dtype=np.float64)
+    ae = np.zeros(B, dtype=np.float64)
+    rc = lib().oracle_attention_entropy(_ptr(q), _ptr(qp), C.c_int(n_q), _ptr(k), C.c_int(_DT[dtype]), C.c_int(B), C.c_int(Hq),
+                                        C.c_int(Hkv), C.c_int(D), C.c_int64(s_max), C.c_double(scale), _ptr(row), _ptr(ae))
+    assert rc == 0
+    return row, ae
 
 
 from .tree_build import expand_level, finalize_tree, build_tree  # noqa: E402,F401  (float64 numpy, same rules as the C part)

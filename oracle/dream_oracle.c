@@ -27,6 +27,9 @@
  *       everything after the first mismatch on a path is discarded; the target's own token at
  *       the last accepted node is the bonus token (Section 4: up to depth + 1 tokens a round).
  *
+ *   oracle_attention_entropy
+ *       the token-level attention entropy of a layer, Eq. 2 of Section 3.2: minus the sum of
+ *       A log A over each row of the causal attention matrix, averaged over rows and heads.
  *   oracle_kv_commit
  *       what Section 2.1 says happens after verification: the tokens after the first rejection
  *       are discarded and decoding continues from the accepted prefix; with KV caching
@@ -38,7 +41,8 @@
  * dense-mask brute force, mask-leak detectors, exhaustive subset search for top-k, root-to-leaf
  * path enumeration and planted paths/ties for acceptance; for the commit, hand-written row markers
  * (including a path whose destination rows are other entries' source rows), the no-op chain path and
- * "attention over the committed cache == tree-masked attention of the accepted node".  No function
+ * "attention over the committed cache == tree-masked attention of the accepted node"; for the entropy, the closed form log(i+1) of uniform rows, the one-hot limit, and the identity
+ * H = LSE - scale q.(attention output with V := K) evaluated through the attention oracle.  No function
  * here is unpinned.
  *
  * Tensor layouts (C order): q [B,Tq,Hq,D]; k,v [B,Hkv,s_max,D]; logits [B,T,V].
@@ -375,5 +379,59 @@ int oracle_kv_commit(void *cache, int dtype, int B, int Hkv, int64_t s_max, int 
             new_len[b] = prefix_len[b] + accept_len[b] + 1;
     }
     free(old_rows);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------------------------ */
+/* Attention entropy, Eq. 2 (Section 3.2).  Row r of q sits at position pos = q_pos ?          */
+/* q_pos[b,r] : r and attends keys 0..pos; A = softmax_row(scale q k^T).                       */
+/* row_entropy[b,h,r] = - sum_j A_j log A_j (natural log; A_j = 0 contributes 0);              */
+/* ae[b] = mean over heads and rows.                                                           */
+/* ------------------------------------------------------------------------------------------ */
+int oracle_attention_entropy(const void *q, const int32_t *q_pos, int n_q, const void *k, int dtype,
+                             int B, int Hq, int Hkv, int D, int64_t s_max, double scale,
+                             double *row_entropy, double *ae)
+{
+    if (Hkv <= 0 || Hq % Hkv != 0)
+        return -1;
+    int G = Hq / Hkv;
+    int64_t nbh = (int64_t)B * Hq;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(g_threads)
+    for (int64_t bh = 0; bh < nbh; bh++) {
+        int b = (int)(bh / Hq), h = (int)(bh % Hq);
+        int64_t kv_base = ((int64_t)b * Hkv + h / G) * s_max * D;
+        for (int r = 0; r < n_q; r++) {
+            int pos = q_pos ? q_pos[(int64_t)b * n_q + r] : r;
+            int n_keys = pos + 1;
+            int64_t q_row = (((int64_t)b * n_q + r) * Hq + h) * D;
+            double *s = (double *)malloc(sizeof(double) * (size_t)n_keys);
+            double m = -INFINITY;
+            for (int j = 0; j < n_keys; j++) {
+                double dot = 0.0;
+                for (int d = 0; d < D; d++)
+                    dot += load_as_double(q, dtype, q_row + d) * load_as_double(k, dtype, kv_base + (int64_t)j * D + d);
+                s[j] = scale * dot;
+                if (s[j] > m)
+                    m = s[j];
+            }
+            double denom = 0.0;
+            for (int j = 0; j < n_keys; j++)
+                denom += exp(s[j] - m);
+            double H = 0.0;
+            for (int j = 0; j < n_keys; j++) {
+                double a = exp(s[j] - m) / denom;
+                if (a > 0.0)
+                    H -= a * log(a);
+            }
+            row_entropy[bh * n_q + r] = H;
+            free(s);
+        }
+    }
+    for (int b = 0; b < B; b++) {
+        double t = 0.0;
+        for (int64_t i = 0; i < (int64_t)Hq * n_q; i++)
+            t += row_entropy[(int64_t)b * Hq * n_q + i];
+        ae[b] = t / ((double)Hq * n_q);
+    }
     return 0;
 }
