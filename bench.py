@@ -227,7 +227,8 @@ def main() -> int:
     }
 
     out["read_ceiling"] = read_ceiling(torch, dream, bytes_launch, L)
-    out["next_rows"] = {"tree_build": tree_build_leg(torch, dream, di, cfg),
+    out["next_rows"] = {"attention_entropy": entropy_leg(torch, dream, desc, pq, vk[L - 1], P),
+                        "tree_build": tree_build_leg(torch, dream, di, cfg),
                         "kv_commit": kv_commit_leg(torch, dream, desc, vk + vv, prefix_len, T, accept_path, accept_len, cfg)}
     out["streaming_regime"] = streaming_regime(torch, dream, di, cfg)
     if not args.no_cpu:
@@ -269,6 +270,35 @@ def read_ceiling(torch, dream, bytes_launch, L):
     gbs = n / (us * 1e-6) / 1e9
     return {"kernel": "stream_read_kernel (16-byte loads, no writes)", "bytes_per_launch": n, "launch_us": round(us, 3),
             "achieved": round(gbs, 1), "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4)}
+
+
+def entropy_leg(torch, dream, desc, pq, k_cache, P):
+    """Eq. 2's attention entropy of one layer over all prefill rows (not part of `value`): the log-sum-exp pass
+    with one more running sum plus a small reduction, 4 calls per graph."""
+    B, Hq = pq.shape[0], pq.shape[2]
+    row = torch.empty(B, Hq, P, dtype=torch.float32, device="cuda")
+    ae = torch.empty(B, dtype=torch.float32, device="cuda")
+    ws = dream.alloc_workspace(dream.dream_attention_entropy_workspace(desc, P))
+    dream.dream_attention_entropy(desc, pq, None, P, k_cache, P, row, ae, ws)
+    torch.cuda.synchronize()
+    stream = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=stream):
+        for _ in range(4):
+            dream.dream_attention_entropy(desc, pq, None, P, k_cache, P, row, ae, ws)
+    reps = 20
+    with torch.cuda.stream(stream):
+        for _ in range(3):
+            g.replay()
+        stream.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            g.replay()
+        e1.record()
+        stream.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / (reps * 4)
+    return {"rows": P, "us": round(us, 2), "ae": [round(float(x), 4) for x in ae.cpu().tolist()[:4]]}
 
 
 def tree_build_leg(torch, dream, di, cfg):

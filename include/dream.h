@@ -167,6 +167,20 @@ int dream_accept_path(const void *logits, int32_t logits_dtype, int32_t batch, i
                       size_t workspace_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * Attention entropy of a layer, Eq. 2 (Section 3.2): row r of q sits at position pos_r (q_pos[b,r],
+ * or r when q_pos is NULL) and attends keys 0..pos_r with A = softmax_row(scale q k^T);
+ *   row_entropy[b, h, r] = - sum_j A_j log A_j   (natural logarithm; nullable output)
+ *   ae[b]                = mean of row_entropy over heads and rows   ([B] float32)
+ * q [B, n_q, Hq, D] and k_cache [B, Hkv, s_max, D] of desc->dtype, n_keys live key rows.  The
+ * attention matrix is never stored: one streaming pass keeps a running (max, sum, score-weighted sum)
+ * per row, as the log-sum-exp pass of dream_visual_compress does.
+ * ------------------------------------------------------------------------------------------- */
+size_t dream_attention_entropy_workspace(const dream_attn_desc *desc, int32_t n_q);
+int dream_attention_entropy(const dream_attn_desc *desc, const void *q, const int32_t *q_pos, int32_t n_q,
+                            const void *k_cache, int32_t n_keys, float *row_entropy, float *ae,
+                            void *workspace, size_t workspace_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
  * KV-cache commit of the accepted path (Section 2.1: the tokens after the first rejected one are
  * discarded and decoding continues from the accepted prefix; Section 4: KV caching).
  *   caches_host    HOST array of n_caches DEVICE pointers, each a cache [B, Hkv, s_max, D] of

@@ -24,6 +24,7 @@ EXPORTED_SYMBOLS = (
     "dream_tree_validate_host", "dream_last_error", "dream_set_kv_splits", "dream_set_q_tiles",
     "dream_attn_plan_describe", "dream_stream_read", "dream_kv_commit",
     "dream_tree_expand_workspace", "dream_tree_expand_level", "dream_tree_finalize",
+    "dream_attention_entropy_workspace", "dream_attention_entropy",
 )
 
 
@@ -61,7 +62,8 @@ def load() -> C.CDLL:
         for name in EXPORTED_SYMBOLS:
             getattr(lib, name)
         for name in ("dream_tree_verify_attn_workspace", "dream_draft_xattn_workspace",
-                     "dream_visual_compress_workspace", "dream_accept_path_workspace", "dream_tree_expand_workspace"):
+                     "dream_visual_compress_workspace", "dream_accept_path_workspace", "dream_tree_expand_workspace",
+                     "dream_attention_entropy_workspace"):
             getattr(lib, name).restype = C.c_size_t
         lib.dream_last_error.restype = C.c_char_p
         lib.dream_set_kv_splits.restype = None
@@ -197,6 +199,16 @@ def dream_kv_commit(desc: AttnDesc, caches: Sequence[torch.Tensor], prefix_len: 
     _check(load().dream_kv_commit(C.byref(desc), ptrs, C.c_int32(len(caches)), _dev(prefix_len), C.c_int32(n_tree),
                                   _dev(accept_path), C.c_int32(accept_path.shape[-1]), _dev(accept_len),
                                   _dev(prefix_len_out), _stream(stream)))
+
+
+def dream_attention_entropy_workspace(desc: AttnDesc, n_q: int) -> int:
+    return int(load().dream_attention_entropy_workspace(C.byref(desc), C.c_int32(n_q)))
+
+
+def dream_attention_entropy(desc: AttnDesc, q, q_pos, n_q: int, k_cache, n_keys: int, row_entropy, ae, workspace, stream=None) -> None:
+    _check(load().dream_attention_entropy(C.byref(desc), _dev(q), _dev(q_pos), C.c_int32(n_q), _dev(k_cache), C.c_int32(n_keys),
+                                          _dev(row_entropy), _dev(ae), _dev(workspace),
+                                          C.c_size_t(workspace.numel() * workspace.element_size()), _stream(stream)))
 
 
 def dream_tree_expand_workspace(batch: int, n_frontier: int, vocab: int, k: int) -> int:

@@ -24,6 +24,7 @@ struct ScoreArgs {
     float *lse2;   // [ns1, B, Hq, n_q_pad]  log2-domain log-sum-exp of each row over the keys of split s (-inf: none)
     float *part;   // [B, Hq, ns2, vis_len]  column sums per head and row split
     int32_t n_q, n_q_pad, n_keys, n_q_heads, n_kv_heads, vis_start, vis_len;
+    float *ent_part;    // [ns1, B, Hq, n_q_pad]  expected score of the row under its attention weights, per split (entropy only)
     int32_t ns1, ns2;   // splits of the streamed axis: keys in pass 1, query rows in pass 2
     int64_t lse_split_stride;   // B * Hq * n_q_pad
     int64_t s_max;
@@ -35,7 +36,10 @@ struct ScoreArgs {
 // which writes a partial log-sum-exp that pass 2 combines.  All 256 threads stream K in 32-key tiles (two tiles ahead in registers, two LDS stages,
 // one barrier per tile); scores are formed transposed (lane = query column), so a lane keeps a private running
 // (max, sum) over its own key rows and the four row groups are combined once at the end.
-template <int D>
+// With ENT the kernel also keeps t = sum_j 2^(x_j - m) x_j, so that the expected score sum_j A_j x_j = t / l of
+// the row is known and the row's entropy -sum A log A = LSE - sum A_j s_j (Eq. 2, Section 3.2) needs no
+// second pass.
+template <int D, bool ENT>
 __global__ __launch_bounds__(256) void scores_lse_bf16_kernel(ScoreArgs a)
 {
     constexpr int NKS = D / 32, STR = D + 8, CH = 32 * D / 8 / 256;
@@ -80,7 +84,7 @@ __global__ __launch_bounds__(256) void scores_lse_bf16_kernel(ScoreArgs a)
         for (int ks = 0; ks < NKS; ks++)
             qf[ks] = *reinterpret_cast<const bf16x8 *>(qp + ks * 32);
     }
-    float m = -INFINITY, l = 0.0f;
+    float m = -INFINITY, l = 0.0f, tx = 0.0f;
     auto step = [&](int i, u32x4(&kr)[CH]) {
         uint16_t *st = lds[i & 1];
 #pragma unroll
@@ -114,11 +118,18 @@ __global__ __launch_bounds__(256) void scores_lse_bf16_kernel(ScoreArgs a)
         }
         const float m_new = fmaxf(m, mx);
         const float m_safe = (m_new == -INFINITY) ? 0.0f : m_new;
-        float sum = 0.0f;
+        float sum = 0.0f, xsum = 0.0f;
 #pragma unroll
-        for (int e = 0; e < 8; e++)
-            sum += __builtin_amdgcn_exp2f(x[e] - m_safe);
-        l = l * __builtin_amdgcn_exp2f(m - m_safe) + sum;
+        for (int e = 0; e < 8; e++) {
+            const float p = __builtin_amdgcn_exp2f(x[e] - m_safe);
+            sum += p;
+            if (ENT)
+                xsum += p * (x[e] == -INFINITY ? 0.0f : x[e]);
+        }
+        const float alpha = __builtin_amdgcn_exp2f(m - m_safe);
+        l = l * alpha + sum;
+        if (ENT)
+            tx = tx * alpha + xsum;
         m = m_new;
     };
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): only tile prefetches are counted inside the loop
@@ -134,11 +145,76 @@ __global__ __launch_bounds__(256) void scores_lse_bf16_kernel(ScoreArgs a)
     float mt = fmaxf(m, __shfl_xor(m, 16));
     mt = fmaxf(mt, __shfl_xor(mt, 32));
     const float ms = (mt == -INFINITY) ? 0.0f : mt;
-    float lw = l * __builtin_amdgcn_exp2f(m - ms);
+    const float wgt = __builtin_amdgcn_exp2f(m - ms);
+    float lw = l * wgt;
     lw += __shfl_xor(lw, 16);
     lw += __shfl_xor(lw, 32);
+    const int64_t o = split * a.lse_split_stride + ((int64_t)b * a.n_q_heads + h) * a.n_q_pad + row;
     if (g == 0 && valid)
-        a.lse2[split * a.lse_split_stride + ((int64_t)b * a.n_q_heads + h) * a.n_q_pad + row] = lw > 0.0f ? mt + log2f(lw) : -INFINITY;
+        a.lse2[o] = lw > 0.0f ? mt + log2f(lw) : -INFINITY;
+    if (ENT) {
+        float tw = tx * wgt;
+        tw += __shfl_xor(tw, 16);
+        tw += __shfl_xor(tw, 32);
+        if (g == 0 && valid)
+            a.ent_part[o] = lw > 0.0f ? tw / lw : 0.0f;
+    }
+}
+
+// Entropy of every row from pass 1's per-split (log-sum-exp, expected score) pairs (Eq. 2).  One thread per
+// (head, row); each workgroup also leaves the sum of its 256 entropies for entropy_mean_kernel, which adds the
+// workgroup sums of a sequence in index order, so the mean is reproducible.
+// log2_domain: bf16 path (scores in log2 units); otherwise natural units and a single split.
+__global__ __launch_bounds__(256) void entropy_rows_kernel(ScoreArgs a, int log2_domain, float *row_entropy, float *block_sum)
+{
+    __shared__ float s_part[4];
+    const int b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n_rows = a.n_q_heads * a.n_q;
+    const int i = blockIdx.x * 256 + tid;
+    float H = 0.0f;
+    if (i < n_rows) {
+        const int h = i / a.n_q, r = i - h * a.n_q;
+        const int64_t o = ((int64_t)b * a.n_q_heads + h) * a.n_q_pad + r;
+        if (log2_domain) {
+            float M = -INFINITY;
+            for (int s = 0; s < a.ns1; s++)
+                M = fmaxf(M, a.lse2[s * a.lse_split_stride + o]);
+            if (M != -INFINITY) {
+                float W = 0.0f, U = 0.0f;
+                for (int s = 0; s < a.ns1; s++) {
+                    const float w = __builtin_amdgcn_exp2f(a.lse2[s * a.lse_split_stride + o] - M);
+                    W += w;
+                    U += w * a.ent_part[s * a.lse_split_stride + o];
+                }
+                H = 0.6931471805599453f * ((M + log2f(W)) - U / W);
+            }
+        } else {
+            const float L = a.lse2[o];
+            H = L == INFINITY ? 0.0f : L - a.ent_part[o];
+        }
+        H = fmaxf(H, 0.0f);   // rounding can leave a tiny negative value for a one-hot row
+        if (row_entropy)
+            row_entropy[((int64_t)b * a.n_q_heads + h) * a.n_q + r] = H;
+    }
+    float acc = H;
+    for (int off = 32; off > 0; off >>= 1)
+        acc += __shfl_xor(acc, off);
+    if (lane == 0)
+        s_part[wave] = acc;
+    __syncthreads();
+    if (tid == 0)
+        block_sum[(int64_t)b * gridDim.x + blockIdx.x] = (s_part[0] + s_part[1]) + (s_part[2] + s_part[3]);
+}
+
+__global__ __launch_bounds__(64) void entropy_mean_kernel(const float *block_sum, int n_blocks, int n_rows, float *ae)
+{
+    const int b = blockIdx.x;
+    if (threadIdx.x == 0) {
+        float t = 0.0f;
+        for (int i = 0; i < n_blocks; i++)
+            t += block_sum[(int64_t)b * n_blocks + i];
+        ae[b] = t / (float)n_rows;
+    }
 }
 
 // Pass 2: column sums of the probabilities.  One workgroup per (64 visual keys, head, sequence, row split); wave w keeps
@@ -274,7 +350,7 @@ __global__ __launch_bounds__(256) void scores_colsum_bf16_kernel(ScoreArgs a)
 __global__ __launch_bounds__(256) void scores_lse_f32_kernel(ScoreArgs a, int D)
 {
     __shared__ float sq[256];
-    __shared__ float red_m[4], red_l[4];
+    __shared__ float red_m[4], red_l[4], red_t[4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int row = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int kvh = h / (a.n_q_heads / a.n_kv_heads);
@@ -284,7 +360,7 @@ __global__ __launch_bounds__(256) void scores_lse_f32_kernel(ScoreArgs a, int D)
     if (tid < D)
         sq[tid] = q[tid];
     __syncthreads();
-    float m = -INFINITY, l = 0.0f;
+    float m = -INFINITY, l = 0.0f, tx = 0.0f;   // tx = sum_j exp(x_j - m) x_j (used for the entropy only)
     const int lim = min(pos + 1, a.n_keys);
     for (int key = tid; key < lim; key += 256) {
         const float *kr = kb + (int64_t)key * D;
@@ -293,28 +369,37 @@ __global__ __launch_bounds__(256) void scores_lse_f32_kernel(ScoreArgs a, int D)
             dot += sq[d] * kr[d];
         float x = dot * a.scale;
         float mn = fmaxf(m, x);
-        l = l * expf(m - mn) + expf(x - mn);
+        const float al = expf(m - mn), p = expf(x - mn);
+        l = l * al + p;
+        tx = tx * al + p * x;
         m = mn;
     }
     for (int off = 32; off > 0; off >>= 1) {
-        float om = __shfl_xor(m, off), ol = __shfl_xor(l, off);
+        float om = __shfl_xor(m, off), ol = __shfl_xor(l, off), ot = __shfl_xor(tx, off);
         float mn = fmaxf(m, om);
         float ms = (mn == -INFINITY) ? 0.0f : mn;
         l = l * expf(m - ms) + ol * expf(om - ms);
+        tx = tx * expf(m - ms) + ot * expf(om - ms);
         m = mn;
     }
     if (lane == 0) {
         red_m[wave] = m;
         red_l[wave] = l;
+        red_t[wave] = tx;
     }
     __syncthreads();
     if (tid == 0) {
         float mm = fmaxf(fmaxf(red_m[0], red_m[1]), fmaxf(red_m[2], red_m[3]));
         float ms = (mm == -INFINITY) ? 0.0f : mm;
-        float ll = 0.0f;
-        for (int w = 0; w < 4; w++)
+        float ll = 0.0f, tt = 0.0f;
+        for (int w = 0; w < 4; w++) {
             ll += red_l[w] * expf(red_m[w] - ms);
-        a.lse2[((int64_t)b * a.n_q_heads + h) * a.n_q_pad + row] = ll > 0.0f ? mm + logf(ll) : INFINITY;   // natural log here
+            tt += red_t[w] * expf(red_m[w] - ms);
+        }
+        const int64_t o = ((int64_t)b * a.n_q_heads + h) * a.n_q_pad + row;
+        a.lse2[o] = ll > 0.0f ? mm + logf(ll) : INFINITY;   // natural log here
+        if (a.ent_part)
+            a.ent_part[o] = ll > 0.0f ? tt / ll : 0.0f;
     }
 }
 
@@ -607,7 +692,7 @@ int dream_visual_compress(const dream_attn_desc *desc, const void *q, const int3
         a.lse2 = reinterpret_cast<float *>(static_cast<char *>(workspace) + p.off_lse);
         a.part = reinterpret_cast<float *>(static_cast<char *>(workspace) + p.off_part);
         a.n_q = n_q; a.n_q_pad = p.n_q_pad; a.n_keys = n_keys;
-        a.ns1 = p.ns1; a.ns2 = p.ns2;
+        a.ns1 = p.ns1; a.ns2 = p.ns2; a.ent_part = nullptr;
         a.lse_split_stride = (int64_t)desc->batch * desc->n_q_heads * p.n_q_pad;
         a.n_q_heads = desc->n_q_heads; a.n_kv_heads = desc->n_kv_heads;
         a.vis_start = vis_start; a.vis_len = vis_len; a.s_max = desc->s_max;
@@ -619,15 +704,15 @@ int dream_visual_compress(const dream_attn_desc *desc, const void *q, const int3
             dim3 g1(desc->n_q_heads, ceil_div(n_q, 64), desc->batch * p.ns1), g2(desc->n_q_heads, ceil_div(vis_len, 64), desc->batch * p.ns2);
             switch (desc->head_dim) {
             case 64:
-                hipLaunchKernelGGL(scores_lse_bf16_kernel<64>, g1, dim3(256), 0, st, a);
+                hipLaunchKernelGGL((scores_lse_bf16_kernel<64, false>), g1, dim3(256), 0, st, a);
                 launch_colsum<64>(p.ns1, g2, st, a);
                 break;
             case 128:
-                hipLaunchKernelGGL(scores_lse_bf16_kernel<128>, g1, dim3(256), 0, st, a);
+                hipLaunchKernelGGL((scores_lse_bf16_kernel<128, false>), g1, dim3(256), 0, st, a);
                 launch_colsum<128>(p.ns1, g2, st, a);
                 break;
             default:
-                hipLaunchKernelGGL(scores_lse_bf16_kernel<256>, g1, dim3(256), 0, st, a);
+                hipLaunchKernelGGL((scores_lse_bf16_kernel<256, false>), g1, dim3(256), 0, st, a);
                 launch_colsum<256>(p.ns1, g2, st, a);
                 break;
             }
@@ -668,6 +753,77 @@ int dream_visual_compress(const dream_attn_desc *desc, const void *q, const int3
         return check_launch("gather_rows_kernel");
     }
     return DREAM_OK;
+}
+
+size_t dream_attention_entropy_workspace(const dream_attn_desc *desc, int32_t n_q)
+{
+    if (!desc || desc->batch < 1 || desc->n_q_heads < 1 || n_q < 1)
+        return DREAM_WORKSPACE_HEADER_BYTES;
+    const CompressPlan p = compress_plan(desc->batch, desc->n_q_heads, n_q, 0, desc->dtype);
+    const size_t part = align_up((size_t)p.ns1 * desc->batch * desc->n_q_heads * p.n_q_pad * sizeof(float), 256);
+    const size_t sums = align_up((size_t)desc->batch * ceil_div((int64_t)desc->n_q_heads * n_q, 256) * sizeof(float), 256);
+    return DREAM_WORKSPACE_HEADER_BYTES + 2 * part + sums;
+}
+
+int dream_attention_entropy(const dream_attn_desc *desc, const void *q, const int32_t *q_pos, int32_t n_q, const void *k_cache,
+                            int32_t n_keys, float *row_entropy, float *ae, void *workspace, size_t workspace_bytes, void *stream)
+{
+    const char *who = "dream_attention_entropy";
+    if (!desc || !q || !k_cache || !ae)
+        return fail(DREAM_ERR_INVALID_ARG, "%s: NULL argument", who);
+    if (desc->batch < 1 || desc->batch > 65535)
+        return fail(DREAM_ERR_INVALID_ARG, "%s: batch %d outside [1, 65535]", who, desc->batch);
+    if (desc->dtype != DREAM_F32 && desc->dtype != DREAM_BF16)
+        return fail(DREAM_ERR_INVALID_ARG, "%s: unknown dtype %d", who, desc->dtype);
+    if (desc->n_q_heads < 1 || desc->n_kv_heads < 1 || desc->n_q_heads % desc->n_kv_heads || desc->n_q_heads > 65535)
+        return fail(DREAM_ERR_INVALID_ARG, "%s: bad head counts %d / %d", who, desc->n_q_heads, desc->n_kv_heads);
+    if (desc->head_dim != 64 && desc->head_dim != 128 && desc->head_dim != 256)
+        return fail(DREAM_ERR_UNSUPPORTED, "%s: head_dim %d not in {64,128,256}", who, desc->head_dim);
+    if (n_q < 1 || n_keys < 1 || n_keys > desc->s_max)
+        return fail(DREAM_ERR_INVALID_ARG, "%s: need n_q >= 1 and 1 <= n_keys <= s_max", who);
+    if (!q_pos && n_q > n_keys)
+        return fail(DREAM_ERR_INVALID_ARG, "%s: %d rows at positions 0..n_q-1 but only %d keys", who, n_q, n_keys);
+    const CompressPlan p = compress_plan(desc->batch, desc->n_q_heads, n_q, 0, desc->dtype);
+    const size_t part = align_up((size_t)p.ns1 * desc->batch * desc->n_q_heads * p.n_q_pad * sizeof(float), 256);
+    const int n_blocks = ceil_div((int64_t)desc->n_q_heads * n_q, 256);
+    const size_t need = DREAM_WORKSPACE_HEADER_BYTES + 2 * part + align_up((size_t)desc->batch * n_blocks * sizeof(float), 256);
+    if (!workspace || workspace_bytes < need)
+        return fail(DREAM_ERR_WORKSPACE, "%s: workspace of %zu bytes, %zu needed", who, workspace_bytes, need);
+    hipStream_t st = as_stream(stream);
+    ScoreArgs a;
+    a.q = q; a.k = k_cache; a.q_pos = q_pos;
+    a.lse2 = reinterpret_cast<float *>(static_cast<char *>(workspace) + DREAM_WORKSPACE_HEADER_BYTES);
+    a.ent_part = reinterpret_cast<float *>(static_cast<char *>(workspace) + DREAM_WORKSPACE_HEADER_BYTES + part);
+    a.part = nullptr;
+    a.n_q = n_q; a.n_q_pad = p.n_q_pad; a.n_keys = n_keys;
+    a.n_q_heads = desc->n_q_heads; a.n_kv_heads = desc->n_kv_heads;
+    a.vis_start = 0; a.vis_len = 0; a.s_max = desc->s_max;
+    a.ns1 = p.ns1; a.ns2 = 1;
+    a.lse_split_stride = (int64_t)desc->batch * desc->n_q_heads * p.n_q_pad;
+    a.scale = desc->scale != 0.0f ? desc->scale : 1.0f / sqrtf((float)desc->head_dim);
+    a.scale_log2 = a.scale * 1.4426950408889634f;
+    if (desc->dtype == DREAM_BF16) {
+        if ((int64_t)desc->batch * p.ns1 > 65535 || ceil_div(n_q, 64) > 65535)
+            return fail(DREAM_ERR_UNSUPPORTED, "%s: batch %d or n_q %d too large for the score grid", who, desc->batch, n_q);
+        dim3 g1(desc->n_q_heads, ceil_div(n_q, 64), desc->batch * p.ns1);
+        switch (desc->head_dim) {
+        case 64:  hipLaunchKernelGGL((scores_lse_bf16_kernel<64, true>), g1, dim3(256), 0, st, a); break;
+        case 128: hipLaunchKernelGGL((scores_lse_bf16_kernel<128, true>), g1, dim3(256), 0, st, a); break;
+        default:  hipLaunchKernelGGL((scores_lse_bf16_kernel<256, true>), g1, dim3(256), 0, st, a); break;
+        }
+    } else {
+        if (n_q > 65535)
+            return fail(DREAM_ERR_UNSUPPORTED, "%s: too many rows for the float32 path", who);
+        hipLaunchKernelGGL(scores_lse_f32_kernel, dim3(n_q, desc->n_q_heads, desc->batch), dim3(256), 0, st, a, desc->head_dim);
+    }
+    int rc = check_launch("entropy score kernel");
+    if (rc)
+        return rc;
+    float *block_sum = reinterpret_cast<float *>(static_cast<char *>(workspace) + DREAM_WORKSPACE_HEADER_BYTES + 2 * part);
+    hipLaunchKernelGGL(entropy_rows_kernel, dim3(n_blocks, desc->batch), dim3(256), 0, st, a, desc->dtype == DREAM_BF16 ? 1 : 0, row_entropy,
+                       block_sum);
+    hipLaunchKernelGGL(entropy_mean_kernel, dim3(desc->batch), dim3(64), 0, st, block_sum, n_blocks, desc->n_q_heads * n_q, ae);
+    return check_launch("entropy reduction kernels");
 }
 
 }  // extern "C"

@@ -155,3 +155,18 @@ def run_finalize(pool_score: np.ndarray, pool_parent: np.ndarray, pool_token: np
                                        dream.to_device(np.ascontiguousarray(pool_token, dtype=np.int32)), B, N, budget, par, tok, pidx)
     torch.cuda.synchronize()
     return n_tree, par.cpu().numpy(), tok.cpu().numpy(), pidx.cpu().numpy()
+
+
+def run_entropy(dtype: str, q: np.ndarray, k: np.ndarray, n_keys: int, q_pos=None, scale: float = 0.0):
+    """Returns (row_entropy [B,Hq,n_q] float32, ae [B] float32)."""
+    B, n_q, Hq, D = q.shape
+    Hkv, s_max = k.shape[1], k.shape[2]
+    desc = dream.attn_desc(B, Hq, Hkv, D, DT[dtype], s_max, scale)
+    dq, dk = dream.to_device(q, dtype), dream.to_device(k, dtype)
+    qp = None if q_pos is None else dream.to_device(np.ascontiguousarray(q_pos, dtype=np.int32))
+    row = torch.full((B, Hq, n_q), float("nan"), dtype=torch.float32, device="cuda")
+    ae = torch.full((B,), float("nan"), dtype=torch.float32, device="cuda")
+    ws = dream.alloc_workspace(dream.dream_attention_entropy_workspace(desc, n_q))
+    dream.dream_attention_entropy(desc, dq, qp, n_q, dk, n_keys, row, ae, ws)
+    torch.cuda.synchronize()
+    return row.cpu().numpy(), ae.cpu().numpy()

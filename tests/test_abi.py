@@ -163,3 +163,19 @@ def test_tree_build_argument_errors(lib):
         return lib.dream_tree_finalize(score, parent, token, C.c_int32(B), C.c_int32(N), C.c_int32(budget), tp, tt, ti, C.byref(n), None), n.value
     assert finalize(score=None)[0] == -1 and finalize(ti=None)[0] == -1
     assert finalize(N=0)[0] == -1 and finalize(N=1025)[0] == -1 and finalize(budget=-1)[0] == -1 and finalize(B=0)[0] == -1
+
+
+def test_attention_entropy_argument_errors(lib):
+    import ctypes as C
+    fake = C.c_void_p(0x1000)
+    desc = dream.attn_desc(1, 32, 32, 128, dream.BF16, 764)
+
+    def call(d=desc, q=fake, n_q=704, k=fake, n_keys=704, ae=fake, ws=fake, nb=1 << 30):
+        return lib.dream_attention_entropy(C.byref(d), q, None, C.c_int32(n_q), k, C.c_int32(n_keys), None, ae, ws, C.c_size_t(nb), None)
+    assert call(q=None) == -1 and call(k=None) == -1 and call(ae=None) == -1
+    assert call(n_q=0) == -1 and call(n_keys=0) == -1 and call(n_keys=765) == -1
+    assert call(n_q=705) == -1                       # rows at positions 0..704 but 704 keys
+    assert call(d=dream.attn_desc(1, 32, 32, 96, dream.BF16, 764)) == -2
+    assert call(d=dream.attn_desc(1, 32, 5, 128, dream.BF16, 764)) == -1
+    need = dream.dream_attention_entropy_workspace(desc, 704)
+    assert need > 65536 and call(nb=need - 1) == -3 and call(ws=None) == -3
