@@ -202,3 +202,4 @@ def attention_entropy(q, k, dtype: str, q_pos=None, scale: Optional[float] = Non
 
 
 from .tree_build import expand_level, finalize_tree, build_tree  # noqa: E402,F401  (float64 numpy, same rules as the C part)
+from .spec_accept import spec_accept  # noqa: E402,F401
