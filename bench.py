@@ -227,7 +227,8 @@ def main() -> int:
     }
 
     out["read_ceiling"] = read_ceiling(torch, dream, bytes_launch, L)
-    out["next_rows"] = {"attention_entropy": entropy_leg(torch, dream, desc, pq, vk[L - 1], P),
+    out["next_rows"] = {"spec_accept": spec_accept_leg(torch, dream, logits, token, parent, cfg),
+                        "attention_entropy": entropy_leg(torch, dream, desc, pq, vk[L - 1], P),
                         "tree_build": tree_build_leg(torch, dream, di, cfg),
                         "kv_commit": kv_commit_leg(torch, dream, desc, vk + vv, prefix_len, T, accept_path, accept_len, cfg)}
     out["streaming_regime"] = streaming_regime(torch, dream, di, cfg)
@@ -270,6 +271,44 @@ def read_ceiling(torch, dream, bytes_launch, L):
     gbs = n / (us * 1e-6) / 1e9
     return {"kernel": "stream_read_kernel (16-byte loads, no writes)", "bytes_per_launch": n, "launch_us": round(us, 3),
             "achieved": round(gbs, 1), "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4)}
+
+
+def spec_accept_leg(torch, dream, logits, token, parent, cfg):
+    """Acceptance at temperature 1 over the same tree and target logits as the greedy phase (not part of `value`),
+    with draft logits = target logits + noise and seeded uniforms; 4 calls per graph."""
+    B, T, V = logits.shape
+    g = torch.Generator(device="cuda")
+    g.manual_seed(cfg.seed)
+    dlogits = (logits.float() + 0.7 * torch.randn(B, T, V, device="cuda", generator=g)).to(torch.bfloat16)
+    ua = torch.rand(B, T, device="cuda", generator=g)
+    ub = torch.rand(B, device="cuda", generator=g)
+    alen = torch.empty(B, dtype=torch.int32, device="cuda")
+    path = torch.empty(B, cfg.depth + 1, dtype=torch.int32, device="cuda")
+    bonus = torch.empty(B, dtype=torch.int32, device="cuda")
+    ws = dream.alloc_workspace(dream.dream_spec_accept_workspace(B, V))
+
+    def run():
+        dream.dream_spec_accept(logits, dlogits, dream.BF16, B, T, V, token, parent, ua, ub, cfg.depth, 1.0, alen, path, bonus, ws)
+    run()
+    torch.cuda.synchronize()
+    stream = torch.cuda.Stream()
+    gr = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(gr, stream=stream):
+        for _ in range(4):
+            run()
+    reps = 20
+    with torch.cuda.stream(stream):
+        for _ in range(3):
+            gr.replay()
+        stream.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            gr.replay()
+        e1.record()
+        stream.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / (reps * 4)
+    return {"temperature": 1.0, "us": round(us, 2), "mean_accept_len": round(float(alen.float().mean().item()), 3)}
 
 
 def entropy_leg(torch, dream, desc, pq, k_cache, P):

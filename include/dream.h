@@ -235,6 +235,30 @@ int dream_tree_finalize(const float *pool_score, const int32_t *pool_parent, con
                         int32_t *tree_token, int32_t *tree_pool_index, int32_t *n_tree_host,
                         void *stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * Acceptance at a sampling temperature (Section 2.1: accept a drafted token d with probability
+ * min(1, P_target(d) / P_draft(d)); Section 4 evaluates at temperature 1).  Over a tree the children
+ * of the current node (root first) are tried in node order; after a rejected child the target
+ * distribution becomes the normalised positive part of (target - draft) and the rejected token
+ * leaves the draft distribution; the first accepted child becomes the current node.  With no
+ * accepted child (or none within max_depth) the next token is drawn from the current target
+ * distribution by inverting its cumulative sum in token order.
+ *   target_logits [B, n_tree, V]   target logits at every node (f32 or bf16)
+ *   draft_logits  [B, n_tree, V]   draft logits at every node: row i is the distribution node i's
+ *                                  children were proposed from (rows of leaves are not read)
+ *   token, parent [B, n_tree] int32;  u_accept [B, n_tree] float32 in [0,1): the random number of
+ *   node i's test;  u_bonus [B] float32 in [0,1): the random number of the final draw
+ *   temperature > 0: both logit rows are divided by it
+ *   accept_len [B], accept_path [B, max_depth+1] (root first, then -1), bonus_token [B] int32
+ * Probabilities are float32 with fixed-order reductions (reproducible run to run).
+ * ------------------------------------------------------------------------------------------- */
+size_t dream_spec_accept_workspace(int32_t batch, int32_t vocab);
+int dream_spec_accept(const void *target_logits, const void *draft_logits, int32_t logits_dtype,
+                      int32_t batch, int32_t n_tree, int32_t vocab, const int32_t *token,
+                      const int32_t *parent, const float *u_accept, const float *u_bonus,
+                      int32_t max_depth, float temperature, int32_t *accept_len, int32_t *accept_path,
+                      int32_t *bonus_token, void *workspace, size_t workspace_bytes, void *stream);
+
 /* Host-side check of one parent array: parent_host[0] == -1 and 0 <= parent_host[i] < i.
  * Writes the maximum depth to *max_depth_out (nullable).  DREAM_OK or DREAM_ERR_INVALID_ARG. */
 int dream_tree_validate_host(const int32_t *parent_host, int32_t n_tree, int32_t *max_depth_out);

@@ -24,7 +24,7 @@ EXPORTED_SYMBOLS = (
     "dream_tree_validate_host", "dream_last_error", "dream_set_kv_splits", "dream_set_q_tiles",
     "dream_attn_plan_describe", "dream_stream_read", "dream_kv_commit",
     "dream_tree_expand_workspace", "dream_tree_expand_level", "dream_tree_finalize",
-    "dream_attention_entropy_workspace", "dream_attention_entropy",
+    "dream_attention_entropy_workspace", "dream_attention_entropy", "dream_spec_accept_workspace", "dream_spec_accept",
 )
 
 
@@ -63,7 +63,7 @@ def load() -> C.CDLL:
             getattr(lib, name)
         for name in ("dream_tree_verify_attn_workspace", "dream_draft_xattn_workspace",
                      "dream_visual_compress_workspace", "dream_accept_path_workspace", "dream_tree_expand_workspace",
-                     "dream_attention_entropy_workspace"):
+                     "dream_attention_entropy_workspace", "dream_spec_accept_workspace"):
             getattr(lib, name).restype = C.c_size_t
         lib.dream_last_error.restype = C.c_char_p
         lib.dream_set_kv_splits.restype = None
@@ -199,6 +199,20 @@ def dream_kv_commit(desc: AttnDesc, caches: Sequence[torch.Tensor], prefix_len: 
     _check(load().dream_kv_commit(C.byref(desc), ptrs, C.c_int32(len(caches)), _dev(prefix_len), C.c_int32(n_tree),
                                   _dev(accept_path), C.c_int32(accept_path.shape[-1]), _dev(accept_len),
                                   _dev(prefix_len_out), _stream(stream)))
+
+
+def dream_spec_accept_workspace(batch: int, vocab: int) -> int:
+    return int(load().dream_spec_accept_workspace(C.c_int32(batch), C.c_int32(vocab)))
+
+
+def dream_spec_accept(target_logits, draft_logits, logits_dtype: int, batch: int, n_tree: int, vocab: int, token, parent,
+                      u_accept, u_bonus, max_depth: int, temperature: float, accept_len, accept_path, bonus_token, workspace,
+                      stream=None) -> None:
+    _check(load().dream_spec_accept(_dev(target_logits), _dev(draft_logits), C.c_int32(logits_dtype), C.c_int32(batch),
+                                    C.c_int32(n_tree), C.c_int32(vocab), _dev(token), _dev(parent), _dev(u_accept), _dev(u_bonus),
+                                    C.c_int32(max_depth), C.c_float(temperature), _dev(accept_len), _dev(accept_path),
+                                    _dev(bonus_token), _dev(workspace), C.c_size_t(workspace.numel() * workspace.element_size()),
+                                    _stream(stream)))
 
 
 def dream_attention_entropy_workspace(desc: AttnDesc, n_q: int) -> int:

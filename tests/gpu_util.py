@@ -170,3 +170,20 @@ def run_entropy(dtype: str, q: np.ndarray, k: np.ndarray, n_keys: int, q_pos=Non
     dream.dream_attention_entropy(desc, dq, qp, n_q, dk, n_keys, row, ae, ws)
     torch.cuda.synchronize()
     return row.cpu().numpy(), ae.cpu().numpy()
+
+
+def run_spec_accept(tlogits: np.ndarray, dlogits: np.ndarray, dtype: str, token, parent, u_accept, u_bonus, max_depth: int,
+                    temperature: float = 1.0):
+    B, T, V = tlogits.shape
+    tl, dl = dream.to_device(tlogits, dtype), dream.to_device(dlogits, dtype)
+    tok = dream.to_device(np.ascontiguousarray(token, dtype=np.int32))
+    par = dream.to_device(np.ascontiguousarray(parent, dtype=np.int32))
+    ua = dream.to_device(np.ascontiguousarray(u_accept, dtype=np.float32))
+    ub = dream.to_device(np.ascontiguousarray(u_bonus, dtype=np.float32))
+    alen = torch.full((B,), -7, dtype=torch.int32, device="cuda")
+    path = torch.full((B, max_depth + 1), -7, dtype=torch.int32, device="cuda")
+    bonus = torch.full((B,), -7, dtype=torch.int32, device="cuda")
+    ws = dream.alloc_workspace(dream.dream_spec_accept_workspace(B, V))
+    dream.dream_spec_accept(tl, dl, DT[dtype], B, T, V, tok, par, ua, ub, max_depth, temperature, alen, path, bonus, ws)
+    torch.cuda.synchronize()
+    return alen.cpu().numpy(), path.cpu().numpy(), bonus.cpu().numpy()

@@ -179,3 +179,20 @@ def test_attention_entropy_argument_errors(lib):
     assert call(d=dream.attn_desc(1, 32, 5, 128, dream.BF16, 764)) == -1
     need = dream.dream_attention_entropy_workspace(desc, 704)
     assert need > 65536 and call(nb=need - 1) == -3 and call(ws=None) == -3
+
+
+def test_spec_accept_argument_errors(lib):
+    import ctypes as C
+    fake = C.c_void_p(0x1000)
+
+    def call(tl=fake, dl=fake, dt=dream.BF16, B=1, T=60, V=32000, tok=fake, par=fake, ua=fake, ub=fake, depth=6, temp=1.0, al=fake,
+             ap=fake, bt=fake, ws=fake, nb=1 << 30):
+        return lib.dream_spec_accept(tl, dl, C.c_int32(dt), C.c_int32(B), C.c_int32(T), C.c_int32(V), tok, par, ua, ub, C.c_int32(depth),
+                                     C.c_float(temp), al, ap, bt, ws, C.c_size_t(nb), None)
+    assert call(tl=None) == -1 and call(dl=None) == -1 and call(ua=None) == -1 and call(ub=None) == -1 and call(bt=None) == -1
+    assert call(dt=9) == -1 and call(B=0) == -1 and call(V=0) == -1 and call(depth=-1) == -1 and call(depth=1024) == -1
+    assert call(T=0) == -2 and call(T=1025) == -2
+    assert call(temp=0.0) == -1 and call(temp=-1.0) == -1
+    assert "greedy" in dream.dream_last_error()
+    need = dream.dream_spec_accept_workspace(1, 32000)
+    assert need == 65536 + 3 * 32000 * 4 and call(nb=need - 1) == -3 and call(ws=None) == -3
