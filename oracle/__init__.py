@@ -186,6 +186,18 @@ def kv_commit(cache, dtype: str, prefix_len, n_tree: int, path, accept_len):
     return cache, new_len
 
 
+def project(x, w, dtype: str, n_heads: int, head_dim: int) -> np.ndarray:
+    """x [B,R,hidden], w [n_heads*head_dim, hidden] -> y [B,R,n_heads,head_dim] f64 (Eq. 1's linear maps)."""
+    x, w = _check(x, dtype), _check(w, dtype)
+    B, R, hidden = x.shape
+    assert w.shape == (n_heads * head_dim, hidden)
+    out = np.zeros((B, R, n_heads, head_dim), dtype=np.float64)
+    rc = lib().oracle_project(_ptr(x), _ptr(w), C.c_int(_DT[dtype]), C.c_int(B), C.c_int(R), C.c_int(hidden), C.c_int(n_heads),
+                              C.c_int(head_dim), _ptr(out))
+    assert rc == 0
+    return out
+
+
 def attention_entropy(q, k, dtype: str, q_pos=None, scale: Optional[float] = None):
     """q [B,Nq,Hq,D], k [B,Hkv,s_max,D] -> (row_entropy [B,Hq,Nq] f64, ae [B] f64), Eq. 2."""
     q, k = _check(q, dtype), _check(k, dtype)

@@ -30,6 +30,9 @@
  *   oracle_attention_entropy
  *       the token-level attention entropy of a layer, Eq. 2 of Section 3.2: minus the sum of
  *       A log A over each row of the causal attention matrix, averaged over rows and heads.
+ *   oracle_project
+ *       the linear maps of Eq. 1 (Section 3.1): Q = E W_Q, K = S W_K, V = S W_V, one output row per
+ *       input feature row, split into heads.
  *   oracle_kv_commit
  *       what Section 2.1 says happens after verification: the tokens after the first rejection
  *       are discarded and decoding continues from the accepted prefix; with KV caching
@@ -42,7 +45,8 @@
  * path enumeration and planted paths/ties for acceptance; for the commit, hand-written row markers
  * (including a path whose destination rows are other entries' source rows), the no-op chain path and
  * "attention over the committed cache == tree-masked attention of the accepted node"; for the entropy, the closed form log(i+1) of uniform rows, the one-hot limit, and the identity
- * H = LSE - scale q.(attention output with V := K) evaluated through the attention oracle.  No function
+ * H = LSE - scale q.(attention output with V := K) evaluated through the attention oracle; for the
+ * projections, identity and averaging weights, linearity and a float64 library product.  No function
  * here is unpinned.
  *
  * Tensor layouts (C order): q [B,Tq,Hq,D]; k,v [B,Hkv,s_max,D]; logits [B,T,V].
@@ -432,6 +436,26 @@ int oracle_attention_entropy(const void *q, const int32_t *q_pos, int n_q, const
         for (int64_t i = 0; i < (int64_t)Hq * n_q; i++)
             t += row_entropy[(int64_t)b * Hq * n_q + i];
         ae[b] = t / ((double)Hq * n_q);
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------------------------ */
+/* Projections of Eq. 1 (Section 3.1): y[b,r,h,:] = x[b,r,:] . W[h*D .. h*D+D-1, :]^T          */
+/* x [B,R,hidden], w [H*D, hidden] (row n holds the weights of output feature n), both of the   */
+/* given dtype; out [B,R,H,D] float64.                                                          */
+/* ------------------------------------------------------------------------------------------ */
+int oracle_project(const void *x, const void *w, int dtype, int B, int R, int hidden, int H, int D, double *out)
+{
+    int64_t rows = (int64_t)B * R;
+#pragma omp parallel for schedule(static) num_threads(g_threads)
+    for (int64_t br = 0; br < rows; br++) {
+        for (int n = 0; n < H * D; n++) {
+            double acc = 0.0;
+            for (int k = 0; k < hidden; k++)
+                acc += load_as_double(x, dtype, br * hidden + k) * load_as_double(w, dtype, (int64_t)n * hidden + k);
+            out[br * H * D + n] = acc;
+        }
     }
     return 0;
 }
