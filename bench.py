@@ -230,6 +230,7 @@ def main() -> int:
     out["next_rows"] = {"spec_accept": spec_accept_leg(torch, dream, logits, token, parent, cfg),
                         "attention_entropy": entropy_leg(torch, dream, desc, pq, vk[L - 1], P),
                         "tree_build": tree_build_leg(torch, dream, di, cfg),
+                        "project": project_leg(torch, dream, desc, xk, xv, prefix_len, xnode[1], cfg),
                         "kv_commit": kv_commit_leg(torch, dream, desc, vk + vv, prefix_len, T, accept_path, accept_len, cfg)}
     out["streaming_regime"] = streaming_regime(torch, dream, di, cfg)
     if not args.no_cpu:
@@ -390,6 +391,52 @@ def tree_build_leg(torch, dream, di, cfg):
     nbytes = sum(lv[0].numel() * 2 for lv in levels)
     return {"levels": depth, "k": k, "budget": budget, "launches": 2 * depth + 1, "us": round(us, 2), "logit_bytes": nbytes,
             "achieved_GBs": round(nbytes / (us * 1e-6) / 1e9, 1), "bound": "hbm (launch latency at one sequence)"}
+
+
+def project_leg(torch, dream, desc, xk, xv, prefix_len, frontier, cfg):
+    """Eq. 1's three linear maps for one draft level (not part of `value`): the frontier rows' queries
+    (W_Q: hidden -> Hq D, dense output) and the same rows' keys and values written into the draft cache at
+    prefix_len + node (W_K, W_V: hidden -> Hkv D).  The weights are read once per call and dominate the bytes;
+    One launch per level carries all three maps; 2 levels per graph, each with its own weights so nothing is
+    served from L2."""
+    B, R = frontier.shape
+    Hq, Hkv, D, hid = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.hidden
+    per_graph = 2
+
+    def rnd(*shape):
+        return torch.randn(*shape, dtype=torch.float32, device="cuda").mul_(hid ** -0.5).to(torch.bfloat16)
+    wq = [rnd(Hq * D, hid) for _ in range(per_graph)]
+    wk = [rnd(Hkv * D, hid) for _ in range(per_graph)]
+    wv = [rnd(Hkv * D, hid) for _ in range(per_graph)]
+    e = torch.randn(B, R, hid, dtype=torch.float32, device="cuda").to(torch.bfloat16)
+    s = torch.randn(B, R, hid, dtype=torch.float32, device="cuda").to(torch.bfloat16)
+    q = torch.empty(B, R, Hq, D, dtype=torch.bfloat16, device="cuda")
+
+    def run(i):
+        dream.dream_project_rows_multi(desc, [(e, wq[i], Hq, None, None, q), (s, wk[i], Hkv, prefix_len, frontier, xk),
+                                              (s, wv[i], Hkv, prefix_len, frontier, xv)], R, hid)
+    run(0)
+    torch.cuda.synchronize()
+    stream = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=stream):
+        for i in range(per_graph):
+            run(i)
+    reps = 20
+    with torch.cuda.stream(stream):
+        for _ in range(3):
+            g.replay()
+        stream.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            g.replay()
+        e1.record()
+        stream.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / (reps * per_graph)
+    nbytes = 2 * hid * (Hq + 2 * Hkv) * D + 2 * B * R * hid * 2 + 2 * B * R * (Hq + 2 * Hkv) * D
+    return {"rows": B * R, "us_per_level": round(us, 2), "bytes": nbytes, "achieved_GBs": round(nbytes / (us * 1e-6) / 1e9, 1),
+            "bound": "hbm"}
 
 
 def kv_commit_leg(torch, dream, desc, caches, prefix_len, T, accept_path, accept_len, cfg):

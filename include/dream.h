@@ -259,6 +259,39 @@ int dream_spec_accept(const void *target_logits, const void *draft_logits, int32
                       int32_t max_depth, float temperature, int32_t *accept_len, int32_t *accept_path,
                       int32_t *bonus_token, void *workspace, size_t workspace_bytes, void *stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * The linear maps of Eq. 1 (Section 3.1: Q = E W_Q, K = S W_K, V = S W_V) for the rows a decode step
+ * adds, written where attention reads them:
+ *   y[b, r, h, :] = x[b, r, :] . w[h*D .. h*D+D-1, :]^T       (float32 accumulation, bf16 result)
+ *   x          [B, n_rows, hidden] bf16     feature rows (draft features E, target features S^L)
+ *   w          [n_heads*D, hidden] bf16     row n holds the weights of output feature n
+ *   row_base   nullable [B] int32; row_index nullable [B, n_rows] int32 (needs row_base)
+ *   out        row_base == NULL: dense [B, n_rows, n_heads, D] (queries);
+ *              otherwise a cache [B, n_heads, s_max, D]: row r of sequence b lands at cache row
+ *              row_base[b] + (row_index ? row_index[b, r] : r) of every head (cache append; the rest
+ *              of the cache keeps its content).  Uses desc->batch, head_dim (D), dtype (bf16 only),
+ *              s_max.  hidden must be a multiple of 256, D of 16; x, w, out 16-byte aligned.
+ *              A destination row outside [0, s_max) is dropped (nothing is written for it).
+ * dream_project_rows_multi runs up to DREAM_MAX_PROJ_JOBS such maps over the same B, n_rows and
+ * hidden in ONE launch (a draft level's W_Q, W_K and W_V: together they fill the chip where the
+ * narrow K/V maps of a grouped-query model alone would not).  `jobs` is a host array read during
+ * the call; jobs must not write overlapping memory.
+ * ------------------------------------------------------------------------------------------- */
+#define DREAM_MAX_PROJ_JOBS 4
+typedef struct dream_proj_job {
+    const void *x;             /* device */
+    const void *w;             /* device */
+    int32_t n_heads;
+    const int32_t *row_base;   /* device, nullable */
+    const int32_t *row_index;  /* device, nullable */
+    void *out;                 /* device */
+} dream_proj_job;
+int dream_project_rows(const dream_attn_desc *desc, const void *x, int32_t n_rows, int32_t hidden,
+                       const void *w, int32_t n_heads, const int32_t *row_base,
+                       const int32_t *row_index, void *out, void *stream);
+int dream_project_rows_multi(const dream_attn_desc *desc, const dream_proj_job *jobs, int32_t n_jobs,
+                             int32_t n_rows, int32_t hidden, void *stream);
+
 /* Host-side check of one parent array: parent_host[0] == -1 and 0 <= parent_host[i] < i.
  * Writes the maximum depth to *max_depth_out (nullable).  DREAM_OK or DREAM_ERR_INVALID_ARG. */
 int dream_tree_validate_host(const int32_t *parent_host, int32_t n_tree, int32_t *max_depth_out);

@@ -25,6 +25,7 @@ EXPORTED_SYMBOLS = (
     "dream_attn_plan_describe", "dream_stream_read", "dream_kv_commit",
     "dream_tree_expand_workspace", "dream_tree_expand_level", "dream_tree_finalize",
     "dream_attention_entropy_workspace", "dream_attention_entropy", "dream_spec_accept_workspace", "dream_spec_accept",
+    "dream_project_rows", "dream_project_rows_multi",
 )
 
 
@@ -199,6 +200,24 @@ def dream_kv_commit(desc: AttnDesc, caches: Sequence[torch.Tensor], prefix_len: 
     _check(load().dream_kv_commit(C.byref(desc), ptrs, C.c_int32(len(caches)), _dev(prefix_len), C.c_int32(n_tree),
                                   _dev(accept_path), C.c_int32(accept_path.shape[-1]), _dev(accept_len),
                                   _dev(prefix_len_out), _stream(stream)))
+
+
+def dream_project_rows(desc: AttnDesc, x, n_rows: int, hidden: int, w, n_heads: int, row_base, row_index, out, stream=None) -> None:
+    _check(load().dream_project_rows(C.byref(desc), _dev(x), C.c_int32(n_rows), C.c_int32(hidden), _dev(w), C.c_int32(n_heads),
+                                     _dev(row_base), _dev(row_index), _dev(out), _stream(stream)))
+
+
+class ProjJob(C.Structure):
+    _fields_ = [("x", C.c_void_p), ("w", C.c_void_p), ("n_heads", C.c_int32), ("row_base", C.c_void_p),
+                ("row_index", C.c_void_p), ("out", C.c_void_p)]
+
+
+def dream_project_rows_multi(desc: AttnDesc, jobs, n_rows: int, hidden: int, stream=None) -> None:
+    """jobs: sequence of (x, w, n_heads, row_base, row_index, out)."""
+    arr = (ProjJob * len(jobs))(*[ProjJob(_dev(x), _dev(w), n_heads, _dev(rb), _dev(ri), _dev(out))
+                                  for x, w, n_heads, rb, ri, out in jobs])
+    _check(load().dream_project_rows_multi(C.byref(desc), arr, C.c_int32(len(jobs)), C.c_int32(n_rows), C.c_int32(hidden),
+                                           _stream(stream)))
 
 
 def dream_spec_accept_workspace(batch: int, vocab: int) -> int:

@@ -1,0 +1,197 @@
+// dream_project_rows: the linear maps of Eq. 1 (Section 3.1), Q = E W_Q, K = S W_K, V = S W_V, for the few
+// feature rows a decode step adds (the frontier's draft features, the accepted tokens' target features), with
+// the result written straight to where attention reads it: head-split rows of a K/V cache
+// [B, H, s_max, D] at row_base[b] + row_index[b, r] (cache append), or a dense [B, R, H, D] tensor (queries).
+//
+// M = B*R is small (<= a few hundred) and the weight matrix [N, hidden] is large, so the call is bound by
+// streaming the weights once from HBM.  One workgroup owns 16 output features (16 weight rows, contiguous in
+// memory); its 8 waves split the hidden dimension, each computing C^T[n][m] += W[n][k] X[m][k] with
+// v_mfma_f32_16x16x32_bf16 (A = weight rows, B = feature rows, both loaded from global memory directly in the
+// operand layout: every weight byte is used by exactly one wave, so staging it in LDS would add nothing), for up
+// to 4 tiles of 16 feature rows at a time; the 8 partial tiles are summed through LDS in wave order and the
+// rows are rounded to bf16 and scattered.  Roofline: HBM, N*hidden*2 weight bytes per call.
+#include "common.h"
+
+using namespace dream;
+
+namespace {
+
+constexpr int NWAVE = 8;
+
+struct ProjJob {
+    const uint16_t *x, *w;
+    uint16_t *out;
+    const int32_t *row_base, *row_index;
+    int32_t n_heads;
+    int32_t tile_end;    // one past this job's last workgroup (jobs occupy consecutive workgroup ranges)
+};
+
+struct ProjArgs {
+    ProjJob job[DREAM_MAX_PROJ_JOBS];
+    int32_t n_jobs;
+    int32_t n_rows;      // R: rows per sequence
+    int32_t m_total;     // B * R
+    int32_t hidden, head_dim;
+    int64_t s_max;       // cache mode only
+};
+
+// MT: tiles of 16 feature rows handled per pass (1, 2 or 4)
+template <int MT>
+__global__ __launch_bounds__(64 * NWAVE) void project_kernel(ProjArgs args)
+{
+    // the job this workgroup belongs to (uniform: scalar selects)
+    int ji = 0;
+    for (int j = 0; j + 1 < args.n_jobs; j++)
+        ji += (int)blockIdx.x >= args.job[j].tile_end;
+    struct {
+        const uint16_t *x, *w;
+        uint16_t *out;
+        const int32_t *row_base, *row_index;
+        int32_t n_heads, n_rows, m_total, hidden, head_dim;
+        int64_t s_max;
+    } a;
+    int tile0 = 0;
+    a.x = args.job[0].x; a.w = args.job[0].w; a.out = args.job[0].out; a.row_base = args.job[0].row_base;
+    a.row_index = args.job[0].row_index; a.n_heads = args.job[0].n_heads;
+#pragma unroll
+    for (int j = 1; j < DREAM_MAX_PROJ_JOBS; j++)
+        if (ji == j) {
+            a.x = args.job[j].x; a.w = args.job[j].w; a.out = args.job[j].out; a.row_base = args.job[j].row_base;
+            a.row_index = args.job[j].row_index; a.n_heads = args.job[j].n_heads;
+            tile0 = args.job[j - 1].tile_end;
+        }
+    a.n_rows = args.n_rows; a.m_total = args.m_total; a.hidden = args.hidden; a.head_dim = args.head_dim; a.s_max = args.s_max;
+
+    __shared__ __attribute__((aligned(16))) float s_part[NWAVE][MT][64][4];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int c = lane & 15, g = lane >> 4;
+    const int n0 = ((int)blockIdx.x - tile0) * 16;
+    const int K = a.hidden, kw = K / NWAVE;          // this wave's slice of the hidden dimension
+    const uint16_t *wrow = a.w + (int64_t)(n0 + c) * K + wave * kw + g * 8;
+    const int h = n0 / a.head_dim, d0 = n0 % a.head_dim;
+
+    for (int m0 = 0; m0 < a.m_total; m0 += 16 * MT) {
+        f32x4 acc[MT];
+        const uint16_t *xrow[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; mt++) {
+            acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+            const int m = min(m0 + mt * 16 + c, a.m_total - 1);   // padding rows repeat the last row; never stored
+            xrow[mt] = a.x + (int64_t)m * K + wave * kw + g * 8;
+        }
+        constexpr int U = MT == 1 ? 8 : (MT == 2 ? 4 : 2);        // k-steps whose loads are in flight together
+        for (int k = 0; k < kw; k += 32 * U) {
+            bf16x8 wf[U], xf[U][MT];
+#pragma unroll
+            for (int u = 0; u < U; u++) {
+                const int kk = min(k + 32 * u, kw - 32);            // (kw is a multiple of 32; a short tail re-reads and is skipped below)
+                wf[u] = *reinterpret_cast<const bf16x8 *>(wrow + kk);
+#pragma unroll
+                for (int mt = 0; mt < MT; mt++)
+                    xf[u][mt] = *reinterpret_cast<const bf16x8 *>(xrow[mt] + kk);
+            }
+#pragma unroll
+            for (int u = 0; u < U; u++) {
+                if (k + 32 * u < kw) {
+#pragma unroll
+                    for (int mt = 0; mt < MT; mt++)
+                        acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[u], xf[u][mt], acc[mt], 0, 0, 0);
+                }
+            }
+        }
+        // sum the 8 waves' partial tiles in wave order; thread (wave, lane) finishes tile mt = wave % MT ... spread evenly
+        __syncthreads();
+#pragma unroll
+        for (int mt = 0; mt < MT; mt++)
+            *reinterpret_cast<f32x4 *>(s_part[wave][mt][lane]) = acc[mt];
+        __syncthreads();
+        if (wave < MT) {
+            const int mt = wave;
+            f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int w = 0; w < NWAVE; w++)
+                sum += *reinterpret_cast<const f32x4 *>(s_part[w][mt][lane]);
+            const int m = m0 + mt * 16 + c;                          // lane holds outputs n0 + g*4 .. +3 of feature row m
+            if (m < a.m_total) {
+                const int b = m / a.n_rows, r = m - b * a.n_rows;
+                bf16x4 o;
+#pragma unroll
+                for (int i = 0; i < 4; i++)
+                    o[i] = (__bf16)sum[i];
+                int64_t dst;
+                if (a.row_base) {
+                    const int row = a.row_base[b] + (a.row_index ? a.row_index[(int64_t)b * a.n_rows + r] : r);
+                    dst = row >= 0 && row < a.s_max ? (((int64_t)b * a.n_heads + h) * a.s_max + row) * a.head_dim + d0 + g * 4 : -1;
+                } else {
+                    dst = (((int64_t)b * a.n_rows + r) * a.n_heads + h) * a.head_dim + d0 + g * 4;
+                }
+                if (dst >= 0)                                        // a row outside the cache is dropped, never written
+                    *reinterpret_cast<bf16x4 *>(a.out + dst) = o;
+            }
+        }
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+int dream_project_rows_multi(const dream_attn_desc *desc, const dream_proj_job *jobs, int32_t n_jobs, int32_t n_rows, int32_t hidden,
+                             void *stream)
+{
+    const char *who = "dream_project_rows";
+    if (!desc || !jobs)
+        return fail(DREAM_ERR_INVALID_ARG, "%s: NULL argument", who);
+    if (n_jobs < 1 || n_jobs > DREAM_MAX_PROJ_JOBS)
+        return fail(DREAM_ERR_INVALID_ARG, "%s: %d jobs outside [1, %d]", who, n_jobs, DREAM_MAX_PROJ_JOBS);
+    if (desc->dtype != DREAM_BF16)
+        return fail(DREAM_ERR_UNSUPPORTED, "%s: bf16 tensors only", who);
+    if (desc->batch < 1 || n_rows < 1 || (int64_t)desc->batch * n_rows > (1 << 20))
+        return fail(DREAM_ERR_INVALID_ARG, "%s: batch and n_rows must be positive, batch * n_rows at most 2^20", who);
+    if (desc->head_dim < 16 || desc->head_dim % 16)
+        return fail(DREAM_ERR_UNSUPPORTED, "%s: head_dim %d is not a positive multiple of 16", who, desc->head_dim);
+    if (hidden < 256 || hidden % 256)
+        return fail(DREAM_ERR_UNSUPPORTED, "%s: hidden %d is not a positive multiple of 256", who, hidden);
+    ProjArgs a = {};
+    int64_t tiles = 0;
+    for (int j = 0; j < n_jobs; j++) {
+        const dream_proj_job &jb = jobs[j];
+        if (!jb.x || !jb.w || !jb.out)
+            return fail(DREAM_ERR_INVALID_ARG, "%s: NULL tensor in job %d", who, j);
+        if (jb.n_heads < 1)
+            return fail(DREAM_ERR_INVALID_ARG, "%s: n_heads of job %d must be positive", who, j);
+        if (jb.row_base && desc->s_max < 1)
+            return fail(DREAM_ERR_INVALID_ARG, "%s: cache output needs s_max", who);
+        if (!jb.row_base && jb.row_index)
+            return fail(DREAM_ERR_INVALID_ARG, "%s: row_index without row_base in job %d", who, j);
+        if ((reinterpret_cast<uintptr_t>(jb.x) | reinterpret_cast<uintptr_t>(jb.w) | reinterpret_cast<uintptr_t>(jb.out)) & 15)
+            return fail(DREAM_ERR_INVALID_ARG, "%s: x, w and out must be 16-byte aligned", who);
+        tiles += (int64_t)jb.n_heads * desc->head_dim / 16;
+        if (tiles > (1 << 24))
+            return fail(DREAM_ERR_UNSUPPORTED, "%s: more than 2^24 tiles of 16 output features", who);
+        a.job[j].x = static_cast<const uint16_t *>(jb.x); a.job[j].w = static_cast<const uint16_t *>(jb.w);
+        a.job[j].out = static_cast<uint16_t *>(jb.out); a.job[j].row_base = jb.row_base; a.job[j].row_index = jb.row_index;
+        a.job[j].n_heads = jb.n_heads; a.job[j].tile_end = (int32_t)tiles;
+    }
+    a.n_jobs = n_jobs; a.n_rows = n_rows; a.m_total = desc->batch * n_rows; a.hidden = hidden; a.head_dim = desc->head_dim;
+    a.s_max = desc->s_max;
+    const dim3 grid((unsigned)tiles);
+    hipStream_t st = as_stream(stream);
+    if (a.m_total <= 16)
+        hipLaunchKernelGGL(project_kernel<1>, grid, dim3(64 * NWAVE), 0, st, a);
+    else if (a.m_total <= 32)
+        hipLaunchKernelGGL(project_kernel<2>, grid, dim3(64 * NWAVE), 0, st, a);
+    else
+        hipLaunchKernelGGL(project_kernel<4>, grid, dim3(64 * NWAVE), 0, st, a);
+    return check_launch("project_kernel");
+}
+
+int dream_project_rows(const dream_attn_desc *desc, const void *x, int32_t n_rows, int32_t hidden, const void *w, int32_t n_heads,
+                       const int32_t *row_base, const int32_t *row_index, void *out, void *stream)
+{
+    dream_proj_job job = {x, w, n_heads, row_base, row_index, out};
+    return dream_project_rows_multi(desc, &job, 1, n_rows, hidden, stream);
+}
+
+}  // extern "C"

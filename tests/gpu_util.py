@@ -187,3 +187,38 @@ def run_spec_accept(tlogits: np.ndarray, dlogits: np.ndarray, dtype: str, token,
     dream.dream_spec_accept(tl, dl, DT[dtype], B, T, V, tok, par, ua, ub, max_depth, temperature, alen, path, bonus, ws)
     torch.cuda.synchronize()
     return alen.cpu().numpy(), path.cpu().numpy(), bonus.cpu().numpy()
+
+
+def run_project(x: np.ndarray, w: np.ndarray, n_heads: int, head_dim: int, row_base=None, row_index=None, cache: np.ndarray = None):
+    """bf16 bit-pattern inputs.  Dense mode returns [B,R,H,D] float64; cache mode returns the whole cache as int16 bits."""
+    B, R, hidden = x.shape
+    s_max = 1 if cache is None else cache.shape[2]
+    desc = dream.attn_desc(B, n_heads, n_heads, head_dim, dream.BF16, s_max)
+    dx, dw = dream.to_device(x, "bf16"), dream.to_device(w, "bf16")
+    if cache is None:
+        out = torch.full((B, R, n_heads, head_dim), float("nan"), dtype=torch.bfloat16, device="cuda")
+        dream.dream_project_rows(desc, dx, R, hidden, dw, n_heads, None, None, out)
+        torch.cuda.synchronize()
+        return out_to_f64(out)
+    out = dream.to_device(cache, "bf16")
+    rb = dream.to_device(np.ascontiguousarray(row_base, dtype=np.int32))
+    ri = None if row_index is None else dream.to_device(np.ascontiguousarray(row_index, dtype=np.int32))
+    dream.dream_project_rows(desc, dx, R, hidden, dw, n_heads, rb, ri, out)
+    torch.cuda.synchronize()
+    return out.view(torch.int16).cpu().numpy()
+
+
+def run_project_qkv(e: np.ndarray, s: np.ndarray, wq, wk, wv, n_q_heads, n_kv_heads, head_dim, row_base, row_index, k_cache, v_cache):
+    """One launch for a draft level: Q dense from e, K and V from s into the caches.  Returns (q f64, k bits, v bits)."""
+    B, R, hidden = e.shape
+    desc = dream.attn_desc(B, n_q_heads, n_kv_heads, head_dim, dream.BF16, k_cache.shape[2])
+    de, ds = dream.to_device(e, "bf16"), dream.to_device(s, "bf16")
+    dwq, dwk, dwv = (dream.to_device(w, "bf16") for w in (wq, wk, wv))
+    q = torch.full((B, R, n_q_heads, head_dim), float("nan"), dtype=torch.bfloat16, device="cuda")
+    kc, vc = dream.to_device(k_cache, "bf16"), dream.to_device(v_cache, "bf16")
+    rb = dream.to_device(np.ascontiguousarray(row_base, dtype=np.int32))
+    ri = dream.to_device(np.ascontiguousarray(row_index, dtype=np.int32))
+    dream.dream_project_rows_multi(desc, [(de, dwq, n_q_heads, None, None, q), (ds, dwk, n_kv_heads, rb, ri, kc),
+                                          (ds, dwv, n_kv_heads, rb, ri, vc)], R, hidden)
+    torch.cuda.synchronize()
+    return out_to_f64(q), kc.view(torch.int16).cpu().numpy(), vc.view(torch.int16).cpu().numpy()

@@ -196,3 +196,29 @@ def test_spec_accept_argument_errors(lib):
     assert "greedy" in dream.dream_last_error()
     need = dream.dream_spec_accept_workspace(1, 32000)
     assert need == 65536 + 3 * 32000 * 4 and call(nb=need - 1) == -3 and call(ws=None) == -3
+
+
+def test_project_rows_argument_errors(lib):
+    import ctypes as C
+    fake = C.c_void_p(0x1000)
+    desc = dream.attn_desc(1, 32, 32, 128, dream.BF16, 764)
+
+    def call(d=desc, x=fake, R=10, hid=4096, w=fake, H=32, rb=None, ri=None, out=fake):
+        return lib.dream_project_rows(C.byref(d), x, C.c_int32(R), C.c_int32(hid), w, C.c_int32(H), rb, ri, out, None)
+    assert call(x=None) == -1 and call(w=None) == -1 and call(out=None) == -1
+    assert call(R=0) == -1 and call(H=0) == -1 and call(R=(1 << 20) + 1) == -1
+    assert call(hid=0) == -2 and call(hid=4000) == -2
+    assert call(d=dream.attn_desc(1, 32, 32, 72, dream.BF16, 764)) == -2
+    assert call(d=dream.attn_desc(1, 32, 32, 128, dream.F32, 764)) == -2
+    assert call(ri=fake) == -1                        # a row index needs a row base
+    assert call(x=C.c_void_p(0x1008)) == -1 and "aligned" in dream.dream_last_error()
+
+    from paper_2505_19201_amd.binding import ProjJob
+
+    def multi(n=1, job=None):
+        arr = (ProjJob * 5)(*[job or ProjJob(0x1000, 0x2000, 8, None, None, 0x3000)] * 5)
+        return lib.dream_project_rows_multi(C.byref(desc), arr, C.c_int32(n), C.c_int32(10), C.c_int32(4096), None)
+    assert multi(0) == -1 and multi(5) == -1
+    assert multi(2, ProjJob(0x1000, None, 8, None, None, 0x3000)) == -1
+    assert multi(1, ProjJob(0x1000, 0x2000, 0, None, None, 0x3000)) == -1
+    assert lib.dream_project_rows_multi(C.byref(desc), None, C.c_int32(1), C.c_int32(10), C.c_int32(4096), None) == -1
