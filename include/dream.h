@@ -28,8 +28,11 @@
  *   - Every function returns a dream_status (0 = ok, negative = error) and never throws or
  *     aborts.  Argument errors are detected on the host before anything is launched; the text of
  *     the last error of the calling thread is available from dream_last_error().
- *   - Device-resident metadata (prefix_len, parent, q_node, token, q_pos) is trusted.
- *     dream_tree_validate_host() is the host-side check for a parent array.
+ *   - Device-resident metadata (prefix_len, parent, q_node, token, q_pos) is trusted to be
+ *     meaningful; dream_tree_validate_host() is the host-side check for a parent array.  The
+ *     kernels still never follow it out of bounds or into a loop: a prefix length is clamped to
+ *     [0, s_max - n_tree], a node index to [0, n_tree), and a parent that does not precede its
+ *     node is treated as "no parent" (results for such input are unspecified, not a fault).
  *
  * Tree convention: node 0 is the root (the target's last emitted token, depth 0, always
  * accepted); parent[0] = -1 and 0 <= parent[i] < i for i > 0.  The K/V rows of the n_tree tree

@@ -109,7 +109,8 @@ __global__ __launch_bounds__(64) void accept_walk_kernel(const float *part_val, 
         for (int ch = 1; ch < n_chunks; ch++)
             better(v, idx, part_val[row * n_chunks + ch], part_idx[row * n_chunks + ch]);
         s_am[i] = idx;
-        s_par[i] = parent[row];
+        const int par = parent[row];
+        s_par[i] = par < i ? par : -1;   // a walk up the tree always ends
         s_tok[i] = token[row];
         node_argmax[row] = idx;
     }
@@ -120,7 +121,7 @@ __global__ __launch_bounds__(64) void accept_walk_kernel(const float *part_val, 
         bool ok = true;
         for (int a = i; a > 0 && ok; d++) {
             const int p = s_par[a];
-            ok = s_tok[a] == s_am[p];
+            ok = p >= 0 && s_tok[a] == s_am[p];
             a = p;
         }
         if (ok && d <= max_depth && d > best_d) {   // nodes are visited in increasing index: strict '>' keeps the lowest

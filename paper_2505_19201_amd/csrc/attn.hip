@@ -292,7 +292,7 @@ __global__ __launch_bounds__(256, (QG == 1 && D <= 128) ? DREAM_Q1_WAVES : 1) vo
     if (!a.tree_mask && tid < a.n_tree)
         my_parent = a.parent[(int64_t)b * a.n_tree + tid];
 
-    const int P = a.prefix_len[b];
+    const int P = (int)min((int64_t)max(a.prefix_len[b], 0), a.s_max - a.n_tree);   // never past the cache, whatever the array holds
     const int kv_len = P + a.n_tree;
     const int tiles_total = (kv_len + 31) / 32;
     const int tps = (tiles_total + nsplit - 1) / nsplit;
@@ -342,7 +342,7 @@ __global__ __launch_bounds__(256, (QG == 1 && D <= 128) ? DREAM_Q1_WAVES : 1) vo
         wave_active = wave_active || q_valid[qt];
         const int row = q_valid[qt] ? ro.row : 0;
         const int head = q_valid[qt] ? ro.head : kvh * a.group;
-        q_node_of[qt] = a.q_node ? a.q_node[(int64_t)b * a.n_q + row] : row;
+        q_node_of[qt] = a.q_node ? min(max(a.q_node[(int64_t)b * a.n_q + row], 0), a.n_tree - 1) : row;
         const uint16_t *qp = reinterpret_cast<const uint16_t *>(a.q) + (((int64_t)b * a.n_q + row) * a.n_q_heads + head) * D + g * 8;
 #pragma unroll
         for (int ks = 0; ks < NKS; ks++)
@@ -350,7 +350,7 @@ __global__ __launch_bounds__(256, (QG == 1 && D <= 128) ? DREAM_Q1_WAVES : 1) vo
     }
     wave_active = __any(wave_active);
     if (!a.tree_mask && tid < a.n_tree)
-        lds_parent[tid] = my_parent;
+        lds_parent[tid] = my_parent < tid ? my_parent : -1;   // a walk up the tree always ends
     TS(2);
     __syncthreads();   // parents staged
     TS(3);
@@ -529,7 +529,7 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a)
     int32_t my_parent = -1;
     if (!a.tree_mask && tid < a.n_tree)
         my_parent = a.parent[(int64_t)b * a.n_tree + tid];
-    const int P = a.prefix_len[b];
+    const int P = (int)min((int64_t)max(a.prefix_len[b], 0), a.s_max - a.n_tree);   // never past the cache, whatever the array holds
     const int kv_len = P + a.n_tree;
     const int t_end = (kv_len + 31) / 32;
     const int n = t_end > wave ? (t_end - wave + NW - 1) / NW : 0;   // tiles of this wave: wave, wave + NW, ...
@@ -562,7 +562,7 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a)
     const bool valid = row < a.n_q;
     bf16x8 qf[1][NKS];
     const int rr = valid ? row : 0;
-    const int node = a.q_node ? a.q_node[(int64_t)b * a.n_q + rr] : rr;
+    const int node = a.q_node ? min(max(a.q_node[(int64_t)b * a.n_q + rr], 0), a.n_tree - 1) : rr;
     {
         const uint16_t *qp = reinterpret_cast<const uint16_t *>(a.q) + (((int64_t)b * a.n_q + rr) * a.n_q_heads + head) * D + g * 8;
 #pragma unroll
@@ -570,7 +570,7 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a)
             qf[0][ks] = *reinterpret_cast<const bf16x8 *>(qp + ks * 32);
     }
     if (!a.tree_mask && tid < a.n_tree)
-        lds_parent[tid] = my_parent;
+        lds_parent[tid] = my_parent < tid ? my_parent : -1;   // a walk up the tree always ends
     __syncthreads();
     TS(3);
     uint64_t qmask[1];
@@ -748,7 +748,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(AttnArgs a, int D)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int row = blockIdx.x, hq = blockIdx.y, b = blockIdx.z;
     const int kvh = hq / a.group;
-    const int P = a.prefix_len[b];
+    const int P = (int)min((int64_t)max(a.prefix_len[b], 0), a.s_max - a.n_tree);   // never past the cache, whatever the array holds
     const int kv_len = P + a.n_tree;
     const float *q = reinterpret_cast<const float *>(a.q) + (((int64_t)b * a.n_q + row) * a.n_q_heads + hq) * D;
     const float *kb = reinterpret_cast<const float *>(a.k) + ((int64_t)b * a.n_kv_heads + kvh) * a.s_max * D;
@@ -756,14 +756,14 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(AttnArgs a, int D)
     if (tid < D)
         sq[tid] = q[tid];
     if (tid == 0) {
-        int node = a.q_node ? a.q_node[(int64_t)b * a.n_q + row] : row;
+        const int node = a.q_node ? min(max(a.q_node[(int64_t)b * a.n_q + row], 0), a.n_tree - 1) : row;
         uint64_t m;
         if (a.tree_mask) {
             m = a.tree_mask[(int64_t)b * a.n_tree + node];
         } else {
             const int32_t *par = a.parent + (int64_t)b * a.n_tree;
             m = a.include_self ? (1ull << node) : 0ull;
-            for (int p = par[node]; p >= 0; p = par[p])
+            for (int prev = node, p = par[node]; p >= 0 && p < prev; prev = p, p = par[p])   // parents decrease: the walk ends
                 m |= 1ull << p;
         }
         smask = m;

@@ -29,7 +29,7 @@ __global__ __launch_bounds__(256) void kv_commit_kernel(CommitArgs a)
 {
     const int h = blockIdx.x, b = blockIdx.y, ci = blockIdx.z;
     const int tid = threadIdx.x;
-    const int P = a.prefix_len[b];
+    const int P = (int)min((int64_t)max(a.prefix_len[b], 0), a.s_max - a.n_tree);
     // device metadata is trusted, but stay inside the tree rows whatever it holds
     const int n = min(max(a.accept_len[b], 0), min(a.path_stride, a.n_tree) - 1);
     if (h == 0 && ci == 0 && a.first_cache == 0 && tid == 0 && a.prefix_len_out)

@@ -84,3 +84,16 @@ def test_large_tree_of_1024_nodes(gu):
     token = di.tree_tokens(parent, 50, 78)
     logits = di.normal((1, T, 50), "bf16", 79, di.STREAM_LOGITS)
     _compare(gu, logits, "bf16", token[None], parent[None], 12)
+
+
+def test_parent_array_with_cycles_still_terminates(gu):
+    """Device metadata is trusted, but a malformed parent array must end in unspecified results, not in a hang."""
+    T, V = 8, 16
+    parent = np.array([[-1, 1, 3, 2, 9, 4, -5, 0]], dtype=np.int32)      # self loop, 2<->3 cycle, out of range, negative
+    token = np.full((1, T), 3, dtype=np.int32)
+    logits = np.zeros((1, T, V), dtype=np.float32)
+    logits[0, :, 3] = 1                                                     # every edge "matches"
+    am, alen, path, bonus = gu.run_accept(logits, "f32", token, parent, 6)
+    assert (am == 3).all() and 0 <= alen[0] <= 6 and bonus[0] == 3
+    assert ((path >= -1) & (path < T)).all()
+    assert alen[0] == 1 and path[0].tolist()[:2] == [0, 7]                  # only node 7 has a well-formed path

@@ -208,3 +208,30 @@ def test_full_size_xattn_round_sampled(gu, name):
             b, h, r = int(g.integers(0, cfg.batch)), int(g.integers(0, cfg.n_q_heads)), int(g.integers(0, rows.shape[1]))
             want, _ = oracle.attn_row(qsel, x.k, x.v, cfg.dtype, x.prefix_len, x.parent, False, b, h, r, node=int(rows[b, r]))
             assert np.abs(got[b, r, h] - want).max() <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_malformed_device_metadata_stays_in_bounds(gu, dtype):
+    """A prefix length past the cache and a parent array with cycles give unspecified numbers but finite ones:
+    the kernels clamp the prefix to the cache and treat a parent that does not precede its node as none."""
+    cfg = di.Config("bad_meta", dtype, 1, 4, 2, 64, 256, 40, 24, 12, 4, 1, 4, 64, 1, 31)
+    x = di.verify_inputs(cfg)
+    good, _ = gu.run_verify(x)
+    dev = gu.DeviceAttn(x)
+    par = x.parent.copy()
+    par[0, 3], par[0, 5], par[0, 6], par[0, 7] = 3, 6, 5, 99
+    dev.parent = dream_to_device(par)
+    dev.prefix_len = dream_to_device(np.array([x.s_max + 1000], dtype=np.int32))
+    dev.max_kv = x.s_max
+    got, lse = gu.run_verify(x, dev=dev)
+    assert np.isfinite(got).all() and np.isfinite(lse).all()
+    dev.prefix_len = dream_to_device(np.array([-17], dtype=np.int32))       # clamps to an empty prefix
+    got, _ = gu.run_verify(x, dev=dev)
+    assert np.isfinite(got).all()
+    again, _ = gu.run_verify(x)                                             # and the well-formed call is unaffected
+    assert np.array_equal(good, again)
+
+
+def dream_to_device(a):
+    import paper_2505_19201_amd as dream
+    return dream.to_device(a)
