@@ -286,7 +286,7 @@ def spec_accept_leg(torch, dream, logits, token, parent, cfg):
     alen = torch.empty(B, dtype=torch.int32, device="cuda")
     path = torch.empty(B, cfg.depth + 1, dtype=torch.int32, device="cuda")
     bonus = torch.empty(B, dtype=torch.int32, device="cuda")
-    ws = dream.alloc_workspace(dream.dream_spec_accept_workspace(B, V))
+    ws = dream.alloc_workspace(dream.dream_spec_accept_workspace(B, T, V))
 
     def run():
         dream.dream_spec_accept(logits, dlogits, dream.BF16, B, T, V, token, parent, ua, ub, cfg.depth, 1.0, alen, path, bonus, ws)

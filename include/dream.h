@@ -249,13 +249,14 @@ int dream_tree_finalize(const float *pool_score, const int32_t *pool_parent, con
  *   target_logits [B, n_tree, V]   target logits at every node (f32 or bf16)
  *   draft_logits  [B, n_tree, V]   draft logits at every node: row i is the distribution node i's
  *                                  children were proposed from (rows of leaves are not read)
+ *   batch * n_tree <= 65535
  *   token, parent [B, n_tree] int32;  u_accept [B, n_tree] float32 in [0,1): the random number of
  *   node i's test;  u_bonus [B] float32 in [0,1): the random number of the final draw
  *   temperature > 0: both logit rows are divided by it
  *   accept_len [B], accept_path [B, max_depth+1] (root first, then -1), bonus_token [B] int32
  * Probabilities are float32 with fixed-order reductions (reproducible run to run).
  * ------------------------------------------------------------------------------------------- */
-size_t dream_spec_accept_workspace(int32_t batch, int32_t vocab);
+size_t dream_spec_accept_workspace(int32_t batch, int32_t n_tree, int32_t vocab);
 int dream_spec_accept(const void *target_logits, const void *draft_logits, int32_t logits_dtype,
                       int32_t batch, int32_t n_tree, int32_t vocab, const int32_t *token,
                       const int32_t *parent, const float *u_accept, const float *u_bonus,

@@ -220,8 +220,8 @@ def dream_project_rows_multi(desc: AttnDesc, jobs, n_rows: int, hidden: int, str
                                            _stream(stream)))
 
 
-def dream_spec_accept_workspace(batch: int, vocab: int) -> int:
-    return int(load().dream_spec_accept_workspace(C.c_int32(batch), C.c_int32(vocab)))
+def dream_spec_accept_workspace(batch: int, n_tree: int, vocab: int) -> int:
+    return int(load().dream_spec_accept_workspace(C.c_int32(batch), C.c_int32(n_tree), C.c_int32(vocab)))
 
 
 def dream_spec_accept(target_logits, draft_logits, logits_dtype: int, batch: int, n_tree: int, vocab: int, token, parent,

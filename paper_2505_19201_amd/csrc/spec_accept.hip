@@ -7,14 +7,17 @@
 // token is drawn from the current target distribution by inverting its cumulative sum in token order.  The
 // uniform random numbers are inputs.
 //
-// One workgroup of 1024 threads walks one sequence (the walk is a dependent chain of at most depth+1 nodes).
-// The target and draft distributions of the current node live unnormalised in the workspace (P, Q and a spare
-// R, V floats each, L2-resident) with their normalisers as scalars, so
-//   a node visit     = two passes over the two logit rows (maxima; exponentials and their sums),
-//   a rejection      = one pass (R = max(P/Zp - Q/Zq, 0) and its sum; then P and R swap; Q[x] = 0, Zq -= Q[x]),
-//   the final draw   = one pass of per-thread contiguous partial sums, a block scan, one thread's rescan.
-// Every reduction has a fixed order, so the result is reproducible.  Roofline: HBM/L2 scans of V logits per
-// visited node; latency bound at one sequence.
+// Two launches.  softmax_stats_kernel (parallel over rows and 8192-logit chunks) leaves (max, sum of
+// exponentials) per chunk for the target row of every node and the draft row of every node with children.
+// spec_walk_kernel, one workgroup of 1024 threads per sequence, merges them per node and evaluates the test of
+// every node against its parent's untouched distributions in parallel: that is exactly the test the walk
+// performs whenever a node is the first child tried, so the walk descends through first children by table
+// lookup.  Only where a first child is rejected do distributions have to exist as arrays: one pass over the two
+// logit rows writes the residual target R = max(P/Zp - Q/Zq, 0) and the draft Q (unnormalised floats in the
+// workspace, L2-resident), later siblings are tested against those (one pass per further rejection), and an
+// accepted sibling returns to the table walk.  The final draw is one pass of per-thread contiguous partial sums,
+// a block scan and one thread's rescan, over the logits directly or over the residual array.  Every reduction
+// has a fixed order, so the result is reproducible.  Roofline: HBM, one read of the logit rows.
 #include "common.h"
 
 using namespace dream;
@@ -73,118 +76,172 @@ __device__ __forceinline__ int block_min_int(int v, int *red, int tid)
     return t;
 }
 
+constexpr int STAT_CHUNK = 8192;    // logits per workgroup of the statistics pass
+
+// tokens t .. t+7 of a row (t a multiple of 8); `vec`: the row is 16-byte aligned and holds a multiple of 8 tokens.
+// Tokens past the end come back as -inf.
 template <bool BF16>
-__global__ __launch_bounds__(NT) void spec_accept_kernel(const void *tlogits, const void *dlogits, int n_tree, int vocab,
-                                                         const int32_t *token, const int32_t *parent, const float *u_accept,
-                                                         const float *u_bonus, int max_depth, float inv_temp, float *work,
-                                                         int32_t *accept_len, int32_t *accept_path, int32_t *bonus_token)
+__device__ __forceinline__ void load8(const void *base, int64_t row, int t, int vocab, bool vec, float v[8])
+{
+    if (vec && t + 8 <= vocab) {
+        if (BF16) {
+            const uint4 u = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint16_t *>(base) + row + t);
+            const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                v[2 * j] = __uint_as_float(w[j] << 16);
+                v[2 * j + 1] = __uint_as_float(w[j] & 0xffff0000u);
+            }
+        } else {
+            const float4 a = *reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(base) + row + t);
+            const float4 c = *reinterpret_cast<const float4 *>(reinterpret_cast<const float *>(base) + row + t + 4);
+            v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = c.x; v[5] = c.y; v[6] = c.z; v[7] = c.w;
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 8; j++)
+            v[j] = t + j < vocab ? load_logit<BF16>(base, row + t + j) : -INFINITY;
+    }
+}
+
+// (max, sum of exp(x/temp - max)) of one 8192-logit chunk of one row.  z = 0: target rows; z = 1: draft rows,
+// skipped (max = -inf, sum = 0) for nodes without children.
+template <bool BF16>
+__global__ __launch_bounds__(256) void softmax_stats_kernel(const void *tlogits, const void *dlogits, int n_tree, int vocab,
+                                                            int n_chunks, bool vec, const int32_t *parent, float inv_temp,
+                                                            float *stat_m, float *stat_s)
+{
+    const int chunk = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t node_row = blockIdx.y;                      // b * n_tree + node
+    const int which = blockIdx.z;
+    const int64_t slot = ((int64_t)which * gridDim.y + node_row) * n_chunks + chunk;
+    __shared__ float red[4];
+    if (which == 1) {
+        const int b = (int)(node_row / n_tree), node = (int)(node_row - (int64_t)b * n_tree);
+        int kids = 0;
+        for (int i = tid; i < n_tree; i += 256)
+            kids |= parent[(int64_t)b * n_tree + i] == node;
+        if (!__syncthreads_or(kids)) {
+            if (tid == 0) {
+                stat_m[slot] = -INFINITY;
+                stat_s[slot] = 0.0f;
+            }
+            return;
+        }
+    }
+    const void *base = which ? dlogits : tlogits;
+    const int64_t row = node_row * vocab;
+    const int begin = chunk * STAT_CHUNK;
+    float x[STAT_CHUNK / 256];
+    float m = -INFINITY;
+#pragma unroll
+    for (int r = 0; r < STAT_CHUNK / 2048; r++) {
+        load8<BF16>(base, row, begin + (r * 256 + tid) * 8, vocab, vec, x + 8 * r);
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+            x[8 * r + j] *= inv_temp;
+            m = fmaxf(m, x[8 * r + j]);
+        }
+    }
+    for (int off = 32; off > 0; off >>= 1)
+        m = fmaxf(m, __shfl_xor(m, off));
+    if (lane == 0)
+        red[wave] = m;
+    __syncthreads();
+    m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    float sum = 0.0f;
+    if (m > -INFINITY) {
+#pragma unroll
+        for (int j = 0; j < STAT_CHUNK / 256; j++)
+            sum += __expf(x[j] - m);                          // exp(-inf) = 0 for the padding
+    }
+    for (int off = 32; off > 0; off >>= 1)
+        sum += __shfl_xor(sum, off);
+    __syncthreads();
+    if (lane == 0)
+        red[wave] = sum;
+    __syncthreads();
+    if (tid == 0) {
+        stat_m[slot] = m;
+        stat_s[slot] = (red[0] + red[1]) + (red[2] + red[3]);
+    }
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(NT) void spec_walk_kernel(const void *tlogits, const void *dlogits, int n_tree, int vocab, int n_chunks,
+                                                       bool vec, const int32_t *token, const int32_t *parent, const float *u_accept,
+                                                       const float *u_bonus, int max_depth, float inv_temp, const float *stat_m,
+                                                       const float *stat_s, float *work, int32_t *accept_len, int32_t *accept_path,
+                                                       int32_t *bonus_token)
 {
     __shared__ int32_t s_par[DREAM_MAX_TREE_ACCEPT];
     __shared__ int32_t s_tok[DREAM_MAX_TREE_ACCEPT];
+    __shared__ int32_t s_first[DREAM_MAX_TREE_ACCEPT];     // first child of a node, or INT_MAX
+    __shared__ float s_mt[DREAM_MAX_TREE_ACCEPT], s_zt[DREAM_MAX_TREE_ACCEPT];   // target row: max, sum
+    __shared__ float s_md[DREAM_MAX_TREE_ACCEPT], s_zd[DREAM_MAX_TREE_ACCEPT];   // draft row
+    __shared__ float s_px[DREAM_MAX_TREE_ACCEPT], s_qx[DREAM_MAX_TREE_ACCEPT];   // unnormalised mass of a node's token at its parent
+    __shared__ uint8_t s_ok[DREAM_MAX_TREE_ACCEPT];        // the node passes its test when it is the first child tried
     __shared__ float s_redf[16];
     __shared__ int s_redi[16];
     __shared__ float s_scan[16];
+    constexpr int NONE = 0x7fffffff;
     const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t bt = (int64_t)b * n_tree, rows_all = (int64_t)gridDim.x * n_tree;
     for (int i = tid; i < n_tree; i += NT) {
-        s_par[i] = parent[(int64_t)b * n_tree + i];
-        s_tok[i] = token[(int64_t)b * n_tree + i];
+        const int par = parent[bt + i];
+        s_par[i] = par < i ? par : -1;
+        s_tok[i] = min(max(token[bt + i], 0), vocab - 1);   // device metadata is trusted but kept inside the row
+        s_first[i] = NONE;
+        // merge the chunk statistics of both rows of node i in chunk order
+        float mt = -INFINITY, md = -INFINITY;
+        for (int c = 0; c < n_chunks; c++) {
+            mt = fmaxf(mt, stat_m[(bt + i) * n_chunks + c]);
+            md = fmaxf(md, stat_m[(rows_all + bt + i) * n_chunks + c]);
+        }
+        float zt = 0.0f, zd = 0.0f;
+        for (int c = 0; c < n_chunks; c++) {
+            const float a = stat_s[(bt + i) * n_chunks + c], d = stat_s[(rows_all + bt + i) * n_chunks + c];
+            if (a > 0.0f)
+                zt += a * __expf(stat_m[(bt + i) * n_chunks + c] - mt);
+            if (d > 0.0f)
+                zd += d * __expf(stat_m[(rows_all + bt + i) * n_chunks + c] - md);
+        }
+        s_mt[i] = mt; s_zt[i] = zt; s_md[i] = md; s_zd[i] = zd;
     }
     float *P = work + (int64_t)b * 3 * vocab, *Q = P + vocab, *R = Q + vocab;
     int32_t *path = accept_path + (int64_t)b * (max_depth + 1);
     if (tid <= max_depth)
         path[tid] = tid == 0 ? 0 : -1;
     __syncthreads();
-
-    int cur = 0, depth = 0;
-    for (;;) {
-        // first child of the current node (children have larger indices than their parent), if depth allows
-        int first = 0x7fffffff;
-        if (depth < max_depth)
-            for (int i = tid; i < n_tree; i += NT)
-                if (i > cur && s_par[i] == cur)
-                    first = min(first, i);
-        first = block_min_int(first, s_redi, tid);
-        const bool has_kids = first != 0x7fffffff;
-        const int64_t row = ((int64_t)b * n_tree + cur) * vocab;
-
-        // ---- node visit: unnormalised target (and draft) distributions of the current node
-        float mt = -INFINITY, md = -INFINITY;
-        for (int t = tid; t < vocab; t += NT) {
-            mt = fmaxf(mt, load_logit<BF16>(tlogits, row + t) * inv_temp);
-            if (has_kids)
-                md = fmaxf(md, load_logit<BF16>(dlogits, row + t) * inv_temp);
+    for (int i = tid; i < n_tree; i += NT) {
+        const int p = s_par[i];
+        if (i > 0 && p >= 0) {
+            atomicMin(&s_first[p], i);
+            const int x = s_tok[i];
+            const float px = __expf(load_logit<BF16>(tlogits, (bt + p) * vocab + x) * inv_temp - s_mt[p]);
+            const float qx = __expf(load_logit<BF16>(dlogits, (bt + p) * vocab + x) * inv_temp - s_md[p]);
+            const float ratio = qx > 0.0f ? (px / s_zt[p]) / (qx / s_zd[p]) : (px > 0.0f ? INFINITY : 0.0f);
+            s_px[i] = px;
+            s_qx[i] = qx;
+            s_ok[i] = u_accept[bt + i] < fminf(1.0f, ratio);
         }
-        mt = block_max(mt, s_redf, tid);
-        if (has_kids)
-            md = block_max(md, s_redf, tid);
-        float zp = 0.0f, zq = 0.0f;
-        for (int t = tid; t < vocab; t += NT) {
-            const float e = __expf(load_logit<BF16>(tlogits, row + t) * inv_temp - mt);
-            P[t] = e;
-            zp += e;
-            if (has_kids) {
-                const float f = __expf(load_logit<BF16>(dlogits, row + t) * inv_temp - md);
-                Q[t] = f;
-                zq += f;
-            }
-        }
-        float Zp = block_sum(zp, s_redf, tid);
-        float Zq = has_kids ? block_sum(zq, s_redf, tid) : 0.0f;
-        __syncthreads();   // P and Q are complete and visible to the whole workgroup
+    }
+    __syncthreads();
 
-        // ---- try the children in node order
-        int accepted = -1;
-        int child = first;
-        while (has_kids && child != 0x7fffffff) {
-            const int x = min(max(s_tok[child], 0), vocab - 1);   // device metadata is trusted but kept inside the row
-            const float px = P[x], qx = Q[x];
-            const float ratio = qx > 0.0f ? (px / Zp) / (qx / Zq) : (px > 0.0f ? INFINITY : 0.0f);
-            if (u_accept[(int64_t)b * n_tree + child] < fminf(1.0f, ratio)) {
-                accepted = child;
-                break;
-            }
-            // rejected: residual target into the spare array, then swap; the token leaves the draft distribution
-            const float ip = 1.0f / Zp, iq = Zq > 0.0f ? 1.0f / Zq : 0.0f;
-            float s = 0.0f;
-            for (int t = tid; t < vocab; t += NT) {
-                const float r = fmaxf(P[t] * ip - Q[t] * iq, 0.0f);
-                R[t] = r;
-                s += r;
-            }
-            s = block_sum(s, s_redf, tid);
-            if (s > 0.0f) {   // (a zero residual means target == draft, which the test above never rejects)
-                float *tmp = P;
-                P = R;
-                R = tmp;
-                Zp = s;
-            }
-            __syncthreads();   // everybody has read Q[x] before it is cleared
-            if (tid == 0)
-                Q[x] = 0.0f;
-            Zq = fmaxf(Zq - qx, 0.0f);
-            // next child of the current node
-            int next = 0x7fffffff;
-            for (int i = tid; i < n_tree; i += NT)
-                if (i > child && s_par[i] == cur)
-                    next = min(next, i);
-            child = block_min_int(next, s_redi, tid);   // (its barriers also publish Q[x] = 0 and the new P)
-        }
-        if (accepted >= 0) {
-            cur = accepted;
-            depth++;
-            if (tid == 0)
-                path[depth] = cur;
-            continue;
-        }
-
-        // ---- no child accepted: draw the next token from P by inverting the cumulative sum in token order
-        const int cpt = (vocab + NT - 1) / NT;          // contiguous tokens per thread
-        const int t0 = min(tid * cpt, vocab), t1 = min(t0 + cpt, vocab);
+    // contiguous token range of this thread for the final draw (a multiple of 8 tokens per thread)
+    const int cpt = ((vocab + NT - 1) / NT + 7) & ~7;
+    const int t0 = min(tid * cpt, vocab), t1 = min(t0 + cpt, vocab);
+    // inverse-CDF draw over values val(t0..t1) read through `fetch8(t, v)` (8 tokens from t, zeros past the end)
+    auto draw = [&](auto fetch8) {
         float local = 0.0f;
-        for (int t = t0; t < t1; t++)
-            local += P[t];
-        // inclusive scan of the per-thread sums: inside a wave by shuffles, wave totals through LDS
-        float inc = local;
+        for (int t = t0; t < t1; t += 8) {
+            float v[8];
+            fetch8(t, v);
+#pragma unroll
+            for (int j = 0; j < 8; j++)
+                local += v[j];
+        }
+        float inc = local;   // inclusive scan of the per-thread sums: inside a wave by shuffles, wave totals through LDS
         for (int off = 1; off < 64; off <<= 1) {
             const float o = __shfl_up(inc, off);
             if (lane >= off)
@@ -204,44 +261,178 @@ __global__ __launch_bounds__(NT) void spec_accept_kernel(const void *tlogits, co
         const float before = base + inc - local;        // sum of all tokens below t0
         const float target = u_bonus[b] * total;
         // the first thread whose inclusive sum exceeds the target holds the token
-        int owner = (before + local > target && t1 > t0) ? tid : 0x7fffffff;
+        int owner = (before + local > target && t1 > t0) ? tid : NONE;
         owner = block_min_int(owner, s_redi, tid);
-        if (owner == 0x7fffffff) {
+        if (owner == NONE) {
             // rounding left the target at or above the total: the last token with mass
             int last = -1;
-            for (int t = t0; t < t1; t++)
-                if (P[t] > 0.0f)
-                    last = t;
+            for (int t = t0; t < t1; t += 8) {
+                float v[8];
+                fetch8(t, v);
+#pragma unroll
+                for (int j = 0; j < 8; j++)
+                    if (v[j] > 0.0f)
+                        last = t + j;
+            }
             last = -block_min_int(-last, s_redi, tid);
             if (tid == 0)
                 bonus_token[b] = max(last, 0);
         } else if (tid == owner) {
             float run = before;
             int pick = t1 - 1;
-            for (int t = t0; t < t1; t++) {
-                run += P[t];
-                if (run > target) {
-                    pick = t;
-                    break;
+            bool found = false;
+            for (int t = t0; t < t1 && !found; t += 8) {
+                float v[8];
+                fetch8(t, v);
+#pragma unroll
+                for (int j = 0; j < 8; j++) {
+                    run += v[j];
+                    if (!found && run > target && t + j < t1) {
+                        pick = t + j;
+                        found = true;
+                    }
                 }
             }
             bonus_token[b] = pick;
         }
+    };
+
+    int cur = 0, depth = 0;
+    for (;;) {
+        // ---- descend through first children whose (precomputed) test passes
+        int first = depth < max_depth ? s_first[cur] : NONE;
+        while (first != NONE && s_ok[first]) {
+            cur = first;
+            depth++;
+            if (tid == 0)
+                path[depth] = cur;
+            first = depth < max_depth ? s_first[cur] : NONE;
+        }
+        const int64_t row = (bt + cur) * vocab;
+        const float mt = s_mt[cur], md = s_md[cur];
+        if (first == NONE) {
+            // ---- no child to try: draw from the node's own target distribution, straight from the logits
+            draw([&](int t, float v[8]) {
+                load8<BF16>(tlogits, row, t, vocab, vec, v);
+#pragma unroll
+                for (int j = 0; j < 8; j++)
+                    v[j] = __expf(v[j] * inv_temp - mt);      // (-inf past the end gives 0)
+            });
+            break;
+        }
+        // ---- the first child was rejected: the residual target and the draft become arrays
+        const float ip = 1.0f / s_zt[cur], iq = s_zd[cur] > 0.0f ? 1.0f / s_zd[cur] : 0.0f;
+        float s = 0.0f;
+        for (int t = tid * 8; t < vocab; t += NT * 8) {
+            float tv[8], dv[8], r[8];
+            load8<BF16>(tlogits, row, t, vocab, vec, tv);
+            load8<BF16>(dlogits, row, t, vocab, vec, dv);
+#pragma unroll
+            for (int j = 0; j < 8; j++) {
+                tv[j] = __expf(tv[j] * inv_temp - mt);
+                dv[j] = __expf(dv[j] * inv_temp - md);
+                r[j] = fmaxf(tv[j] * ip - dv[j] * iq, 0.0f);
+                s += r[j];
+            }
+            if (vec) {
+                *reinterpret_cast<float4 *>(R + t) = float4{r[0], r[1], r[2], r[3]};
+                *reinterpret_cast<float4 *>(R + t + 4) = float4{r[4], r[5], r[6], r[7]};
+                *reinterpret_cast<float4 *>(Q + t) = float4{dv[0], dv[1], dv[2], dv[3]};
+                *reinterpret_cast<float4 *>(Q + t + 4) = float4{dv[4], dv[5], dv[6], dv[7]};
+            } else {
+#pragma unroll
+                for (int j = 0; j < 8; j++)
+                    if (t + j < vocab) {
+                        R[t + j] = r[j];
+                        Q[t + j] = dv[j];
+                    }
+            }
+        }
+        s = block_sum(s, s_redf, tid);
+        float Zp = s_zt[cur], Zq = s_zd[cur];
+        if (s > 0.0f) {
+            float *tmp = P;
+            P = R;
+            R = tmp;
+            Zp = s;
+        } else {
+            // a zero residual means target == draft, which the test never rejects; kept for completeness: P stays
+            for (int t = tid; t < vocab; t += NT)
+                P[t] = __expf(load_logit<BF16>(tlogits, row + t) * inv_temp - mt);
+        }
+        __syncthreads();   // the arrays are complete before anybody reads or clears an entry
         if (tid == 0)
-            accept_len[b] = depth;
-        return;
+            Q[s_tok[first]] = 0.0f;
+        Zq = fmaxf(Zq - s_qx[first], 0.0f);
+
+        // ---- try the later siblings in node order against the arrays
+        int accepted = -1;
+        int child = first;
+        for (;;) {
+            int next = NONE;
+            for (int i = tid; i < n_tree; i += NT)
+                if (i > child && s_par[i] == cur)
+                    next = min(next, i);
+            child = block_min_int(next, s_redi, tid);   // (its barriers also publish the cleared entry and the new P)
+            if (child == NONE)
+                break;
+            const int x = s_tok[child];
+            const float px = P[x], qx = Q[x];
+            const float ratio = qx > 0.0f ? (px / Zp) / (qx / Zq) : (px > 0.0f ? INFINITY : 0.0f);
+            if (u_accept[bt + child] < fminf(1.0f, ratio)) {
+                accepted = child;
+                break;
+            }
+            const float ip2 = 1.0f / Zp, iq2 = Zq > 0.0f ? 1.0f / Zq : 0.0f;
+            float s2 = 0.0f;
+            for (int t = tid; t < vocab; t += NT) {
+                const float r = fmaxf(P[t] * ip2 - Q[t] * iq2, 0.0f);
+                R[t] = r;
+                s2 += r;
+            }
+            s2 = block_sum(s2, s_redf, tid);
+            if (s2 > 0.0f) {
+                float *tmp = P;
+                P = R;
+                R = tmp;
+                Zp = s2;
+            }
+            __syncthreads();   // everybody has read Q[x] before it is cleared
+            if (tid == 0)
+                Q[x] = 0.0f;
+            Zq = fmaxf(Zq - qx, 0.0f);
+        }
+        if (accepted >= 0) {
+            cur = accepted;
+            depth++;
+            if (tid == 0)
+                path[depth] = cur;
+            __syncthreads();   // the arrays may be rewritten at a deeper node: finish reading them first
+            continue;
+        }
+        // ---- every child rejected: draw from the residual array
+        const float *Pc = P;
+        draw([&](int t, float v[8]) {
+#pragma unroll
+            for (int j = 0; j < 8; j++)
+                v[j] = t + j < vocab ? Pc[t + j] : 0.0f;
+        });
+        break;
     }
+    if (tid == 0)
+        accept_len[b] = depth;
 }
 
 }  // namespace
 
 extern "C" {
 
-size_t dream_spec_accept_workspace(int32_t batch, int32_t vocab)
+size_t dream_spec_accept_workspace(int32_t batch, int32_t n_tree, int32_t vocab)
 {
-    if (batch < 1 || vocab < 1)
+    if (batch < 1 || n_tree < 1 || vocab < 1)
         return DREAM_WORKSPACE_HEADER_BYTES;
-    return DREAM_WORKSPACE_HEADER_BYTES + align_up((size_t)batch * 3 * vocab * sizeof(float), 256);
+    const size_t stats = align_up((size_t)2 * batch * n_tree * ceil_div(vocab, STAT_CHUNK) * sizeof(float), 256);
+    return DREAM_WORKSPACE_HEADER_BYTES + align_up((size_t)batch * 3 * vocab * sizeof(float), 256) + 2 * stats;
 }
 
 int dream_spec_accept(const void *target_logits, const void *draft_logits, int32_t logits_dtype, int32_t batch, int32_t n_tree,
@@ -258,19 +449,40 @@ int dream_spec_accept(const void *target_logits, const void *draft_logits, int32
         return fail(DREAM_ERR_INVALID_ARG, "%s: batch in [1, 65535], vocab positive and 0 <= max_depth < %d required", who, NT);
     if (n_tree < 1 || n_tree > DREAM_MAX_TREE_ACCEPT)
         return fail(DREAM_ERR_UNSUPPORTED, "%s: n_tree %d outside [1, %d]", who, n_tree, DREAM_MAX_TREE_ACCEPT);
+    if ((int64_t)batch * n_tree > 65535)
+        return fail(DREAM_ERR_UNSUPPORTED, "%s: batch * n_tree = %lld exceeds 65535 rows", who, (long long)batch * n_tree);
     if (!(temperature > 0.0f))
         return fail(DREAM_ERR_INVALID_ARG, "%s: temperature must be positive (use dream_accept_path for the greedy rule)", who);
-    const size_t need = dream_spec_accept_workspace(batch, vocab);
+    const size_t need = dream_spec_accept_workspace(batch, n_tree, vocab);
     if (!workspace || workspace_bytes < need)
         return fail(DREAM_ERR_WORKSPACE, "%s: workspace of %zu bytes, %zu needed", who, workspace_bytes, need);
-    float *work = reinterpret_cast<float *>(static_cast<char *>(workspace) + DREAM_WORKSPACE_HEADER_BYTES);
-    if (logits_dtype == DREAM_BF16)
-        hipLaunchKernelGGL(spec_accept_kernel<true>, dim3(batch), dim3(NT), 0, as_stream(stream), target_logits, draft_logits, n_tree, vocab,
-                           token, parent, u_accept, u_bonus, max_depth, 1.0f / temperature, work, accept_len, accept_path, bonus_token);
-    else
-        hipLaunchKernelGGL(spec_accept_kernel<false>, dim3(batch), dim3(NT), 0, as_stream(stream), target_logits, draft_logits, n_tree, vocab,
-                           token, parent, u_accept, u_bonus, max_depth, 1.0f / temperature, work, accept_len, accept_path, bonus_token);
-    return check_launch("spec_accept_kernel");
+    const int n_chunks = ceil_div(vocab, STAT_CHUNK);
+    const size_t stats = align_up((size_t)2 * batch * n_tree * n_chunks * sizeof(float), 256);
+    char *wsb = static_cast<char *>(workspace) + DREAM_WORKSPACE_HEADER_BYTES;
+    float *work = reinterpret_cast<float *>(wsb);
+    float *stat_m = reinterpret_cast<float *>(wsb + align_up((size_t)batch * 3 * vocab * sizeof(float), 256));
+    float *stat_s = reinterpret_cast<float *>(reinterpret_cast<char *>(stat_m) + stats);
+    const int esz = logits_dtype == DREAM_BF16 ? 2 : 4;
+    const bool vec = vocab % 8 == 0 &&
+                     ((reinterpret_cast<uintptr_t>(target_logits) | reinterpret_cast<uintptr_t>(draft_logits) |
+                       reinterpret_cast<uintptr_t>(workspace)) & 15) == 0 && ((size_t)vocab * esz) % 16 == 0;
+    const float inv_temp = 1.0f / temperature;
+    hipStream_t st = as_stream(stream);
+    const dim3 sgrid(n_chunks, batch * n_tree, 2);
+    if (logits_dtype == DREAM_BF16) {
+        hipLaunchKernelGGL(softmax_stats_kernel<true>, sgrid, dim3(256), 0, st, target_logits, draft_logits, n_tree, vocab, n_chunks, vec,
+                           parent, inv_temp, stat_m, stat_s);
+        hipLaunchKernelGGL(spec_walk_kernel<true>, dim3(batch), dim3(NT), 0, st, target_logits, draft_logits, n_tree, vocab, n_chunks, vec,
+                           token, parent, u_accept, u_bonus, max_depth, inv_temp, stat_m, stat_s, work, accept_len, accept_path,
+                           bonus_token);
+    } else {
+        hipLaunchKernelGGL(softmax_stats_kernel<false>, sgrid, dim3(256), 0, st, target_logits, draft_logits, n_tree, vocab, n_chunks, vec,
+                           parent, inv_temp, stat_m, stat_s);
+        hipLaunchKernelGGL(spec_walk_kernel<false>, dim3(batch), dim3(NT), 0, st, target_logits, draft_logits, n_tree, vocab, n_chunks, vec,
+                           token, parent, u_accept, u_bonus, max_depth, inv_temp, stat_m, stat_s, work, accept_len, accept_path,
+                           bonus_token);
+    }
+    return check_launch("spec_accept kernels");
 }
 
 }  // extern "C"

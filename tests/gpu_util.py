@@ -183,7 +183,7 @@ def run_spec_accept(tlogits: np.ndarray, dlogits: np.ndarray, dtype: str, token,
     alen = torch.full((B,), -7, dtype=torch.int32, device="cuda")
     path = torch.full((B, max_depth + 1), -7, dtype=torch.int32, device="cuda")
     bonus = torch.full((B,), -7, dtype=torch.int32, device="cuda")
-    ws = dream.alloc_workspace(dream.dream_spec_accept_workspace(B, V))
+    ws = dream.alloc_workspace(dream.dream_spec_accept_workspace(B, T, V))
     dream.dream_spec_accept(tl, dl, DT[dtype], B, T, V, tok, par, ua, ub, max_depth, temperature, alen, path, bonus, ws)
     torch.cuda.synchronize()
     return alen.cpu().numpy(), path.cpu().numpy(), bonus.cpu().numpy()
