@@ -50,6 +50,11 @@ __device__ __forceinline__ uint64_t row_rotate(uint64_t k)
     const uint32_t hi = __builtin_amdgcn_update_dpp(0u, (uint32_t)(k >> 32), ctrl, 0xf, 0xf, false);
     return ((uint64_t)hi << 32) | lo;
 }
+template <int ROT>
+__device__ __forceinline__ float row_rotate_f(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x120 + ROT, 0xf, 0xf, false));
+}
 __device__ __forceinline__ uint64_t lane_value(uint64_t k, int lane)
 {
     return ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(k >> 32), lane) << 32) | (uint32_t)__builtin_amdgcn_readlane((int)k, lane);
@@ -126,6 +131,7 @@ __global__ __launch_bounds__(256) void expand_partial_kernel(const void *logits,
 #pragma unroll
     for (int e = 0; e < PER_THREAD; e++)
         m = fmaxf(m, x[e]);
+    const float tmax = m;   // this thread's maximum (padding is -inf)
     for (int off = 32; off > 0; off >>= 1)
         m = fmaxf(m, __shfl_xor(m, off));
     if (lane == 0)
@@ -147,6 +153,67 @@ __global__ __launch_bounds__(256) void expand_partial_kernel(const void *logits,
         part_s[row * n_chunks + chunk] = (s_f[0] + s_f[1]) + (s_f[2] + s_f[3]);
     }
 
+    // ---- the chunk's k largest.  A lower bound of the k-th largest value first: the 256 thread maxima fall into
+    // 16 rows of 16 lanes, and the k-th largest of the 16 row maxima has at least k elements at or above it.
+    // Elements at or above that bound (a few dozen for ordinary logits) are collected in LDS and ranked by
+    // counting; more than 256 of them (heavy ties) fall back to k rounds of a block-wide arg-max.
+    __shared__ float s_row[16];
+    __shared__ float s_tau;
+    __shared__ int s_count;
+    __shared__ uint64_t s_cand[256];
+    float rm = tmax;
+    rm = fmaxf(rm, row_rotate_f<8>(rm));
+    rm = fmaxf(rm, row_rotate_f<4>(rm));
+    rm = fmaxf(rm, row_rotate_f<2>(rm));
+    rm = fmaxf(rm, row_rotate_f<1>(rm));
+    if ((lane & 15) == 0)
+        s_row[tid >> 4] = rm;
+    if (tid == 0)
+        s_count = 0;
+    __syncthreads();
+    if (tid < 16) {
+        const float mine = s_row[tid];
+        int rank = 0;
+#pragma unroll
+        for (int j = 0; j < 16; j++) {
+            const float o = s_row[j];
+            rank += (o > mine || (o == mine && j < tid)) ? 1 : 0;
+        }
+        if (rank == min(k, 16) - 1)
+            s_tau = mine;
+    }
+    __syncthreads();
+    const float tau = s_tau;
+    int overflow = 0;
+#pragma unroll
+    for (int e = 0; e < PER_THREAD; e++) {
+        const int t = begin + (e >> 3) * 2048 + tid * 8 + (e & 7);
+        if (t < vocab && x[e] >= tau) {
+            const int slot = atomicAdd(&s_count, 1);
+            if (slot < 256)
+                s_cand[slot] = make_key(x[e], t);
+            else
+                overflow = 1;
+        }
+    }
+    __syncthreads();
+    const int n_cand = s_count;
+    uint64_t *out_key = part_key + (row * n_chunks + chunk) * k;
+    if (n_cand <= 256) {
+        if (tid < n_cand) {
+            const uint64_t mine = s_cand[tid];
+            int rank = 0;
+#pragma unroll 8
+            for (int j = 0; j < n_cand; j++)
+                rank += s_cand[j] > mine ? 1 : 0;
+            if (rank < k)
+                out_key[rank] = mine;
+        }
+        if (tid >= n_cand && tid < k)
+            out_key[tid] = 0ull;   // fewer than k tokens in the chunk
+        return;
+    }
+    (void)overflow;
     // keys of this thread's elements (0 for tokens past the vocabulary: below every real key)
     uint64_t key[PER_THREAD];
 #pragma unroll
@@ -173,7 +240,7 @@ __global__ __launch_bounds__(256) void expand_partial_kernel(const void *logits,
             best = s_k[w] > best ? s_k[w] : best;
         __syncthreads();
         if (tid == 0)
-            part_key[(row * n_chunks + chunk) * k + r] = best;   // 0 once the chunk is exhausted
+            out_key[r] = best;   // 0 once the chunk is exhausted
         prev = best;
     }
 }

@@ -75,6 +75,20 @@ def test_exact_ties_resolve_toward_lower_indices(gu):
     assert tok[0, 0].tolist() == [9000, 17000, 0, 1, 2, 3]
 
 
+@pytest.mark.parametrize("levels", [40, 200, 3000])
+def test_heavily_tied_logits(gu, levels):
+    """Logits drawn from a small set of values: the candidate lists of the selection hold from a handful to
+    hundreds of equal values (both of its paths), and ties must still resolve toward lower token indices."""
+    V, F, k = 20000, 3, 10
+    g = di.rng(500 + levels, 401)
+    logits = (g.integers(0, levels, size=(2, F, V)) * (8.0 / levels)).astype(np.float32)
+    cum = np.zeros((2, F), dtype=np.float32)
+    tok, sc, _ = gu.run_expand(logits, "f32", cum, k)
+    want_tok, want_sc, _ = oracle.expand_level(logits.astype(np.float64), cum.astype(np.float64), k)
+    assert np.array_equal(tok, want_tok)
+    assert np.abs(sc - want_sc).max() <= SCORE_TOL
+
+
 def test_finalize_bit_exact_including_ties(gu):
     g = di.rng(77, 400)
     for N, budget in [(85, 32), (85, 100), (2, 1), (1, 5), (1024, 59), (601, 600), (333, 0)]:
