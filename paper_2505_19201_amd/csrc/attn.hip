@@ -851,6 +851,11 @@ int make_plan(const dream_attn_desc *d, int n_q, int64_t max_kv_len, Plan *p)
             qg = qg_max;
         if (base * ceil_div(n_qtiles, 4 * qg) < 256)
             qg = 1;
+        // measured at 32 sequences of a 4-way grouped-query model: below about four workgroups per CU the
+        // chip hides latency better with more, smaller workgroups than it gains from sharing LDS reads
+        // (head_dim 256 is the exception: its tiles are twice the bytes to re-read)
+        while (d->head_dim <= 128 && qg > 1 && base * ceil_div(n_qtiles, 4 * qg) < 1024)
+            qg /= 2;
     }
     if (qg > qg_max)
         qg = qg_max;
