@@ -239,27 +239,15 @@ def main() -> int:
     return 0
 
 
-def read_ceiling(torch, dream, bytes_launch, L):
-    """What a launch that only READS the verification kernel's algorithmic bytes costs: L back-to-back launches
-    of the library's plain 16-byte-load read kernel over L distinct buffers, replayed as a HIP graph like the
-    verification phase.  The attention kernel cannot beat this; it is the ceiling the roofline fraction of a
-    single-sequence launch should be read against."""
-    n = (bytes_launch + 15) // 16 * 16
-    buf = torch.empty(L * n, dtype=torch.uint8, device="cuda").random_(0, 255)
-    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+def graph_time_us(torch, body, reps=20, warm=3):
+    """Capture `body()` (library calls only) into one HIP graph on a side stream and return the mean time of
+    one replay in microseconds, by HIP events on that stream.  `body` must have run eagerly once before."""
     stream = torch.cuda.Stream()
-
-    def run():
-        for l in range(L):
-            dream.dream_stream_read(buf, n, sink, offset_bytes=l * n)
-    run()
-    torch.cuda.synchronize()
     g = torch.cuda.CUDAGraph()
     with torch.cuda.graph(g, stream=stream):
-        run()
-    reps = 20
+        body()
     with torch.cuda.stream(stream):
-        for _ in range(3):
+        for _ in range(warm):
             g.replay()
         stream.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -268,7 +256,24 @@ def read_ceiling(torch, dream, bytes_launch, L):
             g.replay()
         e1.record()
         stream.synchronize()
-    us = e0.elapsed_time(e1) * 1e3 / (reps * L)
+    return e0.elapsed_time(e1) * 1e3 / reps
+
+
+def read_ceiling(torch, dream, bytes_launch, L):
+    """What a launch that only READS the verification kernel's algorithmic bytes costs: L back-to-back launches
+    of the library's plain 16-byte-load read kernel over L distinct buffers, replayed as a HIP graph like the
+    verification phase.  The attention kernel cannot beat this; it is the ceiling the roofline fraction of a
+    single-sequence launch should be read against."""
+    n = (bytes_launch + 15) // 16 * 16
+    buf = torch.empty(L * n, dtype=torch.uint8, device="cuda").random_(0, 255)
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+
+    def run():
+        for l in range(L):
+            dream.dream_stream_read(buf, n, sink, offset_bytes=l * n)
+    run()
+    torch.cuda.synchronize()
+    us = graph_time_us(torch, run) / L
     gbs = n / (us * 1e-6) / 1e9
     return {"kernel": "stream_read_kernel (16-byte loads, no writes)", "bytes_per_launch": n, "launch_us": round(us, 3),
             "achieved": round(gbs, 1), "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4)}
@@ -292,23 +297,7 @@ def spec_accept_leg(torch, dream, logits, token, parent, cfg):
         dream.dream_spec_accept(logits, dlogits, dream.BF16, B, T, V, token, parent, ua, ub, cfg.depth, 1.0, alen, path, bonus, ws)
     run()
     torch.cuda.synchronize()
-    stream = torch.cuda.Stream()
-    gr = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(gr, stream=stream):
-        for _ in range(4):
-            run()
-    reps = 20
-    with torch.cuda.stream(stream):
-        for _ in range(3):
-            gr.replay()
-        stream.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(reps):
-            gr.replay()
-        e1.record()
-        stream.synchronize()
-    us = e0.elapsed_time(e1) * 1e3 / (reps * 4)
+    us = graph_time_us(torch, lambda: [run() for _ in range(4)]) / 4
     return {"temperature": 1.0, "us": round(us, 2), "mean_accept_len": round(float(alen.float().mean().item()), 3)}
 
 
@@ -321,23 +310,7 @@ def entropy_leg(torch, dream, desc, pq, k_cache, P):
     ws = dream.alloc_workspace(dream.dream_attention_entropy_workspace(desc, P))
     dream.dream_attention_entropy(desc, pq, None, P, k_cache, P, row, ae, ws)
     torch.cuda.synchronize()
-    stream = torch.cuda.Stream()
-    g = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(g, stream=stream):
-        for _ in range(4):
-            dream.dream_attention_entropy(desc, pq, None, P, k_cache, P, row, ae, ws)
-    reps = 20
-    with torch.cuda.stream(stream):
-        for _ in range(3):
-            g.replay()
-        stream.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(reps):
-            g.replay()
-        e1.record()
-        stream.synchronize()
-    us = e0.elapsed_time(e1) * 1e3 / (reps * 4)
+    us = graph_time_us(torch, lambda: [dream.dream_attention_entropy(desc, pq, None, P, k_cache, P, row, ae, ws) for _ in range(4)]) / 4
     return {"rows": P, "us": round(us, 2), "ae": [round(float(x), 4) for x in ae.cpu().tolist()[:4]]}
 
 
@@ -371,23 +344,7 @@ def tree_build_leg(torch, dream, di, cfg):
         dream.dream_tree_finalize(pool_score, pool_parent, pool_token, B, n_pool, budget, tp, tt, ti)
     run()
     torch.cuda.synchronize()
-    stream = torch.cuda.Stream()
-    g = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(g, stream=stream):
-        for _ in range(4):
-            run()
-    reps = 20
-    with torch.cuda.stream(stream):
-        for _ in range(3):
-            g.replay()
-        stream.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(reps):
-            g.replay()
-        e1.record()
-        stream.synchronize()
-    us = e0.elapsed_time(e1) * 1e3 / (reps * 4)
+    us = graph_time_us(torch, lambda: [run() for _ in range(4)]) / 4
     nbytes = sum(lv[0].numel() * 2 for lv in levels)
     return {"levels": depth, "k": k, "budget": budget, "launches": 2 * depth + 1, "us": round(us, 2), "logit_bytes": nbytes,
             "achieved_GBs": round(nbytes / (us * 1e-6) / 1e9, 1), "bound": "hbm (launch latency at one sequence)"}
@@ -417,23 +374,7 @@ def project_leg(torch, dream, desc, xk, xv, prefix_len, frontier, cfg):
                                               (s, wv[i], Hkv, prefix_len, frontier, xv)], R, hid)
     run(0)
     torch.cuda.synchronize()
-    stream = torch.cuda.Stream()
-    g = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(g, stream=stream):
-        for i in range(per_graph):
-            run(i)
-    reps = 20
-    with torch.cuda.stream(stream):
-        for _ in range(3):
-            g.replay()
-        stream.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(reps):
-            g.replay()
-        e1.record()
-        stream.synchronize()
-    us = e0.elapsed_time(e1) * 1e3 / (reps * per_graph)
+    us = graph_time_us(torch, lambda: [run(i) for i in range(per_graph)]) / per_graph
     nbytes = 2 * hid * (Hq + 2 * Hkv) * D + 2 * B * R * hid * 2 + 2 * B * R * (Hq + 2 * Hkv) * D
     return {"rows": B * R, "us_per_level": round(us, 2), "bytes": nbytes, "achieved_GBs": round(nbytes / (us * 1e-6) / 1e9, 1),
             "bound": "hbm"}
@@ -444,26 +385,11 @@ def kv_commit_leg(torch, dream, desc, caches, prefix_len, T, accept_path, accept
     path's rows in the K and V caches of every layer.  Timed as a replayed graph; it runs last because it
     rewrites the tree rows of the caches."""
     new_len = torch.empty_like(prefix_len)
-    stream = torch.cuda.Stream()
     dream.dream_kv_commit(desc, caches, prefix_len, T, accept_path, accept_len, new_len)
     torch.cuda.synchronize()
     per_graph = 16   # a lone kernel per graph would time the graph launch, not the kernel
-    g = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(g, stream=stream):
-        for _ in range(per_graph):
-            dream.dream_kv_commit(desc, caches, prefix_len, T, accept_path, accept_len, new_len)
-    reps = 20
-    with torch.cuda.stream(stream):
-        for _ in range(3):
-            g.replay()
-        stream.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(reps):
-            g.replay()
-        e1.record()
-        stream.synchronize()
-    us = e0.elapsed_time(e1) * 1e3 / (reps * per_graph)
+    us = graph_time_us(torch, lambda: [dream.dream_kv_commit(desc, caches, prefix_len, T, accept_path, accept_len, new_len)
+                                       for _ in range(per_graph)]) / per_graph
     rows = int((accept_len + 1).sum().item())
     nbytes = 2 * len(caches) * cfg.n_kv_heads * rows * cfg.head_dim * 2   # read + write of the path rows
     assert new_len.cpu().tolist() == (prefix_len + accept_len + 1).cpu().tolist()

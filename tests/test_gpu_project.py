@@ -17,11 +17,6 @@ def gu():
     import torch
     assert torch.cuda.is_available(), "these tests need the MI355X"
     from tests import gpu_util
-    return gu_module()
-
-
-def gu_module():
-    from tests import gpu_util
     return gpu_util
 
 
