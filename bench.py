@@ -354,11 +354,11 @@ def project_leg(torch, dream, desc, xk, xv, prefix_len, frontier, cfg):
     """Eq. 1's three linear maps for one draft level (not part of `value`): the frontier rows' queries
     (W_Q: hidden -> Hq D, dense output) and the same rows' keys and values written into the draft cache at
     prefix_len + node (W_K, W_V: hidden -> Hkv D).  The weights are read once per call and dominate the bytes;
-    One launch per level carries all three maps; 2 levels per graph, each with its own weights so nothing is
-    served from L2."""
+    One launch per level carries all three maps; 4 levels per graph, each with its own weights (more than the
+    last-level cache holds together), so every launch streams from HBM."""
     B, R = frontier.shape
     Hq, Hkv, D, hid = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.hidden
-    per_graph = 2
+    per_graph = 4
 
     def rnd(*shape):
         return torch.randn(*shape, dtype=torch.float32, device="cuda").mul_(hid ** -0.5).to(torch.bfloat16)

@@ -6,9 +6,11 @@
 // M = B*R is small (<= a few hundred) and the weight matrix [N, hidden] is large, so the call is bound by
 // streaming the weights once from HBM.  One workgroup owns 16 output features (16 weight rows, contiguous in
 // memory); its 8 waves split the hidden dimension, each computing C^T[n][m] += W[n][k] X[m][k] with
-// v_mfma_f32_16x16x32_bf16 (A = weight rows, B = feature rows, both loaded from global memory directly in the
-// operand layout: every weight byte is used by exactly one wave, so staging it in LDS would add nothing), for up
-// to 4 tiles of 16 feature rows at a time; the 8 partial tiles are summed through LDS in wave order and the
+// v_mfma_f32_16x16x32_bf16 (A = weight rows, B = feature rows).  With at most 16 feature rows (the paper's
+// shapes) a wave fetches 256 contiguous bytes of each row at a time and passes them through a private LDS area
+// to reach the operand layout: nobody else reads those bytes, but an operand-layout load touches 16 rows x 64
+// bytes per instruction, half cache lines, and measures 10-13 % slower.  With more rows (up to 4 tiles of 16 at
+// a time) the operands are loaded directly.  The 8 partial tiles are summed through LDS in wave order and the
 // rows are rounded to bf16 and scattered.  Roofline: HBM, N*hidden*2 weight bytes per call.
 #include "common.h"
 
@@ -17,6 +19,13 @@ using namespace dream;
 namespace {
 
 constexpr int NWAVE = 8;
+
+__device__ __forceinline__ void wave_lds_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
 
 struct ProjJob {
     const uint16_t *x, *w;
@@ -80,23 +89,72 @@ __global__ __launch_bounds__(64 * NWAVE) void project_kernel(ProjArgs args)
             const int m = min(m0 + mt * 16 + c, a.m_total - 1);   // padding rows repeat the last row; never stored
             xrow[mt] = a.x + (int64_t)m * K + wave * kw + g * 8;
         }
-        constexpr int U = MT == 1 ? 8 : (MT == 2 ? 4 : 2);        // k-steps whose loads are in flight together
-        for (int k = 0; k < kw; k += 32 * U) {
-            bf16x8 wf[U], xf[U][MT];
+        if (MT == 1) {
+            // Rows are fetched 256 contiguous bytes at a time (4 rows per load instruction: full cache lines) into
+            // a wave-private LDS area and read back in operand layout; loading the operands directly would make
+            // every instruction touch 16 rows x 64 bytes.
+            constexpr int SS = 128, RSTR = SS + 8;             // elements of a row per super-step; padded LDS row stride
+            __shared__ __attribute__((aligned(16))) uint16_t s_stage[NWAVE][2][16 * RSTR];
+            uint16_t *lw = s_stage[wave][0], *lx = s_stage[wave][1];
+            const int lrow = lane >> 4, lcol = (lane & 15) * 8;
+            const int n_ss = (kw + SS - 1) / SS;
+            const uint16_t *wsrc = a.w + (int64_t)n0 * K + wave * kw;
+            const uint16_t *xsrc = a.x + wave * kw;
+            auto issue = [&](int s, u32x4 (&wr)[4], u32x4 (&xr)[4]) {
+                s = min(s, n_ss - 1);                              // the prefetch past the end re-reads and is dropped
+                const int nvalid = min(SS, kw - s * SS);
+                const int col = s * SS + (lcol < nvalid ? lcol : 0);
 #pragma unroll
-            for (int u = 0; u < U; u++) {
-                const int kk = min(k + 32 * u, kw - 32);            // (kw is a multiple of 32; a short tail re-reads and is skipped below)
-                wf[u] = *reinterpret_cast<const bf16x8 *>(wrow + kk);
+                for (int j = 0; j < 4; j++) {
+                    wr[j] = *reinterpret_cast<const u32x4 *>(wsrc + (int64_t)(j * 4 + lrow) * K + col);
+                    const int m = min(m0 + j * 4 + lrow, a.m_total - 1);
+                    xr[j] = *reinterpret_cast<const u32x4 *>(xsrc + (int64_t)m * K + col);
+                }
+            };
+            // one super-step: registers -> LDS, request the super-step that reuses these registers, multiply
+            auto step = [&](int s, u32x4 (&wr)[4], u32x4 (&xr)[4]) {
 #pragma unroll
-                for (int mt = 0; mt < MT; mt++)
-                    xf[u][mt] = *reinterpret_cast<const bf16x8 *>(xrow[mt] + kk);
-            }
+                for (int j = 0; j < 4; j++) {
+                    *reinterpret_cast<u32x4 *>(lw + (j * 4 + lrow) * RSTR + lcol) = wr[j];
+                    *reinterpret_cast<u32x4 *>(lx + (j * 4 + lrow) * RSTR + lcol) = xr[j];
+                }
+                issue(s + 1, wr, xr);
+                wave_lds_fence();
+                const int nvalid = min(SS, kw - s * SS);
 #pragma unroll
-            for (int u = 0; u < U; u++) {
-                if (k + 32 * u < kw) {
+                for (int ks = 0; ks < SS / 32; ks++) {
+                    if (ks * 32 < nvalid) {
+                        const bf16x8 af = *reinterpret_cast<const bf16x8 *>(lw + c * RSTR + ks * 32 + g * 8);
+                        const bf16x8 bfr = *reinterpret_cast<const bf16x8 *>(lx + c * RSTR + ks * 32 + g * 8);
+                        acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, bfr, acc[0], 0, 0, 0);
+                    }
+                }
+                wave_lds_fence();
+            };
+            u32x4 wr[4], xr[4];
+            issue(0, wr, xr);
+            for (int s = 0; s < n_ss; s++)
+                step(s, wr, xr);
+        } else
+        {
+        constexpr int U = 8 / MT;        // k-steps whose loads are in flight together
+            for (int k = 0; k < kw; k += 32 * U) {
+                bf16x8 wf[U], xf[U][MT];
+#pragma unroll
+                for (int u = 0; u < U; u++) {
+                    const int kk = min(k + 32 * u, kw - 32);            // (kw is a multiple of 32; a short tail re-reads and is skipped below)
+                    wf[u] = *reinterpret_cast<const bf16x8 *>(wrow + kk);
 #pragma unroll
                     for (int mt = 0; mt < MT; mt++)
-                        acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[u], xf[u][mt], acc[mt], 0, 0, 0);
+                        xf[u][mt] = *reinterpret_cast<const bf16x8 *>(xrow[mt] + kk);
+                }
+#pragma unroll
+                for (int u = 0; u < U; u++) {
+                    if (k + 32 * u < kw) {
+#pragma unroll
+                        for (int mt = 0; mt < MT; mt++)
+                            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[u], xf[u][mt], acc[mt], 0, 0, 0);
+                    }
                 }
             }
         }
