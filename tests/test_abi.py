@@ -195,7 +195,7 @@ def test_spec_accept_argument_errors(lib):
     assert call(temp=0.0) == -1 and call(temp=-1.0) == -1
     assert "greedy" in dream.dream_last_error()
     need = dream.dream_spec_accept_workspace(1, 60, 32000)
-    assert need == 65536 + 3 * 32000 * 4 + 2 * 2048 and call(nb=need - 1) == -3 and call(ws=None) == -3
+    assert need == 65536 + 3 * 32000 * 4 + 3 * 2048 + 1024 and call(nb=need - 1) == -3 and call(ws=None) == -3
     assert call(B=1100, T=60) == -2                  # more than 65535 rows
 
 

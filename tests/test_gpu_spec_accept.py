@@ -64,6 +64,7 @@ def _case(gu, B, T, depth, V, dtype, seed, spread=2.0, noise=0.7, temperature=1.
     assert np.array_equal(alen[clear], want_len[clear]), (alen[clear], want_len[clear])
     assert np.array_equal(path[clear], want_path[clear])
     assert np.array_equal(bonus[clear], want_bonus[clear])
+    _case.last = (parent, detail, clear)
     return alen, clear
 
 
@@ -117,3 +118,26 @@ def test_trees_of_the_paper_shape(gu, dtype, temperature):
 def test_full_size_vocabularies(gu, name):
     cfg = di.CONFIGS[name]
     _case(gu, 4, cfg.n_tree, cfg.depth, cfg.vocab, "bf16", cfg.seed, min_clear=0.25)
+
+
+def test_every_branch_of_the_walk_is_exercised(gu):
+    """The kernel treats the first rejection at a node symbolically, the second by building arrays, and draws in
+    three different ways; the oracle's record of the tests says which of these each compared sequence took."""
+    _case(gu, 96, 33, 6, 4000, "bf16", 950, noise=1.0)
+    parent, detail, clear = _case.last
+    seen = set()
+    for b in np.flatnonzero(clear):
+        by_node = {}
+        for node, ratio, u in detail[b]["tests"]:
+            by_node.setdefault(int(parent[b, node]), []).append(u < min(1.0, ratio))
+        for outcomes in by_node.values():
+            if outcomes[-1]:
+                seen.add(("accepted as child number", min(len(outcomes), 3)))
+            else:
+                seen.add(("all rejected, children", min(len(outcomes), 3)))
+        if not by_node or all(o[-1] for o in by_node.values()):
+            seen.add(("draw at a node without children",))
+    want = {("accepted as child number", 1), ("accepted as child number", 2), ("accepted as child number", 3),
+            ("all rejected, children", 1), ("all rejected, children", 2), ("all rejected, children", 3),
+            ("draw at a node without children",)}
+    assert want <= seen, want - seen
