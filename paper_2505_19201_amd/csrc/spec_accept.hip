@@ -19,9 +19,12 @@
 // writes the second residual and the reduced draft: unnormalised floats in the workspace, L2-resident); later
 // siblings are tested against those, one pass per further rejection, and an accepted sibling returns to the
 // table walk.  A draw is per-thread contiguous partial sums, a block scan and one thread's rescan.  Every
-// reduction has a fixed order, so the result is reproducible.  Roofline: HBM, one read of the logit rows (a
-// second read of the rows of nodes with children).
+// reduction has a fixed order, so the result is reproducible.  With at most 12 chunks per row (98304 tokens)
+// the second kernel is skipped: the walk merges the statistics itself and sums the first residual of a node only
+// when a first child is rejected there, which is cheaper than a launch for short rows.  Roofline: HBM, one read
+// of the logit rows (a second read of the rows of nodes with children).
 #include "common.h"
+#include <type_traits>
 
 using namespace dream;
 
@@ -276,7 +279,12 @@ __global__ __launch_bounds__(256) void residual_stats_kernel(const void *tlogits
         res_sum[node_row * n_chunks + chunk] = (red[0] + red[1]) + (red[2] + red[3]);
 }
 
-template <bool BF16>
+// LAZY (at most LAZY_CHUNKS chunks per row): residual_stats_kernel has not run; the walk merges the chunk
+// statistics of every node itself and sums the first residual over the chunks of a node only when a first child
+// is rejected there: one pass of the workgroup over two short rows is cheaper than a launch.
+constexpr int LAZY_CHUNKS = 12;
+
+template <bool BF16, bool LAZY>
 __global__ __launch_bounds__(NT) void spec_walk_kernel(const void *tlogits, const void *dlogits, int n_tree, int vocab, int n_chunks,
                                                        bool vec, const int32_t *token, const int32_t *parent, const float *u_accept,
                                                        const float *u_bonus, int max_depth, float inv_temp, const float *stat_m,
@@ -301,8 +309,47 @@ __global__ __launch_bounds__(NT) void spec_walk_kernel(const void *tlogits, cons
         s_par[i] = par < i ? par : -1;
         s_tok[i] = min(max(token[bt + i], 0), vocab - 1);   // device metadata is trusted but kept inside the row
         s_first[i] = NONE;
-        const float4 ns = node_stats[bt + i];
-        s_mt[i] = ns.x; s_zt[i] = ns.y; s_md[i] = ns.z; s_zd[i] = ns.w;
+        if (LAZY) {
+            const int64_t rows_all = (int64_t)gridDim.x * n_tree;
+            const float *tm = stat_m + (bt + i) * n_chunks, *ts = stat_s + (bt + i) * n_chunks;
+            const float *dm = stat_m + (rows_all + bt + i) * n_chunks, *dsum = stat_s + (rows_all + bt + i) * n_chunks;
+            // one row at a time: a workgroup of 1024 threads has 128 registers per thread
+            float mt = -INFINITY, md = -INFINITY, zt = 0.0f, zd = 0.0f;
+            {
+                float am[LAZY_CHUNKS], as[LAZY_CHUNKS];
+#pragma unroll
+                for (int u = 0; u < LAZY_CHUNKS; u++) {
+                    am[u] = u < n_chunks ? tm[u] : -INFINITY;
+                    as[u] = u < n_chunks ? ts[u] : 0.0f;
+                }
+#pragma unroll
+                for (int u = 0; u < LAZY_CHUNKS; u++)
+                    mt = fmaxf(mt, am[u]);
+#pragma unroll
+                for (int u = 0; u < LAZY_CHUNKS; u++)
+                    if (u < n_chunks && as[u] > 0.0f)
+                        zt += as[u] * __expf(am[u] - mt);
+            }
+            {
+                float bm[LAZY_CHUNKS], bs[LAZY_CHUNKS];
+#pragma unroll
+                for (int u = 0; u < LAZY_CHUNKS; u++) {
+                    bm[u] = u < n_chunks ? dm[u] : -INFINITY;
+                    bs[u] = u < n_chunks ? dsum[u] : 0.0f;
+                }
+#pragma unroll
+                for (int u = 0; u < LAZY_CHUNKS; u++)
+                    md = fmaxf(md, bm[u]);
+#pragma unroll
+                for (int u = 0; u < LAZY_CHUNKS; u++)
+                    if (u < n_chunks && bs[u] > 0.0f)
+                        zd += bs[u] * __expf(bm[u] - md);
+            }
+            s_mt[i] = mt; s_zt[i] = zt; s_md[i] = md; s_zd[i] = zd;
+        } else {
+            const float4 ns = node_stats[bt + i];
+            s_mt[i] = ns.x; s_zt[i] = ns.y; s_md[i] = ns.z; s_zd[i] = ns.w;
+        }
     }
     float *P = work + (int64_t)b * 3 * vocab, *Q = P + vocab, *R = Q + vocab;
     int32_t *path = accept_path + (int64_t)b * (max_depth + 1);
@@ -461,7 +508,36 @@ __global__ __launch_bounds__(NT) void spec_walk_kernel(const void *tlogits, cons
         // ---- the first child was rejected.  The residual target max(p - q, 0) is known through its chunk sums;
         // the draft loses the rejected token.
         const float ip = 1.0f / s_zt[cur], iq = s_zd[cur] > 0.0f ? 1.0f / s_zd[cur] : 0.0f;
-        const float *rs = res_sum + (bt + cur) * n_chunks;
+        __shared__ float s_res[LAZY_CHUNKS];
+        __shared__ float s_wres[NT / 64][LAZY_CHUNKS];
+        if (LAZY) {
+            // chunk sums of the first residual of this node: iteration k of the workgroup covers chunk k exactly
+#pragma unroll 2
+            for (int k = 0; k < n_chunks; k++) {
+                float tv[8], dv[8], part = 0.0f;
+                const int t = k * STAT_CHUNK + tid * 8;
+                load8<BF16>(tlogits, row, t, vocab, vec, tv);
+                load8<BF16>(dlogits, row, t, vocab, vec, dv);
+#pragma unroll
+                for (int j = 0; j < 8; j++)
+                    if (t + j < vocab)
+                        part += residual1(tv[j], dv[j], inv_temp, mt, md, ip, iq);
+                for (int off = 32; off > 0; off >>= 1)
+                    part += __shfl_xor(part, off);
+                if (lane == 0)
+                    s_wres[wave][k] = part;
+            }
+            __syncthreads();
+            if (tid < n_chunks) {
+                float t = 0.0f;
+#pragma unroll
+                for (int w = 0; w < NT / 64; w++)
+                    t += s_wres[w][tid];
+                s_res[tid] = t;
+            }
+            __syncthreads();
+        }
+        const float *rs = LAZY ? s_res : res_sum + (bt + cur) * n_chunks;
         float Z1 = 0.0f;
         for (int c0 = 0; c0 < n_chunks; c0 += 16) {   // chunk order, 16 loads in flight
             float a[16];
@@ -690,23 +766,27 @@ int dream_spec_accept(const void *target_logits, const void *draft_logits, int32
     const float inv_temp = 1.0f / temperature;
     hipStream_t st = as_stream(stream);
     const dim3 sgrid(n_chunks, batch * n_tree, 2);
-    if (logits_dtype == DREAM_BF16) {
-        hipLaunchKernelGGL(softmax_stats_kernel<true>, sgrid, dim3(256), 0, st, target_logits, draft_logits, n_tree, vocab, n_chunks, vec,
+    const bool lazy = n_chunks <= LAZY_CHUNKS;
+    auto launch_all = [&](auto bf16) {
+        constexpr bool BF = decltype(bf16)::value;
+        hipLaunchKernelGGL(softmax_stats_kernel<BF>, sgrid, dim3(256), 0, st, target_logits, draft_logits, n_tree, vocab, n_chunks, vec,
                            parent, inv_temp, stat_m, stat_s);
-        hipLaunchKernelGGL(residual_stats_kernel<true>, dim3(n_chunks, batch * n_tree), dim3(256), 0, st, target_logits, draft_logits, n_tree,
-                           vocab, n_chunks, vec, parent, inv_temp, stat_m, stat_s, res_sum, node_stats);
-        hipLaunchKernelGGL(spec_walk_kernel<true>, dim3(batch), dim3(NT), 0, st, target_logits, draft_logits, n_tree, vocab, n_chunks, vec,
-                           token, parent, u_accept, u_bonus, max_depth, inv_temp, stat_m, stat_s, res_sum, node_stats, work, accept_len, accept_path,
-                           bonus_token);
-    } else {
-        hipLaunchKernelGGL(softmax_stats_kernel<false>, sgrid, dim3(256), 0, st, target_logits, draft_logits, n_tree, vocab, n_chunks, vec,
-                           parent, inv_temp, stat_m, stat_s);
-        hipLaunchKernelGGL(residual_stats_kernel<false>, dim3(n_chunks, batch * n_tree), dim3(256), 0, st, target_logits, draft_logits, n_tree,
-                           vocab, n_chunks, vec, parent, inv_temp, stat_m, stat_s, res_sum, node_stats);
-        hipLaunchKernelGGL(spec_walk_kernel<false>, dim3(batch), dim3(NT), 0, st, target_logits, draft_logits, n_tree, vocab, n_chunks, vec,
-                           token, parent, u_accept, u_bonus, max_depth, inv_temp, stat_m, stat_s, res_sum, node_stats, work, accept_len, accept_path,
-                           bonus_token);
-    }
+        if (lazy) {
+            hipLaunchKernelGGL((spec_walk_kernel<BF, true>), dim3(batch), dim3(NT), 0, st, target_logits, draft_logits, n_tree, vocab, n_chunks,
+                               vec, token, parent, u_accept, u_bonus, max_depth, inv_temp, stat_m, stat_s, nullptr, nullptr, work, accept_len,
+                               accept_path, bonus_token);
+        } else {
+            hipLaunchKernelGGL(residual_stats_kernel<BF>, dim3(n_chunks, batch * n_tree), dim3(256), 0, st, target_logits, draft_logits, n_tree,
+                               vocab, n_chunks, vec, parent, inv_temp, stat_m, stat_s, res_sum, node_stats);
+            hipLaunchKernelGGL((spec_walk_kernel<BF, false>), dim3(batch), dim3(NT), 0, st, target_logits, draft_logits, n_tree, vocab, n_chunks,
+                               vec, token, parent, u_accept, u_bonus, max_depth, inv_temp, stat_m, stat_s, res_sum, node_stats, work,
+                               accept_len, accept_path, bonus_token);
+        }
+    };
+    if (logits_dtype == DREAM_BF16)
+        launch_all(std::true_type{});
+    else
+        launch_all(std::false_type{});
     return check_launch("spec_accept kernels");
 }
 
