@@ -914,6 +914,10 @@ int make_plan(const dream_attn_desc *d, int n_q, int64_t max_kv_len, Plan *p)
     } else {
         p->kt = (qg == 1 && d->head_dim == 64) ? 2 : 1;
         p->pfd = 2;
+        // the widest variants keep one step in flight: with two their accumulators and staging registers no
+        // longer fit the 512 registers of a wave (same speed, no spills)
+        if ((qg == 4 && d->head_dim == 128) || (qg == 2 && d->head_dim == 256))
+            p->pfd = 1;
     }
     p->state_floats = (size_t)qg * (d->head_dim / 16) * 256 + (size_t)qg * 2 * 64;
     p->off_part = DREAM_WORKSPACE_HEADER_BYTES;
@@ -1074,9 +1078,9 @@ int run_attention(const char *who, const dream_attn_desc *d, const void *q, cons
     case 644:  return launch_bf16<64, 4, 1, 2>(a, p, st);
     case 1281: return launch_bf16_q1<128>(a, p, st);
     case 1282: return launch_bf16<128, 2, 1, 2>(a, p, st);
-    case 1284: return launch_bf16<128, 4, 1, 2>(a, p, st);
+    case 1284: return launch_bf16<128, 4, 1, 1>(a, p, st);
     case 2561: return launch_bf16_q1<256>(a, p, st);
-    case 2562: return launch_bf16<256, 2, 1, 2>(a, p, st);
+    case 2562: return launch_bf16<256, 2, 1, 1>(a, p, st);
     default:   return fail(DREAM_ERR_UNSUPPORTED, "%s: no kernel for head_dim %d with %d query tiles per wave", who, d->head_dim, p.qg);
     }
 }
