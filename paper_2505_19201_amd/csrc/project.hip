@@ -5,12 +5,12 @@
 //
 // M = B*R is small (<= a few hundred) and the weight matrix [N, hidden] is large, so the call is bound by
 // streaming the weights once from HBM.  One workgroup owns 16 output features (16 weight rows, contiguous in
-// memory); its 8 waves split the hidden dimension, each computing C^T[n][m] += W[n][k] X[m][k] with
+// memory); its 4 waves split the hidden dimension, each computing C^T[n][m] += W[n][k] X[m][k] with
 // v_mfma_f32_16x16x32_bf16 (A = weight rows, B = feature rows).  With at most 16 feature rows (the paper's
 // shapes) a wave fetches 256 contiguous bytes of each row at a time and passes them through a private LDS area
 // to reach the operand layout: nobody else reads those bytes, but an operand-layout load touches 16 rows x 64
 // bytes per instruction, half cache lines, and measures 10-13 % slower.  With more rows (up to 4 tiles of 16 at
-// a time) the operands are loaded directly.  The 8 partial tiles are summed through LDS in wave order and the
+// a time) the operands are loaded directly.  The 4 partial tiles are summed through LDS in wave order and the
 // rows are rounded to bf16 and scattered.  Roofline: HBM, N*hidden*2 weight bytes per call.
 #include "common.h"
 
@@ -18,7 +18,8 @@ using namespace dream;
 
 namespace {
 
-constexpr int NWAVE = 8;
+constexpr int NWAVE = 4;   // (8 waves measured 5-8 % slower on the narrower maps, 2 no faster)
+static_assert(NWAVE >= 4, "the final reduction gives each of up to 4 feature-row tiles to one wave");
 
 __device__ __forceinline__ void wave_lds_fence()
 {
@@ -94,29 +95,34 @@ __global__ __launch_bounds__(64 * NWAVE) void project_kernel(ProjArgs args)
             // a wave-private LDS area and read back in operand layout; loading the operands directly would make
             // every instruction touch 16 rows x 64 bytes.
             constexpr int SS = 128, RSTR = SS + 8;             // elements of a row per super-step; padded LDS row stride
+            constexpr int LPR = SS / 8, RPI = 64 / LPR, NI = 16 / RPI;   // lanes per row, rows per instruction, instructions per 16 rows
             __shared__ __attribute__((aligned(16))) uint16_t s_stage[NWAVE][2][16 * RSTR];
             uint16_t *lw = s_stage[wave][0], *lx = s_stage[wave][1];
-            const int lrow = lane >> 4, lcol = (lane & 15) * 8;
+            const int lrow = lane / LPR, lcol = (lane % LPR) * 8;
             const int n_ss = (kw + SS - 1) / SS;
             const uint16_t *wsrc = a.w + (int64_t)n0 * K + wave * kw;
             const uint16_t *xsrc = a.x + wave * kw;
-            auto issue = [&](int s, u32x4 (&wr)[4], u32x4 (&xr)[4]) {
+            const int xj = min((a.m_total - m0 + RPI - 1) / RPI, NI);
+            auto issue = [&](int s, u32x4 (&wr)[NI], u32x4 (&xr)[NI]) {
                 s = min(s, n_ss - 1);                              // the prefetch past the end re-reads and is dropped
                 const int nvalid = min(SS, kw - s * SS);
                 const int col = s * SS + (lcol < nvalid ? lcol : 0);
 #pragma unroll
-                for (int j = 0; j < 4; j++) {
-                    wr[j] = *reinterpret_cast<const u32x4 *>(wsrc + (int64_t)(j * 4 + lrow) * K + col);
-                    const int m = min(m0 + j * 4 + lrow, a.m_total - 1);
-                    xr[j] = *reinterpret_cast<const u32x4 *>(xsrc + (int64_t)m * K + col);
+                for (int j = 0; j < NI; j++) {
+                    wr[j] = *reinterpret_cast<const u32x4 *>(wsrc + (int64_t)(j * RPI + lrow) * K + col);
+                    if (j < xj) {   // feature rows are fetched RPI at a time, only as many as exist
+                        const int m = min(m0 + j * RPI + lrow, a.m_total - 1);
+                        xr[j] = *reinterpret_cast<const u32x4 *>(xsrc + (int64_t)m * K + col);
+                    }
                 }
             };
             // one super-step: registers -> LDS, request the super-step that reuses these registers, multiply
-            auto step = [&](int s, u32x4 (&wr)[4], u32x4 (&xr)[4]) {
+            auto step = [&](int s, u32x4 (&wr)[NI], u32x4 (&xr)[NI]) {
 #pragma unroll
-                for (int j = 0; j < 4; j++) {
-                    *reinterpret_cast<u32x4 *>(lw + (j * 4 + lrow) * RSTR + lcol) = wr[j];
-                    *reinterpret_cast<u32x4 *>(lx + (j * 4 + lrow) * RSTR + lcol) = xr[j];
+                for (int j = 0; j < NI; j++) {
+                    *reinterpret_cast<u32x4 *>(lw + (j * RPI + lrow) * RSTR + lcol) = wr[j];
+                    if (j < xj)     // (the other LDS rows feed output columns that are never stored)
+                        *reinterpret_cast<u32x4 *>(lx + (j * RPI + lrow) * RSTR + lcol) = xr[j];
                 }
                 issue(s + 1, wr, xr);
                 wave_lds_fence();
@@ -131,7 +137,7 @@ __global__ __launch_bounds__(64 * NWAVE) void project_kernel(ProjArgs args)
                 }
                 wave_lds_fence();
             };
-            u32x4 wr[4], xr[4];
+            u32x4 wr[NI], xr[NI];
             issue(0, wr, xr);
             for (int s = 0; s < n_ss; s++)
                 step(s, wr, xr);
@@ -158,7 +164,7 @@ __global__ __launch_bounds__(64 * NWAVE) void project_kernel(ProjArgs args)
                 }
             }
         }
-        // sum the 8 waves' partial tiles in wave order; thread (wave, lane) finishes tile mt = wave % MT ... spread evenly
+        // sum the waves' partial tiles in wave order; thread (wave, lane) finishes tile mt = wave % MT ... spread evenly
         __syncthreads();
 #pragma unroll
         for (int mt = 0; mt < MT; mt++)
