@@ -50,7 +50,8 @@ __global__ __launch_bounds__(256) void scores_lse_bf16_kernel(ScoreArgs a)
     // x walks the heads with the KV head fastest: workgroup ids that share a KV head are congruent mod 8
     // (when there are 8 or more KV heads), so its K is fetched into one XCD's L2 only
     const int kvh = blockIdx.x % a.n_kv_heads, h = kvh * (a.n_q_heads / a.n_kv_heads) + blockIdx.x / a.n_kv_heads;
-    const int blk = blockIdx.y, b = blockIdx.z / a.ns1, split = blockIdx.z % a.ns1;
+    // later row blocks see more keys: they are dispatched first so that the launch does not end on the longest workgroups
+    const int blk = gridDim.y - 1 - blockIdx.y, b = blockIdx.z / a.ns1, split = blockIdx.z % a.ns1;
     const int row = blk * 64 + wave * 16 + c;
     const bool valid = row < a.n_q;
     const int pos = valid ? (a.q_pos ? a.q_pos[(int64_t)b * a.n_q + row] : row) : -1;
