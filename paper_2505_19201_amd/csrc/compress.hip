@@ -64,6 +64,10 @@ __global__ __launch_bounds__(256) void scores_lse_bf16_kernel(ScoreArgs a)
     for (int off = 32; off > 0; off >>= 1)
         wave_max_pos = max(wave_max_pos, __shfl_xor(wave_max_pos, off));
     wave_max_pos = __builtin_amdgcn_readfirstlane(wave_max_pos);
+    int wave_min_pos = valid ? pos : 0x7fffffff;   // rows that do not exist keep nothing, so they do not count
+    for (int off = 32; off > 0; off >>= 1)
+        wave_min_pos = min(wave_min_pos, __shfl_xor(wave_min_pos, off));
+    wave_min_pos = __builtin_amdgcn_readfirstlane(wave_min_pos);
 
     const uint16_t *kb = reinterpret_cast<const uint16_t *>(a.k) + ((int64_t)b * a.n_kv_heads + kvh) * a.s_max * D;
     u32x4 kreg[2][CH];
@@ -108,24 +112,40 @@ __global__ __launch_bounds__(256) void scores_lse_bf16_kernel(ScoreArgs a)
             acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kfr[0][ks], qf[ks], acc0, 0, 0, 0);
             acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kfr[1][ks], qf[ks], acc1, 0, 0, 0);
         }
-        float x[8], mx = -INFINITY;
-        const int lim = min(pos, a.n_keys - 1);
+        float sum = 0.0f, xsum = 0.0f, m_new, m_safe;
+        if (key0 + 31 <= wave_min_pos && key0 + 31 < a.n_keys && a.scale_log2 > 0.0f) {
+            // every key of the tile is visible to every row of the wave (all but the tiles on the diagonal):
+            // no masking, the maximum is taken before scaling and the scale rides in the exponent's fma
+            float mx = fmaxf(fmaxf(fmaxf(acc0[0], acc0[1]), fmaxf(acc0[2], acc0[3])), fmaxf(fmaxf(acc1[0], acc1[1]), fmaxf(acc1[2], acc1[3])));
+            m_new = fmaxf(m, mx * a.scale_log2);
+            m_safe = m_new;   // finite: the tile has visible keys
 #pragma unroll
-        for (int e = 0; e < 8; e++) {
-            const int kk = key0 + (e >> 2) * 16 + g * 4 + (e & 3);
-            const float v = (e < 4 ? acc0[e & 3] : acc1[e & 3]) * a.scale_log2;
-            x[e] = kk <= lim ? v : -INFINITY;
-            mx = fmaxf(mx, x[e]);
-        }
-        const float m_new = fmaxf(m, mx);
-        const float m_safe = (m_new == -INFINITY) ? 0.0f : m_new;
-        float sum = 0.0f, xsum = 0.0f;
+            for (int e = 0; e < 8; e++) {
+                const float raw = e < 4 ? acc0[e & 3] : acc1[e & 3];
+                const float p = __builtin_amdgcn_exp2f(fmaf(raw, a.scale_log2, -m_safe));
+                sum += p;
+                if (ENT)
+                    xsum += p * (raw * a.scale_log2);
+            }
+        } else {
+            float x[8], mx = -INFINITY;
+            const int lim = min(pos, a.n_keys - 1);
 #pragma unroll
-        for (int e = 0; e < 8; e++) {
-            const float p = __builtin_amdgcn_exp2f(x[e] - m_safe);
-            sum += p;
-            if (ENT)
-                xsum += p * (x[e] == -INFINITY ? 0.0f : x[e]);
+            for (int e = 0; e < 8; e++) {
+                const int kk = key0 + (e >> 2) * 16 + g * 4 + (e & 3);
+                const float v = (e < 4 ? acc0[e & 3] : acc1[e & 3]) * a.scale_log2;
+                x[e] = kk <= lim ? v : -INFINITY;
+                mx = fmaxf(mx, x[e]);
+            }
+            m_new = fmaxf(m, mx);
+            m_safe = (m_new == -INFINITY) ? 0.0f : m_new;
+#pragma unroll
+            for (int e = 0; e < 8; e++) {
+                const float p = __builtin_amdgcn_exp2f(x[e] - m_safe);
+                sum += p;
+                if (ENT)
+                    xsum += p * (x[e] == -INFINITY ? 0.0f : x[e]);
+            }
         }
         const float alpha = __builtin_amdgcn_exp2f(m - m_safe);
         l = l * alpha + sum;
@@ -323,12 +343,21 @@ __global__ __launch_bounds__(256) void scores_colsum_bf16_kernel(ScoreArgs a)
             acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qfr[0][ks], kf[ks], acc0, 0, 0, 0);
             acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qfr[1][ks], kf[ks], acc1, 0, 0, 0);
         }
+        if (!a.q_pos && r0 >= j0 + 15) {
+            // every row of the tile sits at or after every key of this wave: nothing to mask
 #pragma unroll
-        for (int r = 0; r < 4; r++) {
-            const float p0 = __builtin_amdgcn_exp2f(acc0[r] * a.scale_log2 - L0[r]);
-            const float p1 = __builtin_amdgcn_exp2f(acc1[r] * a.scale_log2 - L1[r]);
-            cs += key <= pp[r] ? p0 : 0.0f;
-            cs += key <= pp[16 + r] ? p1 : 0.0f;
+            for (int r = 0; r < 4; r++) {
+                cs += __builtin_amdgcn_exp2f(fmaf(acc0[r], a.scale_log2, -L0[r]));
+                cs += __builtin_amdgcn_exp2f(fmaf(acc1[r], a.scale_log2, -L1[r]));
+            }
+        } else {
+#pragma unroll
+            for (int r = 0; r < 4; r++) {
+                const float p0 = __builtin_amdgcn_exp2f(acc0[r] * a.scale_log2 - L0[r]);
+                const float p1 = __builtin_amdgcn_exp2f(acc1[r] * a.scale_log2 - L1[r]);
+                cs += key <= pp[r] ? p0 : 0.0f;
+                cs += key <= pp[16 + r] ? p1 : 0.0f;
+            }
         }
     };
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
