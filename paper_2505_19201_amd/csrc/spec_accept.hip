@@ -512,7 +512,6 @@ __global__ __launch_bounds__(NT) void spec_walk_kernel(const void *tlogits, cons
         __shared__ float s_wres[NT / 64][LAZY_CHUNKS];
         if (LAZY) {
             // chunk sums of the first residual of this node: iteration k of the workgroup covers chunk k exactly
-#pragma unroll 2
             for (int k = 0; k < n_chunks; k++) {
                 float tv[8], dv[8], part = 0.0f;
                 const int t = k * STAT_CHUNK + tid * 8;
