@@ -120,6 +120,11 @@ def test_full_size_vocabularies(gu, name):
     _case(gu, 4, cfg.n_tree, cfg.depth, cfg.vocab, "bf16", cfg.seed, min_clear=0.25)
 
 
+def test_largest_tree(gu):
+    """1024 nodes per sequence, the most the entry point takes (every per-node table at its full size)."""
+    _case(gu, 3, 1024, 12, 777, "f32", 960)
+
+
 def test_every_branch_of_the_walk_is_exercised(gu):
     """The kernel treats the first rejection at a node symbolically, the second by building arrays, and draws in
     three different ways; the oracle's record of the tests says which of these each compared sequence took."""
