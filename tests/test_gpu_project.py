@@ -32,7 +32,7 @@ def _close(got, want):
 
 
 @pytest.mark.parametrize("B,R,hidden,H,D", [(1, 1, 4096, 32, 128), (1, 10, 4096, 32, 128), (1, 60, 4096, 32, 128), (2, 7, 5120, 8, 128),
-                                            (1, 16, 3840, 16, 256), (8, 10, 2048, 32, 64), (3, 33, 256, 2, 16)])
+                                            (1, 16, 3840, 16, 256), (8, 10, 2048, 32, 64), (3, 33, 256, 2, 16), (30, 11, 512, 4, 64)])
 def test_dense_queries(gu, B, R, hidden, H, D):
     x, w = _inputs(B, R, hidden, H, D, 40 + R)
     got = gu.run_project(x, w, H, D)
