@@ -28,6 +28,7 @@
 // fp32 path (attn_f32_kernel): plain vector-ALU kernel, one workgroup per (query row, head,
 // sequence), used for float32 tensors (the small correctness configuration).
 #include "common.h"
+#include <atomic>
 #include <math.h>
 
 using namespace dream;
@@ -948,7 +949,7 @@ template <int D, int QG, int KT, int PFD>
 int launch_bf16(const AttnArgs &a, const Plan &p, hipStream_t st)
 {
     using G = Geom<D, QG, KT>;
-    static bool attr_set = false;
+    static std::atomic<bool> attr_set{false};   // (two threads may both set the attribute once: harmless)
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_kernel<D, QG, KT, PFD>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)G::LDS_BYTES) != hipSuccess)
@@ -970,7 +971,7 @@ int launch_wave(const AttnArgs &a, const Plan &p, hipStream_t st)
     constexpr size_t tile_bytes = (size_t)NW * G::TILE_ELEMS * 2, merge_bytes = (size_t)NW * StateGeom<D / DS, 1>::STATE_FLOATS * 4;
     constexpr size_t lds_bytes = (tile_bytes > merge_bytes ? tile_bytes : merge_bytes) + DREAM_MAX_TREE * sizeof(int32_t);
     static_assert(merge_bytes <= tile_bytes, "the wave merge buffers reuse the tile area");
-    static bool attr_set = false;
+    static std::atomic<bool> attr_set{false};   // (two threads may both set the attribute once: harmless)
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_wave_kernel<D, NW, DS>), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)lds_bytes) != hipSuccess)

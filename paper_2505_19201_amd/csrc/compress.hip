@@ -13,6 +13,7 @@
 // plus the first ties in position order, and compacts the survivors in position order; the optional
 // gather copies the surviving rows of a [rows, row_elems] matrix.
 #include "common.h"
+#include <atomic>
 
 using namespace dream;
 
@@ -762,7 +763,7 @@ int dream_visual_compress(const dream_attn_desc *desc, const void *q, const int3
         *n_kept_host = k;
     if (vis_len > 0 && (k > 0 || scores_out)) {
         size_t lds = (size_t)vis_len * 4 + (256 + 32 + 4) * 4;
-        static bool attr_set = false;
+        static std::atomic<bool> attr_set{false};   // (two threads may both set the attribute once: harmless)
         if (!attr_set) {
             if (hipFuncSetAttribute(reinterpret_cast<const void *>(&topk_keep_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                                     DREAM_MAX_VISUAL * 4 + (256 + 32 + 4) * 4) != hipSuccess)
