@@ -556,7 +556,7 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a)
     issue(wave);
     TS(2);
 
-    // the query tile: head hh of the group, rows nt*16 .. nt*16+15 (tq < 4, so no division)
+    // the query tile: head hh of the group, rows nt*16 .. nt*16+15 (at most 4 heads per group, so three compares instead of a division)
     const int tph = a.tiles_per_head;
     const int hh = (tq >= tph) + (tq >= 2 * tph) + (tq >= 3 * tph), nt = tq - hh * tph;
     const int row = nt * 16 + c, head = kvh * a.group + hh;
@@ -867,7 +867,7 @@ int make_plan(const dream_attn_desc *d, int n_q, int64_t max_kv_len, Plan *p)
     // few, short streams with at most 4 query tiles each: a workgroup per query tile fills half the chip
     // without splitting keys, which saves the merge launch
     p->wave_mode = q_tiles_override() == 0 && kv_splits_override() == 0 &&
-                   d->dtype == DREAM_BF16 && n_qtiles <= 4 && base * n_qtiles <= 256 && base * n_qtiles >= 32 && tiles <= 64 &&
+                   d->dtype == DREAM_BF16 && n_qtiles <= 16 && G <= 4 && base * n_qtiles <= 256 && base * n_qtiles >= 32 && tiles <= 64 &&
                    d->s_max * d->head_dim < (1ll << 31);
     if (p->wave_mode) {
         p->qg = 1;
@@ -978,8 +978,8 @@ int launch_wave(const AttnArgs &a, const Plan &p, hipStream_t st)
             return fail(DREAM_ERR_HIP, "attention: cannot reserve %zu bytes of LDS", lds_bytes);
         attr_set = true;
     }
-    if (a.n_qg > 4)
-        return fail(DREAM_ERR_INVALID_ARG, "attention: the wave kernel serves at most 4 query tiles per KV head");
+    if (a.n_qg > 16 || a.group > 4)
+        return fail(DREAM_ERR_INVALID_ARG, "attention: the wave kernel serves at most 16 query tiles and 4 query heads per KV head");
     const dim3 grid(8 * a.n_qg * DS, ceil_div(a.n_kv_heads, 8), p.n_streams / a.n_kv_heads);
     hipLaunchKernelGGL((attn_wave_kernel<D, NW, DS>), grid, dim3(64 * NW), lds_bytes, st, a);
     return check_launch("attn_wave_kernel");

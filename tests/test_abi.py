@@ -61,9 +61,9 @@ def test_host_side_argument_errors(lib):
     assert f(*args(d, n_tree=65)) == -2
     assert f(*args(d, n_tree=0)) == -2
     assert f(*args(d, maxkv=129)) == -1                                           # beyond s_max
-    big = dream.attn_desc(1, 32, 8, 128, dream.BF16, 1400)                        # few KV heads: key splits need a workspace
-    assert dream.dream_tree_verify_attn_workspace(big, 60, 1340) > 65536
-    assert f(*args(big, n_tree=60, maxkv=1340, wsb=65536)) == -3                   # workspace too small
+    big = dream.attn_desc(1, 32, 8, 128, dream.BF16, 4200)                        # a long cache with few KV heads: key splits need a workspace
+    assert dream.dream_tree_verify_attn_workspace(big, 60, 4156) > 65536
+    assert f(*args(big, n_tree=60, maxkv=4156, wsb=65536)) == -3                   # workspace too small
     assert "workspace" in dream.dream_last_error()
     g = lib.dream_accept_path
     assert g(one, C.c_int32(1), C.c_int32(1), C.c_int32(2000), C.c_int32(100), one, one, C.c_int32(6), one, one, one, one,
@@ -97,8 +97,9 @@ def test_workspace_sizes_are_monotone(lib):
 
 
 def test_launch_plans_of_the_paper_shapes(lib):
-    """The plan is host logic: one sequence of an MHA model takes the single-launch wave kernel with its output
-    columns split over workgroups, a GQA model or a batch of sequences takes the shared-tile kernel."""
+    """The plan is host logic: one sequence with a short cache takes the single-launch wave kernel with its output
+    columns split over workgroups (MHA, and GQA groups of up to 4 heads), a long cache or a batch of sequences the
+    shared-tile kernel, with key splits and a merge launch where the streams are few."""
     def plan(B, hq, hkv, d, n_q, s):
         return dream.dream_attn_plan_describe(dream.attn_desc(B, hq, hkv, d, dream.BF16, s), n_q, s)
     llava = plan(1, 32, 32, 128, 60, 764)
@@ -106,7 +107,11 @@ def test_launch_plans_of_the_paper_shapes(lib):
     level = plan(1, 32, 32, 128, 16, 764)            # one drafted tree level: a single query tile per head
     assert level.startswith("attn_wave_kernel<128,8,4>") and "workgroups=128" in level
     pixtral = plan(1, 32, 8, 128, 60, 1340)
-    assert pixtral.startswith("attn_bf16_kernel<128,1,") and "splits=8" in pixtral and "merge_launch=1" in pixtral
+    assert pixtral.startswith("attn_wave_kernel<128,8,2>") and "workgroups=256" in pixtral and "merge_launch=0" in pixtral
+    gemma3 = plan(1, 16, 8, 256, 60, 1340)
+    assert gemma3.startswith("attn_wave_kernel<256,4,4>") and "workgroups=256" in gemma3
+    long_cache = plan(1, 32, 8, 128, 60, 4156)        # more than 64 key tiles
+    assert long_cache.startswith("attn_bf16_kernel<128,1,") and "splits=8" in long_cache and "merge_launch=1" in long_cache
     batch = plan(32, 32, 32, 64, 60, 1660)
     assert batch.startswith("attn_bf16_kernel<64,1,") and "splits=1 " in batch and "merge_launch=0" in batch
     f32 = dream.dream_attn_plan_describe(dream.attn_desc(1, 4, 4, 64, dream.F32, 104), 8, 104)
