@@ -491,7 +491,7 @@ __device__ __forceinline__ void wave_lds_fence()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// Short streams with few query tiles (one sequence, MHA): a workgroup serves ONE 16-row query tile of one
+// Short streams with few query tiles (one sequence; up to 4 query heads per KV head): a workgroup serves ONE 16-row query tile of one
 // head over the whole key range, its NW waves stream disjoint 32-key tiles (each through a private LDS
 // area, no workgroup barrier in the loop) and merge their states through LDS at the end, in a fixed
 // order.  No key split, so no second launch; the workgroups of a head re-read its K/V through the L2 of
@@ -864,7 +864,7 @@ int make_plan(const dream_attn_desc *d, int n_q, int64_t max_kv_len, Plan *p)
         qg = 1;
     p->qg = qg;
     p->n_qg = ceil_div(n_qtiles, 4 * qg);
-    // few, short streams with at most 4 query tiles each: a workgroup per query tile fills half the chip
+    // few, short streams with at most 16 query tiles each: a workgroup per query tile fills at least half the chip
     // without splitting keys, which saves the merge launch
     p->wave_mode = q_tiles_override() == 0 && kv_splits_override() == 0 &&
                    d->dtype == DREAM_BF16 && n_qtiles <= 16 && G <= 4 && base * n_qtiles <= 256 && base * n_qtiles >= 32 && tiles <= 64 &&
