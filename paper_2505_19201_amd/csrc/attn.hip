@@ -865,9 +865,11 @@ int make_plan(const dream_attn_desc *d, int n_q, int64_t max_kv_len, Plan *p)
     p->qg = qg;
     p->n_qg = ceil_div(n_qtiles, 4 * qg);
     // few, short streams with at most 16 query tiles each: a workgroup per query tile fills at least half the chip
-    // without splitting keys, which saves the merge launch
+    // without splitting keys, which saves the merge launch (short: up to 64 key tiles at head_dim 128, twice that
+    // at 64: the measured crossover against the key-split path, which comes a little later for grouped-query
+    // shapes because their split states are larger)
     p->wave_mode = q_tiles_override() == 0 && kv_splits_override() == 0 &&
-                   d->dtype == DREAM_BF16 && n_qtiles <= 16 && G <= 4 && base * n_qtiles <= 256 && base * n_qtiles >= 32 && tiles <= 64 &&
+                   d->dtype == DREAM_BF16 && n_qtiles <= 16 && G <= 4 && base * n_qtiles <= 256 && base * n_qtiles >= 32 && (int64_t)tiles * d->head_dim <= (G > 1 ? 12288 : 8192) &&
                    d->s_max * d->head_dim < (1ll << 31);
     if (p->wave_mode) {
         p->qg = 1;

@@ -46,6 +46,9 @@ SMALL_CASES = [
     ("t17", 1, 4, 2, 128, 90, 9, 17, 4, [99], 2),
     ("paper_tree33", 1, 4, 4, 128, 144, 40, 33, 6, [184], 0),
     ("empty_prefix", 1, 2, 2, 64, 0, 0, 20, 4, [0], 0),
+    ("long_mha64", 1, 8, 8, 64, 2900, 140, 60, 6, [3040], 0),        # 97 key tiles, still one launch at head_dim 64
+    ("long_gqa4_128", 1, 16, 4, 128, 2500, 60, 60, 6, [2560], 0),    # 82 key tiles, grouped queries
+    ("longer_mha128", 1, 8, 8, 128, 2500, 60, 60, 6, [2560], 0),     # past the single-launch limit: key splits and merge
 ]
 
 
