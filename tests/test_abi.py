@@ -228,3 +228,20 @@ def test_project_rows_argument_errors(lib):
     assert multi(2, ProjJob(0x1000, None, 8, None, None, 0x3000)) == -1
     assert multi(1, ProjJob(0x1000, 0x2000, 0, None, None, 0x3000)) == -1
     assert lib.dream_project_rows_multi(C.byref(desc), None, C.c_int32(1), C.c_int32(10), C.c_int32(4096), None) == -1
+
+
+def test_header_compiles_as_c_and_host_calls_work(lib, tmp_path):
+    """include/dream.h is a C header: a C99 program built against it with gcc calls the host-only entry points."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no gcc")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    libdir = os.path.dirname(dream.library_path())
+    exe = str(tmp_path / "abi_check")
+    subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(root, "include"),
+                    os.path.join(root, "tests", "c", "abi_check.c"), "-o", exe, "-L", libdir, "-ldream", "-Wl,-rpath," + libdir],
+                   check=True, capture_output=True, text=True)
+    out = subprocess.run([exe], check=True, capture_output=True, text=True).stdout
+    assert out.startswith("attn_wave_kernel<128,8,2>")
