@@ -504,14 +504,16 @@ __device__ __forceinline__ void wave_lds_fence()
 //
 // Each wave keeps one tile in flight in registers: a CU holds about 64 KB of outstanding loads whatever is
 // asked of it, so a second tile in flight per wave only queues behind the first.
-template <int D, int NW, int DS>
+// QT: query tiles a workgroup serves (1, or 2 when there are more (KV head, query tile) pairs than CUs: the
+// same K/V stream then feeds two tiles and half as many workgroups pull it).
+template <int D, int NW, int DS, int QT = 1>
 __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a)
 {
     constexpr int DV = D / DS;
     using G = Geom<D, 1, 1, DV>;
     constexpr int KSTR = G::KSTR, VSTR = G::VSTR, NDT = G::NDT, NKS = G::NKS;
     constexpr int CHK = 32 * D / 8 / 64, CHV = 32 * DV / 8 / 64;   // 16-byte chunks per lane per tile of K, V
-    constexpr int STATE = StateGeom<DV, 1>::STATE_FLOATS;
+    constexpr int STATE = StateGeom<DV, QT>::STATE_FLOATS;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     uint16_t *lds = reinterpret_cast<uint16_t *>(smem_raw);
     int32_t *lds_parent = reinterpret_cast<int32_t *>(smem_raw + (size_t)NW * G::TILE_ELEMS * 2);
@@ -520,7 +522,7 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = lane & 15, g = lane >> 4;
     const int unit = blockIdx.x >> 3;
-    const int kvh = blockIdx.y * 8 + (blockIdx.x & 7), tq = unit / DS, ds = unit % DS, b = blockIdx.z;
+    const int kvh = blockIdx.y * 8 + (blockIdx.x & 7), tq0 = (unit / DS) * QT, ds = unit % DS, b = blockIdx.z;
     if (kvh >= a.n_kv_heads)
         return;
     TS(0);
@@ -556,39 +558,47 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a)
     issue(wave);
     TS(2);
 
-    // the query tile: head hh of the group, rows nt*16 .. nt*16+15 (at most 4 heads per group, so three compares instead of a division)
+    // the query tiles: head hh of the group, rows nt*16 .. nt*16+15 (at most 4 heads per group, so three compares instead of a division)
     const int tph = a.tiles_per_head;
-    const int hh = (tq >= tph) + (tq >= 2 * tph) + (tq >= 3 * tph), nt = tq - hh * tph;
-    const int row = nt * 16 + c, head = kvh * a.group + hh;
-    const bool valid = row < a.n_q;
-    bf16x8 qf[1][NKS];
-    const int rr = valid ? row : 0;
-    const int node = a.q_node ? min(max(a.q_node[(int64_t)b * a.n_q + rr], 0), a.n_tree - 1) : rr;
-    {
-        const uint16_t *qp = reinterpret_cast<const uint16_t *>(a.q) + (((int64_t)b * a.n_q + rr) * a.n_q_heads + head) * D + g * 8;
+    int row[QT], head[QT], node[QT];
+    bool valid[QT];
+    bf16x8 qf[QT][NKS];
+#pragma unroll
+    for (int qt = 0; qt < QT; qt++) {
+        const int tq = tq0 + qt;
+        const int hh = (tq >= tph) + (tq >= 2 * tph) + (tq >= 3 * tph), nt = tq - hh * tph;
+        row[qt] = nt * 16 + c;
+        valid[qt] = hh < a.group && row[qt] < a.n_q;     // (the second tile of the last pair may not exist)
+        head[qt] = kvh * a.group + (hh < a.group ? hh : 0);
+        const int rr = valid[qt] ? row[qt] : 0;
+        node[qt] = a.q_node ? min(max(a.q_node[(int64_t)b * a.n_q + rr], 0), a.n_tree - 1) : rr;
+        const uint16_t *qp = reinterpret_cast<const uint16_t *>(a.q) + (((int64_t)b * a.n_q + rr) * a.n_q_heads + head[qt]) * D + g * 8;
 #pragma unroll
         for (int ks = 0; ks < NKS; ks++)
-            qf[0][ks] = *reinterpret_cast<const bf16x8 *>(qp + ks * 32);
+            qf[qt][ks] = *reinterpret_cast<const bf16x8 *>(qp + ks * 32);
     }
     if (!a.tree_mask && tid < a.n_tree)
         lds_parent[tid] = my_parent < tid ? my_parent : -1;   // a walk up the tree always ends
     __syncthreads();
     TS(3);
-    uint64_t qmask[1];
-    qmask[0] = valid ? visible_nodes(a, b, node, lds_parent) : 0ull;
-    if (!valid) {
+    uint64_t qmask[QT];
+    WaveState<QT, NDT> st;
 #pragma unroll
-        for (int ks = 0; ks < NKS; ks++)
+    for (int qt = 0; qt < QT; qt++) {
+        qmask[qt] = valid[qt] ? visible_nodes(a, b, node[qt], lds_parent) : 0ull;
+        if (!valid[qt]) {
 #pragma unroll
-            for (int i = 0; i < 8; i++)
-                qf[0][ks][i] = (__bf16)0.0f;
+            for (int ks = 0; ks < NKS; ks++)
+#pragma unroll
+                for (int i = 0; i < 8; i++)
+                    qf[qt][ks][i] = (__bf16)0.0f;
+        }
+        st.m[qt] = -INFINITY;
+        st.l[qt] = 0.0f;
+#pragma unroll
+        for (int dt = 0; dt < NDT; dt++)
+            st.o[qt][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
-    WaveState<1, NDT> st;
-    st.m[0] = -INFINITY;
-    st.l[0] = 0.0f;
-#pragma unroll
-    for (int dt = 0; dt < NDT; dt++)
-        st.o[0][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     TS(4);
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): from here on only tile prefetches are in flight
     TS(5);
@@ -606,53 +616,57 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a)
         wave_lds_fence();
         TS(8 + i * 2);
         issue(t + NW);
-        tiles_compute<D, 1, 1, DV>(wt, t * 32, P, kv_len, a.n_tree, a.scale_log2, qf, qmask, st, c, g);
+        tiles_compute<D, QT, 1, DV>(wt, t * 32, P, kv_len, a.n_tree, a.scale_log2, qf, qmask, st, c, g);
         wave_lds_fence();
         if (st.l[0] != 12345.f) TS(9 + i * 2);
     }
-    {
-        float l = st.l[0];
+#pragma unroll
+    for (int qt = 0; qt < QT; qt++) {
+        float l = st.l[qt];
         l += __shfl_xor(l, 16);
         l += __shfl_xor(l, 32);
-        st.l[0] = l;
+        st.l[qt] = l;
     }
     // merge the waves through LDS (the tile areas are free by then) in one round: every wave parks its
     // state, then wave w sums the 16-wide output column tiles w, w+NW, ... over the states in wave order
     float *mbuf = reinterpret_cast<float *>(smem_raw);
     TS(6);
     __syncthreads();
-    state_store<1, NDT>(st, mbuf + wave * STATE, lane);
+    state_store<QT, NDT>(st, mbuf + wave * STATE, lane);
     __syncthreads();
-    if (!valid)
-        return;
-    float mj[NW], m = -INFINITY;
 #pragma unroll
-    for (int j = 0; j < NW; j++) {
-        mj[j] = mbuf[j * STATE + NDT * 256 + lane];
-        m = fmaxf(m, mj[j]);
+    for (int qt = 0; qt < QT; qt++) {
+        if (!valid[qt])
+            continue;
+        float mj[NW], m = -INFINITY;
+#pragma unroll
+        for (int j = 0; j < NW; j++) {
+            mj[j] = mbuf[j * STATE + QT * NDT * 256 + (qt * 2) * 64 + lane];
+            m = fmaxf(m, mj[j]);
+        }
+        const float ms = (m == -INFINITY) ? 0.0f : m;
+        float l = 0.0f;
+#pragma unroll
+        for (int j = 0; j < NW; j++) {
+            mj[j] = __builtin_amdgcn_exp2f(mj[j] - ms);
+            l += mj[j] * mbuf[j * STATE + QT * NDT * 256 + (qt * 2 + 1) * 64 + lane];
+        }
+        const float inv = l > 0.0f ? 1.0f / l : 0.0f;
+        uint16_t *op = reinterpret_cast<uint16_t *>(a.out) + (((int64_t)b * a.n_q + row[qt]) * a.n_q_heads + head[qt]) * D + ds * DV + g * 4;
+        for (int dt = wave; dt < NDT; dt += NW) {
+            f32x4 o = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int j = 0; j < NW; j++)
+                o += reinterpret_cast<const f32x4 *>(mbuf + j * STATE)[(qt * NDT + dt) * 64 + lane] * mj[j];
+            bf16x4 ob;
+#pragma unroll
+            for (int r = 0; r < 4; r++)
+                ob[r] = (__bf16)(o[r] * inv);
+            *reinterpret_cast<bf16x4 *>(op + dt * 16) = ob;
+        }
+        if (wave == 0 && ds == 0 && a.lse && g == 0)
+            a.lse[((int64_t)b * a.n_q_heads + head[qt]) * a.n_q + row[qt]] = l > 0.0f ? (m + log2f(l)) * 0.6931471805599453f : -INFINITY;
     }
-    const float ms = (m == -INFINITY) ? 0.0f : m;
-    float l = 0.0f;
-#pragma unroll
-    for (int j = 0; j < NW; j++) {
-        mj[j] = __builtin_amdgcn_exp2f(mj[j] - ms);
-        l += mj[j] * mbuf[j * STATE + NDT * 256 + 64 + lane];
-    }
-    const float inv = l > 0.0f ? 1.0f / l : 0.0f;
-    uint16_t *op = reinterpret_cast<uint16_t *>(a.out) + (((int64_t)b * a.n_q + row) * a.n_q_heads + head) * D + ds * DV + g * 4;
-    for (int dt = wave; dt < NDT; dt += NW) {
-        f32x4 o = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int j = 0; j < NW; j++)
-            o += reinterpret_cast<const f32x4 *>(mbuf + j * STATE)[dt * 64 + lane] * mj[j];
-        bf16x4 ob;
-#pragma unroll
-        for (int r = 0; r < 4; r++)
-            ob[r] = (__bf16)(o[r] * inv);
-        *reinterpret_cast<bf16x4 *>(op + dt * 16) = ob;
-    }
-    if (wave == 0 && ds == 0 && a.lse && g == 0)
-        a.lse[((int64_t)b * a.n_q_heads + head) * a.n_q + row] = l > 0.0f ? (m + log2f(l)) * 0.6931471805599453f : -INFINITY;
 #ifdef DREAM_TIMESTAMPS
     if (wave == 0) {
         __builtin_amdgcn_s_waitcnt(0x0F70);
@@ -831,12 +845,14 @@ struct Plan {
     bool wave_mode;   // one query tile per workgroup, waves split the keys, no key split (attn_wave_kernel)
     int wave_nw;      // waves per workgroup in that mode
     int wave_ds;      // workgroups that share the output columns of a query tile in that mode (1, 2 or 4)
+    int wave_qt;      // query tiles per workgroup in that mode (1 or 2)
     size_t state_floats, off_part, total;
 };
 
 int make_plan(const dream_attn_desc *d, int n_q, int64_t max_kv_len, Plan *p)
 {
     const int G = d->n_q_heads / d->n_kv_heads;
+    p->wave_qt = 1;
     p->tiles_per_head = ceil_div(n_q, 16);
     const int n_qtiles = G * p->tiles_per_head;
     const int qg_max = d->head_dim == 256 ? 2 : 4;   // accumulator registers bound the query tiles per wave
@@ -869,7 +885,8 @@ int make_plan(const dream_attn_desc *d, int n_q, int64_t max_kv_len, Plan *p)
     // at 64: the measured crossover against the key-split path, which comes a little later for grouped-query
     // shapes because their split states are larger)
     p->wave_mode = q_tiles_override() == 0 && kv_splits_override() == 0 &&
-                   d->dtype == DREAM_BF16 && n_qtiles <= 16 && G <= 4 && base * n_qtiles <= 256 && base * n_qtiles >= 32 && (int64_t)tiles * d->head_dim <= (G > 1 ? 12288 : 8192) &&
+                   d->dtype == DREAM_BF16 && n_qtiles <= 16 && G <= 4 && base * n_qtiles <= 512 && base * n_qtiles >= 32 &&
+                   (base * n_qtiles <= 256 || d->head_dim <= 128) && (int64_t)tiles * d->head_dim <= (G > 1 ? 12288 : 8192) &&
                    d->s_max * d->head_dim < (1ll << 31);
     if (p->wave_mode) {
         p->qg = 1;
@@ -878,6 +895,9 @@ int make_plan(const dream_attn_desc *d, int n_q, int64_t max_kv_len, Plan *p)
         p->wave_ds = 1;
         while (p->wave_ds < 4 && base * n_qtiles * p->wave_ds * 2 <= 256 && d->head_dim / (p->wave_ds * 2) >= 32)
             p->wave_ds *= 2;
+        // more pairs than CUs (up to twice as many; beyond that the shared-tile kernel measures faster): a
+        // workgroup serves two query tiles from the one K/V stream
+        p->wave_qt = base * n_qtiles > 256 ? 2 : 1;
         // 8 waves (two per SIMD) where the registers allow it and each wave still gets a few tiles
         p->wave_nw = (d->head_dim <= 128 && (tiles > 32 || p->wave_ds > 1)) ? 8 : 4;
         p->n_splits = 1;
@@ -966,30 +986,34 @@ int launch_bf16(const AttnArgs &a, const Plan &p, hipStream_t st)
     return check_launch("attn_merge_kernel");
 }
 
-template <int D, int NW, int DS>
+template <int D, int NW, int DS, int QT = 1>
 int launch_wave(const AttnArgs &a, const Plan &p, hipStream_t st)
 {
     using G = Geom<D, 1, 1, D / DS>;
-    constexpr size_t tile_bytes = (size_t)NW * G::TILE_ELEMS * 2, merge_bytes = (size_t)NW * StateGeom<D / DS, 1>::STATE_FLOATS * 4;
+    constexpr size_t tile_bytes = (size_t)NW * G::TILE_ELEMS * 2, merge_bytes = (size_t)NW * StateGeom<D / DS, QT>::STATE_FLOATS * 4;
     constexpr size_t lds_bytes = (tile_bytes > merge_bytes ? tile_bytes : merge_bytes) + DREAM_MAX_TREE * sizeof(int32_t);
     static_assert(merge_bytes <= tile_bytes, "the wave merge buffers reuse the tile area");
     static std::atomic<bool> attr_set{false};   // (two threads may both set the attribute once: harmless)
     if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_wave_kernel<D, NW, DS>), hipFuncAttributeMaxDynamicSharedMemorySize,
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_wave_kernel<D, NW, DS, QT>), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)lds_bytes) != hipSuccess)
             return fail(DREAM_ERR_HIP, "attention: cannot reserve %zu bytes of LDS", lds_bytes);
         attr_set = true;
     }
     if (a.n_qg > 16 || a.group > 4)
         return fail(DREAM_ERR_INVALID_ARG, "attention: the wave kernel serves at most 16 query tiles and 4 query heads per KV head");
-    const dim3 grid(8 * a.n_qg * DS, ceil_div(a.n_kv_heads, 8), p.n_streams / a.n_kv_heads);
-    hipLaunchKernelGGL((attn_wave_kernel<D, NW, DS>), grid, dim3(64 * NW), lds_bytes, st, a);
+    const dim3 grid(8 * ceil_div(a.n_qg, QT) * DS, ceil_div(a.n_kv_heads, 8), p.n_streams / a.n_kv_heads);
+    hipLaunchKernelGGL((attn_wave_kernel<D, NW, DS, QT>), grid, dim3(64 * NW), lds_bytes, st, a);
     return check_launch("attn_wave_kernel");
 }
 
 template <int D>
 int launch_wave_d(const AttnArgs &a, const Plan &p, hipStream_t st)
 {
+    if constexpr (D <= 128) {
+        if (p.wave_qt == 2)   // (only with unsplit output columns)
+            return p.wave_nw == 8 ? launch_wave<D, 8, 1, 2>(a, p, st) : launch_wave<D, 4, 1, 2>(a, p, st);
+    }
     if constexpr (D <= 128) {
         if (p.wave_nw == 8) {
             if constexpr (D >= 128) {
@@ -1131,8 +1155,8 @@ int dream_attn_plan_describe(const dream_attn_desc *desc, int32_t n_q, int64_t m
     if (desc->dtype == DREAM_F32)
         snprintf(buf, buf_bytes, "attn_f32_kernel workgroups=%lld", (long long)desc->batch * desc->n_q_heads * n_q);
     else if (p.wave_mode)
-        snprintf(buf, buf_bytes, "attn_wave_kernel<%d,%d,%d> workgroups=%d splits=1 merge_launch=0", desc->head_dim, p.wave_nw,
-                 p.wave_ds, p.n_qg * p.wave_ds * desc->n_kv_heads * desc->batch);
+        snprintf(buf, buf_bytes, "attn_wave_kernel<%d,%d,%d%s> workgroups=%d splits=1 merge_launch=0", desc->head_dim, p.wave_nw,
+                 p.wave_ds, p.wave_qt == 2 ? ",2" : "", ceil_div(p.n_qg, p.wave_qt) * p.wave_ds * desc->n_kv_heads * desc->batch);
     else
         snprintf(buf, buf_bytes, "attn_bf16_kernel<%d,%d,%d,%d> workgroups=%d splits=%d merge_launch=%d", desc->head_dim, p.qg, p.kt,
                  p.pfd, p.n_groups * p.n_splits, p.n_splits, p.n_splits > 1 ? 1 : 0);

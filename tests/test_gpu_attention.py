@@ -49,6 +49,9 @@ SMALL_CASES = [
     ("long_mha64", 1, 8, 8, 64, 2900, 140, 60, 6, [3040], 0),        # 97 key tiles, still one launch at head_dim 64
     ("long_gqa4_128", 1, 16, 4, 128, 2500, 60, 60, 6, [2560], 0),    # 82 key tiles, grouped queries
     ("longer_mha128", 1, 8, 8, 128, 2500, 60, 60, 6, [2560], 0),     # past the single-launch limit: key splits and merge
+    ("pairs320_mha64", 5, 16, 16, 64, 150, 43, 60, 6, [193, 101, 64, 180, 33], 0),   # more (head, tile) pairs than CUs
+    ("pairs288_gqa128", 3, 24, 8, 128, 100, 30, 60, 6, [130, 77, 101], 0),            # 12 query tiles per KV head, in pairs
+    ("pairs_odd_tiles", 6, 16, 16, 128, 100, 30, 40, 5, [130, 77, 101, 64, 90, 33], 0),   # 3 query tiles per head: a pair with one tile missing
 ]
 
 
