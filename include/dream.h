@@ -170,6 +170,27 @@ int dream_accept_path(const void *logits, int32_t logits_dtype, int32_t batch, i
                       size_t workspace_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * dream_accept_path for callers that cannot allocate device memory or hand over a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and results as
+ * dream_accept_path without the workspace: the per-chunk partial results live in a scratch array inside the
+ * library (DREAM_ACCEPT_STATIC_SCRATCH_BYTES of device memory per GPU, held until the process ends).  The
+ * call allocates nothing and frees nothing.
+ *   Limit: batch * n_tree * ceil(vocab / 8192) partial results of 8 bytes (two arrays, each rounded up to
+ *   256 bytes) must fit the scratch: up to 131040 of them, e.g. 32 sequences x 60 nodes at a vocabulary
+ *   of 524288; larger problems return DREAM_ERR_UNSUPPORTED (use dream_accept_path).
+ *   Every call on a GPU shares that GPU's scratch: calls that overlap on one GPU (two streams, two host
+ *   threads) race; calls ordered on one stream do not.  Nothing in the scratch has to start at zero.
+ * dream_accept_static_init() looks up the scratch address for the CURRENT device (once per device; the first
+ * dream_accept_path_static call on a device does it otherwise).  Call it at set-up, outside any capture.
+ * ------------------------------------------------------------------------------------------- */
+#define DREAM_ACCEPT_STATIC_SCRATCH_BYTES (1 << 20)
+int dream_accept_static_init(void);
+int dream_accept_path_static(const void *logits, int32_t logits_dtype, int32_t batch, int32_t n_tree,
+                             int32_t vocab, const int32_t *token, const int32_t *parent,
+                             int32_t max_depth, int32_t *node_argmax, int32_t *accept_len,
+                             int32_t *accept_path, int32_t *bonus_token, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Attention entropy of a layer, Eq. 2 (Section 3.2): row r of q sits at position pos_r (q_pos[b,r],
  * or r when q_pos is NULL) and attends keys 0..pos_r with A = softmax_row(scale q k^T);
  *   row_entropy[b, h, r] = - sum_j A_j log A_j   (natural logarithm; nullable output)

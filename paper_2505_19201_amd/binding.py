@@ -25,7 +25,7 @@ EXPORTED_SYMBOLS = (
     "dream_attn_plan_describe", "dream_stream_read", "dream_kv_commit",
     "dream_tree_expand_workspace", "dream_tree_expand_level", "dream_tree_finalize",
     "dream_attention_entropy_workspace", "dream_attention_entropy", "dream_spec_accept_workspace", "dream_spec_accept",
-    "dream_project_rows", "dream_project_rows_multi",
+    "dream_project_rows", "dream_project_rows_multi", "dream_accept_path_static", "dream_accept_static_init",
 )
 
 
@@ -191,6 +191,18 @@ def dream_accept_path(logits, logits_dtype: int, batch: int, n_tree: int, vocab:
                                     _dev(node_argmax), _dev(accept_len), _dev(accept_path), _dev(bonus_token),
                                     _dev(workspace), C.c_size_t(workspace.numel() * workspace.element_size()),
                                     _stream(stream)))
+
+
+def dream_accept_static_init() -> None:
+    _check(load().dream_accept_static_init())
+
+
+def dream_accept_path_static(logits, logits_dtype: int, batch: int, n_tree: int, vocab: int, token, parent, max_depth: int,
+                             node_argmax, accept_len, accept_path, bonus_token, stream=None) -> None:
+    _check(load().dream_accept_path_static(_dev(logits), C.c_int32(logits_dtype), C.c_int32(batch), C.c_int32(n_tree),
+                                           C.c_int32(vocab), _dev(token), _dev(parent), C.c_int32(max_depth),
+                                           _dev(node_argmax), _dev(accept_len), _dev(accept_path), _dev(bonus_token),
+                                           _stream(stream)))
 
 
 def dream_kv_commit(desc: AttnDesc, caches: Sequence[torch.Tensor], prefix_len: torch.Tensor, n_tree: int,

@@ -9,12 +9,19 @@
 // result does not depend on how rows are chunked.  accept_walk_kernel merges the chunk results and
 // walks the tree in node order in a single wavefront per sequence.
 #include "common.h"
+#include <mutex>
 
 using namespace dream;
+
+// Scratch of dream_accept_path_static: the per-chunk (value, index) partial results live here instead of in a
+// caller's workspace.  One copy per GPU, held until the process ends; host code only ever uses the address
+// hipGetSymbolAddress reports for the current device, never the symbol itself.
+static __device__ __align__(256) unsigned char scratch[DREAM_ACCEPT_STATIC_SCRATCH_BYTES];
 
 namespace {
 
 constexpr int CHUNK_ELEMS = 8192;   // logits handled by one workgroup
+constexpr int MAX_DEVICES = 64;
 
 __device__ __forceinline__ void better(float &v, int &i, float ov, int oi)
 {
@@ -148,24 +155,16 @@ __global__ __launch_bounds__(64) void accept_walk_kernel(const float *part_val, 
     }
 }
 
-}  // namespace
-
-extern "C" {
-
-size_t dream_accept_path_workspace(int32_t batch, int32_t n_tree, int32_t vocab)
+size_t partial_bytes(int batch, int n_tree, int vocab)
 {
-    if (batch < 1 || n_tree < 1 || vocab < 1)
-        return DREAM_WORKSPACE_HEADER_BYTES;
-    size_t n = (size_t)batch * n_tree * ceil_div(vocab, CHUNK_ELEMS);
-    return DREAM_WORKSPACE_HEADER_BYTES + align_up(n * 4, 256) + align_up(n * 4, 256);
+    const size_t n = (size_t)batch * n_tree * ceil_div(vocab, CHUNK_ELEMS);
+    return align_up(n * 4, 256) + align_up(n * 4, 256);
 }
 
-int dream_accept_path(const void *logits, int32_t logits_dtype, int32_t batch, int32_t n_tree, int32_t vocab,
-                      const int32_t *token, const int32_t *parent, int32_t max_depth, int32_t *node_argmax,
-                      int32_t *accept_len, int32_t *accept_path, int32_t *bonus_token, void *workspace,
-                      size_t workspace_bytes, void *stream)
+int validate_accept(const char *who, const void *logits, int logits_dtype, int batch, int n_tree, int vocab, const int32_t *token,
+                    const int32_t *parent, int max_depth, const int32_t *node_argmax, const int32_t *accept_len,
+                    const int32_t *accept_path, const int32_t *bonus_token)
 {
-    const char *who = "dream_accept_path";
     if (!logits || !token || !parent || !node_argmax || !accept_len || !accept_path || !bonus_token)
         return fail(DREAM_ERR_INVALID_ARG, "%s: NULL argument", who);
     if (logits_dtype != DREAM_F32 && logits_dtype != DREAM_BF16)
@@ -176,13 +175,18 @@ int dream_accept_path(const void *logits, int32_t logits_dtype, int32_t batch, i
         return fail(DREAM_ERR_UNSUPPORTED, "%s: n_tree %d outside [1, %d]", who, n_tree, DREAM_MAX_TREE_ACCEPT);
     if ((int64_t)batch * n_tree > 65535)
         return fail(DREAM_ERR_UNSUPPORTED, "%s: batch * n_tree = %lld exceeds 65535 rows", who, (long long)batch * n_tree);
-    const size_t need = dream_accept_path_workspace(batch, n_tree, vocab);
-    if (!workspace || workspace_bytes < need)
-        return fail(DREAM_ERR_WORKSPACE, "%s: workspace of %zu bytes, %zu needed", who, workspace_bytes, need);
+    return DREAM_OK;
+}
+
+// The two launches; `partials` is device memory of partial_bytes() bytes (a workspace or the static scratch).
+int launch_accept(const void *logits, int logits_dtype, int batch, int n_tree, int vocab, const int32_t *token, const int32_t *parent,
+                  int max_depth, int32_t *node_argmax, int32_t *accept_len, int32_t *accept_path, int32_t *bonus_token, void *partials,
+                  void *stream)
+{
     const int n_chunks = ceil_div(vocab, CHUNK_ELEMS);
     const size_t n = (size_t)batch * n_tree * n_chunks;
-    float *part_val = reinterpret_cast<float *>(static_cast<char *>(workspace) + DREAM_WORKSPACE_HEADER_BYTES);
-    int32_t *part_idx = reinterpret_cast<int32_t *>(static_cast<char *>(workspace) + DREAM_WORKSPACE_HEADER_BYTES + align_up(n * 4, 256));
+    float *part_val = reinterpret_cast<float *>(partials);
+    int32_t *part_idx = reinterpret_cast<int32_t *>(static_cast<char *>(partials) + align_up(n * 4, 256));
     hipStream_t st = as_stream(stream);
     dim3 grid(n_chunks, batch * n_tree);
     if (logits_dtype == DREAM_BF16)
@@ -195,6 +199,83 @@ int dream_accept_path(const void *logits, int32_t logits_dtype, int32_t batch, i
     hipLaunchKernelGGL(accept_walk_kernel, dim3(batch), dim3(64), 0, st, part_val, part_idx, n_chunks, n_tree, token, parent,
                        max_depth, node_argmax, accept_len, accept_path, bonus_token);
     return check_launch("accept_walk_kernel");
+}
+
+// Device address of `scratch` on the current GPU, looked up once per device (each GPU holds its own copy).
+int static_scratch_address(const char *who, void **out)
+{
+    static std::mutex mu;
+    static void *address[MAX_DEVICES] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES)
+        return fail(DREAM_ERR_HIP, "%s: no current HIP device (or its index is not below %d)", who, MAX_DEVICES);
+    std::lock_guard<std::mutex> lock(mu);
+    if (!address[dev]) {
+        void *p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p)
+            return fail(DREAM_ERR_HIP, "%s: hipGetSymbolAddress(scratch) on device %d: %s", who, dev, hipGetErrorString(e));
+        address[dev] = p;
+    }
+    *out = address[dev];
+    return DREAM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t dream_accept_path_workspace(int32_t batch, int32_t n_tree, int32_t vocab)
+{
+    if (batch < 1 || n_tree < 1 || vocab < 1)
+        return DREAM_WORKSPACE_HEADER_BYTES;
+    return DREAM_WORKSPACE_HEADER_BYTES + partial_bytes(batch, n_tree, vocab);
+}
+
+int dream_accept_path(const void *logits, int32_t logits_dtype, int32_t batch, int32_t n_tree, int32_t vocab,
+                      const int32_t *token, const int32_t *parent, int32_t max_depth, int32_t *node_argmax,
+                      int32_t *accept_len, int32_t *accept_path, int32_t *bonus_token, void *workspace,
+                      size_t workspace_bytes, void *stream)
+{
+    const char *who = "dream_accept_path";
+    int rc = validate_accept(who, logits, logits_dtype, batch, n_tree, vocab, token, parent, max_depth, node_argmax, accept_len,
+                             accept_path, bonus_token);
+    if (rc)
+        return rc;
+    const size_t need = dream_accept_path_workspace(batch, n_tree, vocab);
+    if (!workspace || workspace_bytes < need)
+        return fail(DREAM_ERR_WORKSPACE, "%s: workspace of %zu bytes, %zu needed", who, workspace_bytes, need);
+    return launch_accept(logits, logits_dtype, batch, n_tree, vocab, token, parent, max_depth, node_argmax, accept_len, accept_path,
+                         bonus_token, static_cast<char *>(workspace) + DREAM_WORKSPACE_HEADER_BYTES, stream);
+}
+
+int dream_accept_path_static(const void *logits, int32_t logits_dtype, int32_t batch, int32_t n_tree, int32_t vocab,
+                             const int32_t *token, const int32_t *parent, int32_t max_depth, int32_t *node_argmax,
+                             int32_t *accept_len, int32_t *accept_path, int32_t *bonus_token, void *stream)
+{
+    const char *who = "dream_accept_path_static";
+    int rc = validate_accept(who, logits, logits_dtype, batch, n_tree, vocab, token, parent, max_depth, node_argmax, accept_len,
+                             accept_path, bonus_token);
+    if (rc)
+        return rc;
+    const size_t need = partial_bytes(batch, n_tree, vocab);
+    if (need > DREAM_ACCEPT_STATIC_SCRATCH_BYTES)
+        return fail(DREAM_ERR_UNSUPPORTED, "%s: batch * n_tree * ceil(vocab / %d) = %zu partial results need %zu bytes, the static scratch "
+                    "holds %d; use dream_accept_path with a workspace", who, CHUNK_ELEMS,
+                    (size_t)batch * n_tree * ceil_div(vocab, CHUNK_ELEMS), need, DREAM_ACCEPT_STATIC_SCRATCH_BYTES);
+    void *base = nullptr;
+    rc = static_scratch_address(who, &base);
+    if (rc)
+        return rc;
+    // every partial result the walk reads is written by this call's first kernel: nothing has to start at zero
+    return launch_accept(logits, logits_dtype, batch, n_tree, vocab, token, parent, max_depth, node_argmax, accept_len, accept_path,
+                         bonus_token, base, stream);
+}
+
+int dream_accept_static_init(void)
+{
+    void *base = nullptr;
+    return static_scratch_address("dream_accept_static_init", &base);
 }
 
 }  // extern "C"
