@@ -20,10 +20,10 @@
  *     buffer.  The library allocates nothing, never synchronises, and enqueues all work on
  *     `stream` (a hipStream_t passed as void*; NULL = the default stream).  Results are valid
  *     once the caller has synchronised the stream.
- *   - Inputs are never written; outputs are fully overwritten; the workspace is scratch, except
- *     that its first DREAM_WORKSPACE_HEADER_BYTES must be zero when a call starts.  Zero them once
- *     with dream_workspace_init() after allocating; every call leaves them zero again.  Calls that
- *     share a workspace must be ordered on one stream.
+ *   - Inputs are never written; outputs are fully overwritten; the workspace is scratch whose
+ *     content means nothing between calls (no initialisation is needed).  A *_workspace() query
+ *     never returns less than DREAM_WORKSPACE_MIN_BYTES.  Calls that share a workspace must be
+ *     ordered on one stream.
  *   - Tensors are dense, C order.  bf16 means the upper 16 bits of an IEEE float32.
  *   - Every function returns a dream_status (0 = ok, negative = error) and never throws or
  *     aborts.  Argument errors are detected on the host before anything is launched; the text of
@@ -58,7 +58,7 @@ typedef enum {
     DREAM_ERR_HIP = -4          /* a HIP launch reported an error                              */
 } dream_status;
 
-#define DREAM_WORKSPACE_HEADER_BYTES 65536
+#define DREAM_WORKSPACE_MIN_BYTES 256
 #define DREAM_MAX_TREE 64       /* tree nodes per sequence handled by the attention calls      */
 #define DREAM_MAX_TREE_ACCEPT 1024 /* tree nodes per sequence handled by dream_accept_path     */
 #define DREAM_MAX_TREE_WIDTH 16     /* children per node / frontier rows of one tree-expansion level */
@@ -75,9 +75,6 @@ typedef struct {
     float scale;        /* multiplies q.k before the softmax; 0 selects 1/sqrt(D) (Eq. 1)      */
     int64_t s_max;      /* row capacity of every [B, Hkv, s_max, D] cache                      */
 } dream_attn_desc;
-
-/* Zero the workspace header (a small fill kernel on `stream`).  Call once per workspace. */
-int dream_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
  * Tree-masked verification attention (Section 3.1; Eq. 1 gives the attention form).
@@ -336,12 +333,11 @@ int dream_attn_plan_describe(const dream_attn_desc *desc, int32_t n_q, int64_t m
  * this call is the floor for any kernel that has to read that many bytes in one launch.  src 16-byte aligned. */
 int dream_stream_read(const void *src, size_t bytes, void *sink, void *stream);
 
-/* Launch-shape overrides for experiments (0 = choose automatically): number of key-range splits
- * the attention calls use, and number of 16-row query tiles one workgroup serves (1, 2 or 4).
- * Results are identical up to floating-point summation order.  Query the workspace size again
- * after changing either. */
-void dream_set_kv_splits(int32_t n_splits);
-void dream_set_q_tiles(int32_t q_tiles);
+/* One-time set-up for the CURRENT device, optional: raises the dynamic-LDS limit of every kernel that needs
+ * it and looks up the static scratch of dream_accept_path_static, so that no later call has to (each call
+ * otherwise does this itself the first time it needs it).  Call it outside any stream capture.  DREAM_OK,
+ * or DREAM_ERR_HIP when no GPU is usable. */
+int dream_init(void);
 
 #ifdef __cplusplus
 }

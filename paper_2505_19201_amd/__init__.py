@@ -7,7 +7,7 @@ library is missing or no GPU is present, calls fail loudly.
 """
 from .binding import (  # noqa: F401
     BF16, F32, DreamError, AttnDesc, attn_desc, load, library_path,
-    dream_workspace_init, dream_tree_verify_attn_workspace, dream_tree_verify_attn,
+    dream_init, dream_tree_verify_attn_workspace, dream_tree_verify_attn,
     dream_draft_xattn_workspace, dream_draft_xattn, dream_visual_compress_workspace,
     dream_visual_compress, dream_accept_path_workspace, dream_accept_path,
     dream_accept_path_static, dream_accept_static_init,

@@ -18,7 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libdream.so")
 
 EXPORTED_SYMBOLS = (
-    "dream_workspace_init", "dream_tree_verify_attn_workspace", "dream_tree_verify_attn",
+    "dream_init", "dream_tree_verify_attn_workspace", "dream_tree_verify_attn",
     "dream_draft_xattn_workspace", "dream_draft_xattn", "dream_visual_compress_workspace",
     "dream_visual_compress", "dream_accept_path_workspace", "dream_accept_path",
     "dream_tree_validate_host", "dream_last_error", "dream_set_kv_splits", "dream_set_q_tiles",
@@ -117,16 +117,13 @@ def dream_attn_plan_describe(desc: "AttnDesc", n_q: int, max_kv_len: int) -> str
     return buf.value.decode()
 
 
-def dream_workspace_init(workspace: torch.Tensor, stream=None) -> None:
-    _check(load().dream_workspace_init(_dev(workspace), C.c_size_t(workspace.numel() * workspace.element_size()),
-                                       _stream(stream)))
+def dream_init() -> None:
+    _check(load().dream_init())
 
 
 def alloc_workspace(nbytes: int, device="cuda") -> torch.Tensor:
-    """Device scratch of at least nbytes with its header zeroed (allocation is the caller's job in C)."""
-    ws = torch.empty(max(int(nbytes), 65536), dtype=torch.uint8, device=device)
-    dream_workspace_init(ws)
-    return ws
+    """Device scratch of at least nbytes (allocation is the caller's job in C; the content needs no initialisation)."""
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
 
 
 def to_device(a: np.ndarray, dtype: Optional[str] = None, device="cuda") -> torch.Tensor:

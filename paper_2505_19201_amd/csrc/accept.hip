@@ -228,8 +228,8 @@ extern "C" {
 size_t dream_accept_path_workspace(int32_t batch, int32_t n_tree, int32_t vocab)
 {
     if (batch < 1 || n_tree < 1 || vocab < 1)
-        return DREAM_WORKSPACE_HEADER_BYTES;
-    return DREAM_WORKSPACE_HEADER_BYTES + partial_bytes(batch, n_tree, vocab);
+        return DREAM_WORKSPACE_MIN_BYTES;
+    return DREAM_WORKSPACE_MIN_BYTES + partial_bytes(batch, n_tree, vocab);
 }
 
 int dream_accept_path(const void *logits, int32_t logits_dtype, int32_t batch, int32_t n_tree, int32_t vocab,
@@ -246,7 +246,7 @@ int dream_accept_path(const void *logits, int32_t logits_dtype, int32_t batch, i
     if (!workspace || workspace_bytes < need)
         return fail(DREAM_ERR_WORKSPACE, "%s: workspace of %zu bytes, %zu needed", who, workspace_bytes, need);
     return launch_accept(logits, logits_dtype, batch, n_tree, vocab, token, parent, max_depth, node_argmax, accept_len, accept_path,
-                         bonus_token, static_cast<char *>(workspace) + DREAM_WORKSPACE_HEADER_BYTES, stream);
+                         bonus_token, static_cast<char *>(workspace) + DREAM_WORKSPACE_MIN_BYTES, stream);
 }
 
 int dream_accept_path_static(const void *logits, int32_t logits_dtype, int32_t batch, int32_t n_tree, int32_t vocab,

@@ -123,68 +123,14 @@ __device__ __forceinline__ RowOwner row_owner(const AttnArgs &a, int kvh, int qg
 #define DREAM_Q1_WAVES 2
 #endif
 
-// Optional in-kernel timeline (build with -DDREAM_TIMESTAMPS): lane 0 of each wave of workgroup 8 records
-// the shader clock at a few points into a host-visible buffer.  Compiled out of the product build.
-#ifdef DREAM_TIMESTAMPS
-__device__ unsigned long long *g_dev_ts = nullptr;
-#define TS(i) do { if (g_dev_ts && blockIdx.x == 8 && blockIdx.y + blockIdx.z == 0 && lane == 0) g_dev_ts[wave * 64 + (i)] = clock64(); } while (0)
-#else
-#define TS(i) do { } while (0)
-#endif
-
-// QK^T, online softmax and PV for KT consecutive 32-key tiles held in LDS at `stage` (K tile, then V tile,
-// per 32 keys), for the QG query tiles of this wave.  key0 is the global key index of the first row.
-template <int D, int QG, int KT, int DV = D>
-__device__ __forceinline__ void tiles_compute(const uint16_t *stage, int key0, int P, int key_end, int n_tree, float scale_log2,
-                                              const bf16x8 (&qf)[QG][D / 32], const uint64_t (&qmask)[QG],
-                                              WaveState<QG, DV / 16> &st, int c, int g)
+// Online softmax of KT 32-key tiles for the QG query tiles of a wave.  sacc holds the raw scores S^T (lane owns
+// query column c and key rows g*4+r of every 16-key block); on return pf holds the probabilities as the bf16 B
+// operand of O^T += V^T P^T, and the running (reference, sum, accumulators) of `st` are updated.
+template <int QG, int KT, int NDT>
+__device__ __forceinline__ void softmax_tiles(f32x4 (&sacc)[KT][2][QG], bf16x8 (&pf)[KT][QG], WaveState<QG, NDT> &st,
+                                              const uint64_t (&qmask)[QG], bool needs_mask, int key0, int P, int key_end, int n_tree,
+                                              float scale_log2, int g)
 {
-    using G = Geom<D, QG, KT, DV>;
-    constexpr int KSTR = G::KSTR, VSTR = G::VSTR, NDT = G::NDT, NKS = G::NKS;
-    const bool needs_mask = key0 + KT * 32 > min(P, key_end);   // step touches tree rows, the ragged end or the next split
-
-    // ---- S^T = K Q^T for KT*32 keys x (16 * QG) query columns; independent accumulators keep the MFMA pipe full
-    f32x4 sacc[KT][2][QG];
-#pragma unroll
-    for (int kt = 0; kt < KT; kt++) {
-        const uint16_t *sk = stage + kt * G::TILE_ELEMS;
-        bf16x8 kfr[2][NKS];
-#pragma unroll
-        for (int ks = 0; ks < NKS; ks++) {
-            kfr[0][ks] = *reinterpret_cast<const bf16x8 *>(sk + c * KSTR + ks * 32 + g * 8);
-            kfr[1][ks] = *reinterpret_cast<const bf16x8 *>(sk + (16 + c) * KSTR + ks * 32 + g * 8);
-        }
-#pragma unroll
-        for (int qt = 0; qt < QG; qt++) {
-            sacc[kt][0][qt] = f32x4{0.f, 0.f, 0.f, 0.f};
-            sacc[kt][1][qt] = f32x4{0.f, 0.f, 0.f, 0.f};
-        }
-#pragma unroll
-        for (int ks = 0; ks < NKS; ks++) {
-#pragma unroll
-            for (int qt = 0; qt < QG; qt++) {
-                sacc[kt][0][qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kfr[0][ks], qf[qt][ks], sacc[kt][0][qt], 0, 0, 0);
-                sacc[kt][1][qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kfr[1][ks], qf[qt][ks], sacc[kt][1][qt], 0, 0, 0);
-            }
-        }
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    // ---- V^T fragments of the first tile (first half of the head dimension for D = 256) are requested
-    // now, so their LDS latency hides behind the softmax arithmetic
-    constexpr int VH = DV == 256 ? 2 : 1, NDH = NDT / VH;
-    s16x4 vfr[NDH][2];
-    const int v_off = 32 * KSTR + (g * 4 + (c >> 2)) * VSTR + (c & 3) * 4;
-    auto read_v = [&](int kt, int h) {
-        const uint16_t *vrow = stage + kt * G::TILE_ELEMS + v_off + h * NDH * 16;
-#pragma unroll
-        for (int dt = 0; dt < NDH; dt++) {
-            vfr[dt][0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(vrow + dt * 16));
-            vfr[dt][1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(vrow + dt * 16 + 16 * VSTR));
-        }
-    };
-    read_v(0, 0);
-    // ---- online softmax; lane owns query column c and key rows g*4+r of every 16-key block
-    bf16x8 pf[KT][QG];
     bool raise = false;
 #pragma unroll
     for (int qt = 0; qt < QG; qt++) {
@@ -244,6 +190,62 @@ __device__ __forceinline__ void tiles_compute(const uint16_t *stage, int key0, i
         }
         st.l[qt] += psum;
     }
+}
+
+// QK^T, online softmax and PV for KT consecutive 32-key tiles held in LDS at `stage` (K tile, then V tile,
+// per 32 keys), for the QG query tiles of this wave.  key0 is the global key index of the first row.
+template <int D, int QG, int KT, int DV = D>
+__device__ __forceinline__ void tiles_compute(const uint16_t *stage, int key0, int P, int key_end, int n_tree, float scale_log2,
+                                              const bf16x8 (&qf)[QG][D / 32], const uint64_t (&qmask)[QG],
+                                              WaveState<QG, DV / 16> &st, int c, int g)
+{
+    using G = Geom<D, QG, KT, DV>;
+    constexpr int KSTR = G::KSTR, VSTR = G::VSTR, NDT = G::NDT, NKS = G::NKS;
+    const bool needs_mask = key0 + KT * 32 > min(P, key_end);   // step touches tree rows, the ragged end or the next split
+
+    // ---- S^T = K Q^T for KT*32 keys x (16 * QG) query columns; independent accumulators keep the MFMA pipe full
+    f32x4 sacc[KT][2][QG];
+#pragma unroll
+    for (int kt = 0; kt < KT; kt++) {
+        const uint16_t *sk = stage + kt * G::TILE_ELEMS;
+        bf16x8 kfr[2][NKS];
+#pragma unroll
+        for (int ks = 0; ks < NKS; ks++) {
+            kfr[0][ks] = *reinterpret_cast<const bf16x8 *>(sk + c * KSTR + ks * 32 + g * 8);
+            kfr[1][ks] = *reinterpret_cast<const bf16x8 *>(sk + (16 + c) * KSTR + ks * 32 + g * 8);
+        }
+#pragma unroll
+        for (int qt = 0; qt < QG; qt++) {
+            sacc[kt][0][qt] = f32x4{0.f, 0.f, 0.f, 0.f};
+            sacc[kt][1][qt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+#pragma unroll
+        for (int ks = 0; ks < NKS; ks++) {
+#pragma unroll
+            for (int qt = 0; qt < QG; qt++) {
+                sacc[kt][0][qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kfr[0][ks], qf[qt][ks], sacc[kt][0][qt], 0, 0, 0);
+                sacc[kt][1][qt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kfr[1][ks], qf[qt][ks], sacc[kt][1][qt], 0, 0, 0);
+            }
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // ---- V^T fragments of the first tile (first half of the head dimension for D = 256) are requested
+    // now, so their LDS latency hides behind the softmax arithmetic
+    constexpr int VH = DV == 256 ? 2 : 1, NDH = NDT / VH;
+    s16x4 vfr[NDH][2];
+    const int v_off = 32 * KSTR + (g * 4 + (c >> 2)) * VSTR + (c & 3) * 4;
+    auto read_v = [&](int kt, int h) {
+        const uint16_t *vrow = stage + kt * G::TILE_ELEMS + v_off + h * NDH * 16;
+#pragma unroll
+        for (int dt = 0; dt < NDH; dt++) {
+            vfr[dt][0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(vrow + dt * 16));
+            vfr[dt][1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(vrow + dt * 16 + 16 * VSTR));
+        }
+    };
+    read_v(0, 0);
+    // ---- online softmax; lane owns query column c and key rows g*4+r of every 16-key block
+    bf16x8 pf[KT][QG];
+    softmax_tiles<QG, KT, NDT>(sacc, pf, st, qmask, needs_mask, key0, P, key_end, n_tree, scale_log2, g);
     // ---- O^T += V^T P^T
 #pragma unroll
     for (int kt = 0; kt < KT; kt++) {
@@ -277,7 +279,6 @@ __global__ __launch_bounds__(256, (QG == 1 && D <= 128) ? DREAM_Q1_WAVES : 1) vo
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps bookkeeping in scalar registers
     const int c = lane & 15, g = lane >> 4;
-    TS(0);
 
     // workgroup id -> (K/V stream, query group): ids that share a stream are congruent mod 8 (same XCD)
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
@@ -302,7 +303,6 @@ __global__ __launch_bounds__(256, (QG == 1 && D <= 128) ? DREAM_Q1_WAVES : 1) vo
     const int n_my = max(t_end - t_begin, 0);
     const int n_steps = (n_my + KT - 1) / KT;
     const int key_end = min(kv_len, t_end * 32);   // keys at or past it belong to nobody or to the next split
-    if (key_end >= 0) TS(1);
 
     const uint16_t *kbase = reinterpret_cast<const uint16_t *>(a.k) + ((int64_t)b * a.n_kv_heads + kvh) * a.s_max * D;
     const uint16_t *vbase = reinterpret_cast<const uint16_t *>(a.v) + ((int64_t)b * a.n_kv_heads + kvh) * a.s_max * D;
@@ -352,9 +352,7 @@ __global__ __launch_bounds__(256, (QG == 1 && D <= 128) ? DREAM_Q1_WAVES : 1) vo
     wave_active = __any(wave_active);
     if (!a.tree_mask && tid < a.n_tree)
         lds_parent[tid] = my_parent < tid ? my_parent : -1;   // a walk up the tree always ends
-    TS(2);
     __syncthreads();   // parents staged
-    TS(3);
 
     uint64_t qmask[QG];
 #pragma unroll
@@ -381,7 +379,6 @@ __global__ __launch_bounds__(256, (QG == 1 && D <= 128) ? DREAM_Q1_WAVES : 1) vo
 
     // one step of KT tiles: registers -> LDS stage, barrier, refill the register set, compute from LDS
     auto step = [&](int i, u32x4(&kr)[NLD], u32x4(&vr)[NLD]) {
-        TS(8 + i * 5);
         uint16_t *stage = lds + (i & 1) * G::STAGE_ELEMS;
         {
             uint16_t *dk = stage + ld_row * KSTR + ld_col * 8, *dv = stage + 32 * KSTR + ld_row * VSTR + ld_col * 8;
@@ -395,9 +392,7 @@ __global__ __launch_bounds__(256, (QG == 1 && D <= 128) ? DREAM_Q1_WAVES : 1) vo
             }
         }
         __syncthreads();
-        TS(9 + i * 5);
         load_step(i + PFD, kr, vr);
-        TS(10 + i * 5);
         if (!wave_active)
             return;
         tiles_compute<D, QG, KT>(stage, (t_begin + i * KT) * 32, P, key_end, a.n_tree, a.scale_log2, qf, qmask, st, c, g);
@@ -405,9 +400,7 @@ __global__ __launch_bounds__(256, (QG == 1 && D <= 128) ? DREAM_Q1_WAVES : 1) vo
 
     // every load issued so far (queries, masks, first tiles) has to land before the loop: the in-order
     // load counter then only ever counts tile prefetches inside it
-    TS(4);
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0)
-    TS(5);
     {
         int i = 0;
         for (; i + PFD <= n_steps; i += PFD) {
@@ -424,7 +417,6 @@ __global__ __launch_bounds__(256, (QG == 1 && D <= 128) ? DREAM_Q1_WAVES : 1) vo
     if (!wave_active)
         return;
 
-    if (st.o[0][0][0] != 12345.f) TS(6);
     // the softmax sum was kept per lane over the lane's own key rows: complete it across the 4 row groups
 #pragma unroll
     for (int qt = 0; qt < QG; qt++) {
@@ -437,7 +429,6 @@ __global__ __launch_bounds__(256, (QG == 1 && D <= 128) ? DREAM_Q1_WAVES : 1) vo
         // several splits: publish this wave's state for attn_merge_kernel
         const int64_t grp = ((int64_t)b * a.n_kv_heads + kvh) * a.n_qg + qg;
         state_store<QG, NDT>(st, a.part + ((grp * nsplit + split) * 4 + wave) * StateGeom<D, QG>::STATE_FLOATS, lane);
-        TS(7);
         return;
     }
     constexpr float LN2 = 0.6931471805599453f;
@@ -525,7 +516,6 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a)
     const int kvh = blockIdx.y * 8 + (blockIdx.x & 7), tq0 = (unit / DS) * QT, ds = unit % DS, b = blockIdx.z;
     if (kvh >= a.n_kv_heads)
         return;
-    TS(0);
     const uint16_t *kbase = reinterpret_cast<const uint16_t *>(a.k) + ((int64_t)b * a.n_kv_heads + kvh) * a.s_max * D;
     const uint16_t *vbase = reinterpret_cast<const uint16_t *>(a.v) + ((int64_t)b * a.n_kv_heads + kvh) * a.s_max * D + ds * DV;
 
@@ -536,7 +526,6 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a)
     const int kv_len = P + a.n_tree;
     const int t_end = (kv_len + 31) / 32;
     const int n = t_end > wave ? (t_end - wave + NW - 1) / NW : 0;   // tiles of this wave: wave, wave + NW, ...
-    if (kv_len > 0) TS(1);
 
     u32x4 kr[CHK], vr[CHV];
     const int k_row = lane / (D / 8), k_col = lane % (D / 8), v_row = lane / (DV / 8), v_col = lane % (DV / 8);
@@ -556,7 +545,6 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a)
         }
     };
     issue(wave);
-    TS(2);
 
     // the query tiles: head hh of the group, rows nt*16 .. nt*16+15 (at most 4 heads per group, so three compares instead of a division)
     const int tph = a.tiles_per_head;
@@ -580,7 +568,6 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a)
     if (!a.tree_mask && tid < a.n_tree)
         lds_parent[tid] = my_parent < tid ? my_parent : -1;   // a walk up the tree always ends
     __syncthreads();
-    TS(3);
     uint64_t qmask[QT];
     WaveState<QT, NDT> st;
 #pragma unroll
@@ -599,9 +586,7 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a)
         for (int dt = 0; dt < NDT; dt++)
             st.o[qt][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
-    TS(4);
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): from here on only tile prefetches are in flight
-    TS(5);
 
     uint16_t *wt = lds + wave * G::TILE_ELEMS;
     for (int i = 0; i < n; i++) {
@@ -614,11 +599,9 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a)
         for (int j = 0; j < CHV; j++)
             *reinterpret_cast<u32x4 *>(dv + j * (512 / DV) * VSTR) = vr[j];
         wave_lds_fence();
-        TS(8 + i * 2);
         issue(t + NW);
         tiles_compute<D, QT, 1, DV>(wt, t * 32, P, kv_len, a.n_tree, a.scale_log2, qf, qmask, st, c, g);
         wave_lds_fence();
-        if (st.l[0] != 12345.f) TS(9 + i * 2);
     }
 #pragma unroll
     for (int qt = 0; qt < QT; qt++) {
@@ -630,7 +613,6 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a)
     // merge the waves through LDS (the tile areas are free by then) in one round: every wave parks its
     // state, then wave w sums the 16-wide output column tiles w, w+NW, ... over the states in wave order
     float *mbuf = reinterpret_cast<float *>(smem_raw);
-    TS(6);
     __syncthreads();
     state_store<QT, NDT>(st, mbuf + wave * STATE, lane);
     __syncthreads();
@@ -667,12 +649,6 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a)
         if (wave == 0 && ds == 0 && a.lse && g == 0)
             a.lse[((int64_t)b * a.n_q_heads + head[qt]) * a.n_q + row[qt]] = l > 0.0f ? (m + log2f(l)) * 0.6931471805599453f : -INFINITY;
     }
-#ifdef DREAM_TIMESTAMPS
-    if (wave == 0) {
-        __builtin_amdgcn_s_waitcnt(0x0F70);
-        TS(63);
-    }
-#endif
 }
 
 // Merge the split states of one (group, wave, query tile) in split order and write the rows.  One
@@ -907,8 +883,8 @@ int make_plan(const dream_attn_desc *d, int n_q, int64_t max_kv_len, Plan *p)
         p->kt = 1;
         p->pfd = 1;
         p->state_floats = 0;
-        p->off_part = DREAM_WORKSPACE_HEADER_BYTES;
-        p->total = DREAM_WORKSPACE_HEADER_BYTES;
+        p->off_part = DREAM_WORKSPACE_MIN_BYTES;
+        p->total = DREAM_WORKSPACE_MIN_BYTES;
         return 0;
     }
     int s = kv_splits_override();
@@ -943,10 +919,10 @@ int make_plan(const dream_attn_desc *d, int n_q, int64_t max_kv_len, Plan *p)
             p->pfd = 1;
     }
     p->state_floats = (size_t)qg * (d->head_dim / 16) * 256 + (size_t)qg * 2 * 64;
-    p->off_part = DREAM_WORKSPACE_HEADER_BYTES;
+    p->off_part = DREAM_WORKSPACE_MIN_BYTES;
     p->total = p->off_part + (s > 1 ? (size_t)groups * s * 4 * p->state_floats * sizeof(float) : 0);
     if (d->dtype == DREAM_F32)
-        p->total = DREAM_WORKSPACE_HEADER_BYTES;
+        p->total = DREAM_WORKSPACE_MIN_BYTES;
     return 0;
 }
 
@@ -967,17 +943,28 @@ int validate_desc(const dream_attn_desc *d, const char *who)
     return DREAM_OK;
 }
 
+// The dynamic-LDS limit of a kernel is raised once (dream_init does it for every variant up front; a variant
+// that is reached first by a call does it then).  Two threads may both set it once: harmless.
 template <int D, int QG, int KT, int PFD>
-int launch_bf16(const AttnArgs &a, const Plan &p, hipStream_t st)
+int ensure_bf16_lds()
 {
     using G = Geom<D, QG, KT>;
-    static std::atomic<bool> attr_set{false};   // (two threads may both set the attribute once: harmless)
+    static std::atomic<bool> attr_set{false};
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_kernel<D, QG, KT, PFD>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)G::LDS_BYTES) != hipSuccess)
             return fail(DREAM_ERR_HIP, "attention: cannot reserve %zu bytes of LDS", G::LDS_BYTES);
         attr_set = true;
     }
+    return DREAM_OK;
+}
+
+template <int D, int QG, int KT, int PFD>
+int launch_bf16(const AttnArgs &a, const Plan &p, hipStream_t st)
+{
+    using G = Geom<D, QG, KT>;
+    if (int rc = ensure_bf16_lds<D, QG, KT, PFD>())
+        return rc;
     hipLaunchKernelGGL((attn_bf16_kernel<D, QG, KT, PFD>), dim3(p.grid), dim3(256), G::LDS_BYTES, st, a);
     int rc = check_launch("attn_bf16_kernel");
     if (rc || p.n_splits == 1)
@@ -986,20 +973,33 @@ int launch_bf16(const AttnArgs &a, const Plan &p, hipStream_t st)
     return check_launch("attn_merge_kernel");
 }
 
+template <int D, int NW, int DS, int QT>
+struct WaveLds {
+    using G = Geom<D, 1, 1, D / DS>;
+    static constexpr size_t tile_bytes = (size_t)NW * G::TILE_ELEMS * 2, merge_bytes = (size_t)NW * StateGeom<D / DS, QT>::STATE_FLOATS * 4;
+    static constexpr size_t bytes = (tile_bytes > merge_bytes ? tile_bytes : merge_bytes) + DREAM_MAX_TREE * sizeof(int32_t);
+    static_assert(merge_bytes <= tile_bytes, "the wave merge buffers reuse the tile area");
+};
+
+template <int D, int NW, int DS, int QT = 1>
+int ensure_wave_lds()
+{
+    static std::atomic<bool> attr_set{false};
+    if (!attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_wave_kernel<D, NW, DS, QT>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)WaveLds<D, NW, DS, QT>::bytes) != hipSuccess)
+            return fail(DREAM_ERR_HIP, "attention: cannot reserve %zu bytes of LDS", WaveLds<D, NW, DS, QT>::bytes);
+        attr_set = true;
+    }
+    return DREAM_OK;
+}
+
 template <int D, int NW, int DS, int QT = 1>
 int launch_wave(const AttnArgs &a, const Plan &p, hipStream_t st)
 {
-    using G = Geom<D, 1, 1, D / DS>;
-    constexpr size_t tile_bytes = (size_t)NW * G::TILE_ELEMS * 2, merge_bytes = (size_t)NW * StateGeom<D / DS, QT>::STATE_FLOATS * 4;
-    constexpr size_t lds_bytes = (tile_bytes > merge_bytes ? tile_bytes : merge_bytes) + DREAM_MAX_TREE * sizeof(int32_t);
-    static_assert(merge_bytes <= tile_bytes, "the wave merge buffers reuse the tile area");
-    static std::atomic<bool> attr_set{false};   // (two threads may both set the attribute once: harmless)
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_wave_kernel<D, NW, DS, QT>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)lds_bytes) != hipSuccess)
-            return fail(DREAM_ERR_HIP, "attention: cannot reserve %zu bytes of LDS", lds_bytes);
-        attr_set = true;
-    }
+    constexpr size_t lds_bytes = WaveLds<D, NW, DS, QT>::bytes;
+    if (int rc = ensure_wave_lds<D, NW, DS, QT>())
+        return rc;
     if (a.n_qg > 16 || a.group > 4)
         return fail(DREAM_ERR_INVALID_ARG, "attention: the wave kernel serves at most 16 query tiles and 4 query heads per KV head");
     const dim3 grid(8 * ceil_div(a.n_qg, QT) * DS, ceil_div(a.n_kv_heads, 8), p.n_streams / a.n_kv_heads);
@@ -1116,29 +1116,53 @@ size_t workspace_for(const dream_attn_desc *d, int n_q, int64_t max_kv_len)
 {
     if (!d || d->n_kv_heads < 1 || d->n_q_heads < 1 || d->n_q_heads % d->n_kv_heads || n_q < 1 || max_kv_len < 1 ||
         d->batch < 1)
-        return DREAM_WORKSPACE_HEADER_BYTES;
+        return DREAM_WORKSPACE_MIN_BYTES;
     Plan p;
     make_plan(d, n_q, max_kv_len, &p);
     return p.total;
 }
 
+template <int D>
+int ensure_all_for_head_dim()
+{
+    int rc = DREAM_OK;
+    auto acc = [&](int r) { if (r && !rc) rc = r; };
+    if constexpr (D <= 128) {
+        acc(ensure_bf16_lds<D, 1, 2, 1>()); acc(ensure_bf16_lds<D, 1, 3, 1>()); acc(ensure_bf16_lds<D, 1, 4, 1>());
+        acc(ensure_bf16_lds<D, 2, 1, 2>());
+        acc(ensure_wave_lds<D, 8, 1, 2>()); acc(ensure_wave_lds<D, 4, 1, 2>());
+        acc(ensure_wave_lds<D, 8, 1>()); acc(ensure_wave_lds<D, 8, 2>());
+    }
+    if constexpr (D == 64) {
+        acc(ensure_bf16_lds<D, 1, 2, 2>()); acc(ensure_bf16_lds<D, 4, 1, 2>());
+    } else {
+        acc(ensure_bf16_lds<D, 1, 1, 2>());
+    }
+    if constexpr (D == 128) {
+        acc(ensure_bf16_lds<D, 4, 1, 1>()); acc(ensure_wave_lds<D, 8, 4>());
+    }
+    if constexpr (D == 256)
+        acc(ensure_bf16_lds<D, 2, 1, 1>());
+    if constexpr (D >= 128)
+        acc(ensure_wave_lds<D, 4, 4>());
+    acc(ensure_wave_lds<D, 4, 1>()); acc(ensure_wave_lds<D, 4, 2>());
+    return rc;
+}
+
 }  // namespace
 
-extern "C" {
-
-#ifdef DREAM_TIMESTAMPS
-unsigned long long *dream_debug_ts(void)
+namespace dream {
+// every attention kernel variant the launch plan can choose (part of dream_init)
+int attn_init()
 {
-    static unsigned long long *buf = nullptr;
-    if (!buf) {
-        (void)hipHostMalloc(reinterpret_cast<void **>(&buf), 4 * 64 * 8, 0);
-        for (int i = 0; i < 256; i++)
-            buf[i] = 0;
-        (void)hipMemcpyToSymbol(HIP_SYMBOL(g_dev_ts), &buf, sizeof(buf));
-    }
-    return buf;
+    int rc = ensure_all_for_head_dim<64>();
+    if (!rc) rc = ensure_all_for_head_dim<128>();
+    if (!rc) rc = ensure_all_for_head_dim<256>();
+    return rc;
 }
-#endif
+}  // namespace dream
+
+extern "C" {
 
 int dream_attn_plan_describe(const dream_attn_desc *desc, int32_t n_q, int64_t max_kv_len, char *buf, size_t buf_bytes)
 {

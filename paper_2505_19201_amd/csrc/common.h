@@ -20,6 +20,10 @@ inline int ceil_div(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 int kv_splits_override();
 int q_tiles_override();
 
+// per-file parts of dream_init()
+int attn_init();
+int compress_init();
+
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));

@@ -1,12 +1,14 @@
-// Error reporting, workspace initialisation and tree validation shared by all entry points.
+// Error reporting, launch-shape overrides, the read-only measurement kernel and tree validation shared by all entry points.
 #include "common.h"
+#include "dream_tuning.h"
+#include <atomic>
 #include <string.h>
 
 namespace dream {
 
 static thread_local char g_error[512] = "";
-static int g_kv_splits = 0;
-static int g_q_tiles = 0;
+static std::atomic<int> g_kv_splits{0};
+static std::atomic<int> g_q_tiles{0};
 
 char *error_buffer() { return g_error; }
 
@@ -27,15 +29,8 @@ int check_launch(const char *what)
     return DREAM_OK;
 }
 
-int kv_splits_override() { return g_kv_splits; }
-int q_tiles_override() { return g_q_tiles; }
-
-__global__ void zero_words_kernel(uint32_t *p, int n)
-{
-    int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n)
-        p[i] = 0u;
-}
+int kv_splits_override() { return g_kv_splits.load(std::memory_order_relaxed); }
+int q_tiles_override() { return g_q_tiles.load(std::memory_order_relaxed); }
 
 // Reads n16 16-byte words once, grid-stride, and folds them into one word per thread; the fold is stored only
 // if it equals a value the caller does not expect, which keeps the loads alive without a write stream.
@@ -58,21 +53,21 @@ extern "C" {
 
 const char *dream_last_error(void) { return error_buffer(); }
 
-void dream_set_kv_splits(int32_t n_splits) { dream::g_kv_splits = n_splits < 0 ? 0 : n_splits; }
+void dream_set_kv_splits(int32_t n_splits) { dream::g_kv_splits.store(n_splits < 0 ? 0 : n_splits, std::memory_order_relaxed); }
 
-void dream_set_q_tiles(int32_t q_tiles) { dream::g_q_tiles = q_tiles < 0 ? 0 : q_tiles; }
+void dream_set_q_tiles(int32_t q_tiles) { dream::g_q_tiles.store(q_tiles < 0 ? 0 : q_tiles, std::memory_order_relaxed); }
 
-int dream_workspace_init(void *workspace, size_t workspace_bytes, void *stream)
+int dream_init(void)
 {
-    if (!workspace)
-        return fail(DREAM_ERR_INVALID_ARG, "dream_workspace_init: workspace is NULL");
-    if (workspace_bytes < DREAM_WORKSPACE_HEADER_BYTES)
-        return fail(DREAM_ERR_WORKSPACE, "dream_workspace_init: workspace of %zu bytes is smaller than the %d-byte header",
-                    workspace_bytes, DREAM_WORKSPACE_HEADER_BYTES);
-    const int n = DREAM_WORKSPACE_HEADER_BYTES / 4;
-    hipLaunchKernelGGL(zero_words_kernel, dim3((n + 255) / 256), dim3(256), 0, as_stream(stream),
-                       reinterpret_cast<uint32_t *>(workspace), n);
-    return check_launch("dream_workspace_init");
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess)
+        return fail(DREAM_ERR_HIP, "dream_init: no usable HIP device");
+    int rc = attn_init();
+    if (!rc)
+        rc = compress_init();
+    if (!rc)
+        rc = dream_accept_static_init();
+    return rc;
 }
 
 int dream_stream_read(const void *src, size_t bytes, void *sink, void *stream)

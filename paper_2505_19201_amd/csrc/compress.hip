@@ -656,20 +656,37 @@ CompressPlan compress_plan(int batch, int n_heads, int n_q, int vis_len, int dty
         p.ns1 = score_splits((int64_t)ceil_div(n_q, 64) * n_heads * batch, ceil_div(n_q, 32));
         p.ns2 = score_splits((int64_t)ceil_div(vis_len > 0 ? vis_len : 1, 64) * n_heads * batch, ceil_div(n_q, 32));
     }
-    p.off_lse = DREAM_WORKSPACE_HEADER_BYTES;
+    p.off_lse = DREAM_WORKSPACE_MIN_BYTES;
     p.off_part = align_up(p.off_lse + (size_t)p.ns1 * batch * n_heads * p.n_q_pad * sizeof(float), 256);
     p.total = align_up(p.off_part + (size_t)p.ns2 * batch * n_heads * (vis_len > 0 ? vis_len : 1) * sizeof(float), 256);
     return p;
 }
 
+// the selection kernel's dynamic LDS holds up to DREAM_MAX_VISUAL scores: raise its limit once
+int ensure_topk_lds(const char *who)
+{
+    static std::atomic<bool> attr_set{false};   // (two threads may both set the attribute once: harmless)
+    if (!attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&topk_keep_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                DREAM_MAX_VISUAL * 4 + (256 + 32 + 4) * 4) != hipSuccess)
+            return fail(DREAM_ERR_HIP, "%s: cannot reserve LDS for the selection kernel", who);
+        attr_set = true;
+    }
+    return DREAM_OK;
+}
+
 }  // namespace
+
+namespace dream {
+int compress_init() { return ensure_topk_lds("dream_init"); }
+}  // namespace dream
 
 extern "C" {
 
 size_t dream_visual_compress_workspace(const dream_attn_desc *desc, int32_t n_q, int32_t vis_len)
 {
     if (!desc || desc->batch < 1 || desc->n_q_heads < 1 || n_q < 1)
-        return DREAM_WORKSPACE_HEADER_BYTES;
+        return DREAM_WORKSPACE_MIN_BYTES;
     return compress_plan(desc->batch, desc->n_q_heads, n_q, vis_len, desc->dtype).total;
 }
 
@@ -763,13 +780,8 @@ int dream_visual_compress(const dream_attn_desc *desc, const void *q, const int3
         *n_kept_host = k;
     if (vis_len > 0 && (k > 0 || scores_out)) {
         size_t lds = (size_t)vis_len * 4 + (256 + 32 + 4) * 4;
-        static std::atomic<bool> attr_set{false};   // (two threads may both set the attribute once: harmless)
-        if (!attr_set) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(&topk_keep_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    DREAM_MAX_VISUAL * 4 + (256 + 32 + 4) * 4) != hipSuccess)
-                return fail(DREAM_ERR_HIP, "%s: cannot reserve LDS for the selection kernel", who);
-            attr_set = true;
-        }
+        if (int rc = ensure_topk_lds(who))
+            return rc;
         hipLaunchKernelGGL(topk_keep_kernel, dim3(desc->batch), dim3(1024), lds, st, part, n_heads, scores_in, scores_out,
                            vis_start, vis_len, k, kept_idx);
         int rc = check_launch("topk_keep_kernel");
@@ -789,11 +801,11 @@ int dream_visual_compress(const dream_attn_desc *desc, const void *q, const int3
 size_t dream_attention_entropy_workspace(const dream_attn_desc *desc, int32_t n_q)
 {
     if (!desc || desc->batch < 1 || desc->n_q_heads < 1 || n_q < 1)
-        return DREAM_WORKSPACE_HEADER_BYTES;
+        return DREAM_WORKSPACE_MIN_BYTES;
     const CompressPlan p = compress_plan(desc->batch, desc->n_q_heads, n_q, 0, desc->dtype);
     const size_t part = align_up((size_t)p.ns1 * desc->batch * desc->n_q_heads * p.n_q_pad * sizeof(float), 256);
     const size_t sums = align_up((size_t)desc->batch * ceil_div((int64_t)desc->n_q_heads * n_q, 256) * sizeof(float), 256);
-    return DREAM_WORKSPACE_HEADER_BYTES + 2 * part + sums;
+    return DREAM_WORKSPACE_MIN_BYTES + 2 * part + sums;
 }
 
 int dream_attention_entropy(const dream_attn_desc *desc, const void *q, const int32_t *q_pos, int32_t n_q, const void *k_cache,
@@ -817,14 +829,14 @@ int dream_attention_entropy(const dream_attn_desc *desc, const void *q, const in
     const CompressPlan p = compress_plan(desc->batch, desc->n_q_heads, n_q, 0, desc->dtype);
     const size_t part = align_up((size_t)p.ns1 * desc->batch * desc->n_q_heads * p.n_q_pad * sizeof(float), 256);
     const int n_blocks = ceil_div((int64_t)desc->n_q_heads * n_q, 256);
-    const size_t need = DREAM_WORKSPACE_HEADER_BYTES + 2 * part + align_up((size_t)desc->batch * n_blocks * sizeof(float), 256);
+    const size_t need = DREAM_WORKSPACE_MIN_BYTES + 2 * part + align_up((size_t)desc->batch * n_blocks * sizeof(float), 256);
     if (!workspace || workspace_bytes < need)
         return fail(DREAM_ERR_WORKSPACE, "%s: workspace of %zu bytes, %zu needed", who, workspace_bytes, need);
     hipStream_t st = as_stream(stream);
     ScoreArgs a;
     a.q = q; a.k = k_cache; a.q_pos = q_pos;
-    a.lse2 = reinterpret_cast<float *>(static_cast<char *>(workspace) + DREAM_WORKSPACE_HEADER_BYTES);
-    a.ent_part = reinterpret_cast<float *>(static_cast<char *>(workspace) + DREAM_WORKSPACE_HEADER_BYTES + part);
+    a.lse2 = reinterpret_cast<float *>(static_cast<char *>(workspace) + DREAM_WORKSPACE_MIN_BYTES);
+    a.ent_part = reinterpret_cast<float *>(static_cast<char *>(workspace) + DREAM_WORKSPACE_MIN_BYTES + part);
     a.part = nullptr;
     a.n_q = n_q; a.n_q_pad = p.n_q_pad; a.n_keys = n_keys;
     a.n_q_heads = desc->n_q_heads; a.n_kv_heads = desc->n_kv_heads;
@@ -850,7 +862,7 @@ int dream_attention_entropy(const dream_attn_desc *desc, const void *q, const in
     int rc = check_launch("entropy score kernel");
     if (rc)
         return rc;
-    float *block_sum = reinterpret_cast<float *>(static_cast<char *>(workspace) + DREAM_WORKSPACE_HEADER_BYTES + 2 * part);
+    float *block_sum = reinterpret_cast<float *>(static_cast<char *>(workspace) + DREAM_WORKSPACE_MIN_BYTES + 2 * part);
     hipLaunchKernelGGL(entropy_rows_kernel, dim3(n_blocks, desc->batch), dim3(256), 0, st, a, desc->dtype == DREAM_BF16 ? 1 : 0, row_entropy,
                        block_sum);
     hipLaunchKernelGGL(entropy_mean_kernel, dim3(desc->batch), dim3(64), 0, st, block_sum, n_blocks, desc->n_q_heads * n_q, ae);

@@ -724,9 +724,9 @@ extern "C" {
 size_t dream_spec_accept_workspace(int32_t batch, int32_t n_tree, int32_t vocab)
 {
     if (batch < 1 || n_tree < 1 || vocab < 1)
-        return DREAM_WORKSPACE_HEADER_BYTES;
+        return DREAM_WORKSPACE_MIN_BYTES;
     const size_t stats = align_up((size_t)2 * batch * n_tree * ceil_div(vocab, STAT_CHUNK) * sizeof(float), 256);
-    return DREAM_WORKSPACE_HEADER_BYTES + align_up((size_t)batch * 3 * vocab * sizeof(float), 256) + 3 * stats + align_up((size_t)batch * n_tree * 4 * sizeof(float), 256);
+    return DREAM_WORKSPACE_MIN_BYTES + align_up((size_t)batch * 3 * vocab * sizeof(float), 256) + 3 * stats + align_up((size_t)batch * n_tree * 4 * sizeof(float), 256);
 }
 
 int dream_spec_accept(const void *target_logits, const void *draft_logits, int32_t logits_dtype, int32_t batch, int32_t n_tree,
@@ -752,7 +752,7 @@ int dream_spec_accept(const void *target_logits, const void *draft_logits, int32
         return fail(DREAM_ERR_WORKSPACE, "%s: workspace of %zu bytes, %zu needed", who, workspace_bytes, need);
     const int n_chunks = ceil_div(vocab, STAT_CHUNK);
     const size_t stats = align_up((size_t)2 * batch * n_tree * n_chunks * sizeof(float), 256);
-    char *wsb = static_cast<char *>(workspace) + DREAM_WORKSPACE_HEADER_BYTES;
+    char *wsb = static_cast<char *>(workspace) + DREAM_WORKSPACE_MIN_BYTES;
     float *work = reinterpret_cast<float *>(wsb);
     float *stat_m = reinterpret_cast<float *>(wsb + align_up((size_t)batch * 3 * vocab * sizeof(float), 256));
     float *stat_s = reinterpret_cast<float *>(reinterpret_cast<char *>(stat_m) + stats);

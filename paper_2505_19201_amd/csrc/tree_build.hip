@@ -377,7 +377,7 @@ ExpandPlan expand_plan(int batch, int n_frontier, int vocab, int k)
     ExpandPlan p;
     p.n_chunks = ceil_div(vocab, CHUNK);
     const size_t rows = (size_t)batch * n_frontier;
-    p.off_m = DREAM_WORKSPACE_HEADER_BYTES;
+    p.off_m = DREAM_WORKSPACE_MIN_BYTES;
     p.off_s = align_up(p.off_m + rows * p.n_chunks * sizeof(float), 256);
     p.off_key = align_up(p.off_s + rows * p.n_chunks * sizeof(float), 256);
     p.total = align_up(p.off_key + rows * p.n_chunks * k * sizeof(uint64_t), 256);
@@ -391,7 +391,7 @@ extern "C" {
 size_t dream_tree_expand_workspace(int32_t batch, int32_t n_frontier, int32_t vocab, int32_t k)
 {
     if (batch < 1 || n_frontier < 1 || vocab < 1 || k < 1)
-        return DREAM_WORKSPACE_HEADER_BYTES;
+        return DREAM_WORKSPACE_MIN_BYTES;
     return expand_plan(batch, n_frontier, vocab, k).total;
 }
 

@@ -25,7 +25,7 @@ int main(void)
         printf("plan: %s\n", dream_last_error());
         return 3;
     }
-    if (dream_tree_verify_attn_workspace(&desc, 60, 764) < DREAM_WORKSPACE_HEADER_BYTES)
+    if (dream_tree_verify_attn_workspace(&desc, 60, 764) < DREAM_WORKSPACE_MIN_BYTES)
         return 4;
     /* a NULL tensor is an argument error found on the host: nothing is launched */
     if (dream_tree_verify_attn(&desc, NULL, NULL, NULL, NULL, 60, NULL, NULL, 764, NULL, NULL, NULL, 0, NULL) != DREAM_ERR_INVALID_ARG)
