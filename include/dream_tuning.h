@@ -7,6 +7,7 @@
 #ifndef DREAM_TUNING_H
 #define DREAM_TUNING_H
 
+#include <stddef.h>
 #include <stdint.h>
 
 #ifdef __cplusplus
@@ -20,6 +21,12 @@ extern "C" {
  * it again after changing either, and change neither while another thread is inside an attention call. */
 void dream_set_kv_splits(int32_t n_splits);
 void dream_set_q_tiles(int32_t q_tiles);
+
+/* Host-only: the names of all bf16 attention kernel variants the launch plan can choose, separated by ';', in the
+ * spelling dream_attn_plan_describe uses ("attn_wave_kernel<128,8,2,1>": head_dim, waves, column slices, query tiles
+ * per workgroup; "attn_bf16_kernel<128,1,1,2>": head_dim, query tiles per wave, key tiles per step, steps in flight).
+ * The tests use it to make sure every variant has a parity case.  0, or -1 if buf is too small. */
+int dream_attn_variants(char *buf, size_t buf_bytes);
 
 #ifdef __cplusplus
 }

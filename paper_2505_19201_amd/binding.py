@@ -21,7 +21,7 @@ EXPORTED_SYMBOLS = (
     "dream_init", "dream_tree_verify_attn_workspace", "dream_tree_verify_attn",
     "dream_draft_xattn_workspace", "dream_draft_xattn", "dream_visual_compress_workspace",
     "dream_visual_compress", "dream_accept_path_workspace", "dream_accept_path",
-    "dream_tree_validate_host", "dream_last_error", "dream_set_kv_splits", "dream_set_q_tiles",
+    "dream_tree_validate_host", "dream_last_error", "dream_set_kv_splits", "dream_set_q_tiles", "dream_attn_variants",
     "dream_attn_plan_describe", "dream_stream_read", "dream_kv_commit",
     "dream_tree_expand_workspace", "dream_tree_expand_level", "dream_tree_finalize",
     "dream_attention_entropy_workspace", "dream_attention_entropy", "dream_spec_accept_workspace", "dream_spec_accept",
@@ -109,6 +109,12 @@ def dream_stream_read(src: torch.Tensor, nbytes: int, sink: torch.Tensor, offset
     if offset_bytes < 0 or offset_bytes + nbytes > src.numel() * src.element_size():
         raise ValueError("range outside the source tensor")
     _check(load().dream_stream_read(C.c_void_p(src.data_ptr() + offset_bytes), C.c_size_t(nbytes), _dev(sink), _stream(stream)))
+
+
+def dream_attn_variants() -> list:
+    buf = C.create_string_buffer(4096)
+    _check(load().dream_attn_variants(buf, C.c_size_t(4096)))
+    return buf.value.decode().split(";")
 
 
 def dream_attn_plan_describe(desc: "AttnDesc", n_q: int, max_kv_len: int) -> str:

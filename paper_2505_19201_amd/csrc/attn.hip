@@ -28,6 +28,7 @@
 // fp32 path (attn_f32_kernel): plain vector-ALU kernel, one workgroup per (query row, head,
 // sequence), used for float32 tensors (the small correctness configuration).
 #include "common.h"
+#include "dream_tuning.h"
 #include <atomic>
 #include <math.h>
 
@@ -1007,45 +1008,55 @@ int launch_wave(const AttnArgs &a, const Plan &p, hipStream_t st)
     return check_launch("attn_wave_kernel");
 }
 
-template <int D>
-int launch_wave_d(const AttnArgs &a, const Plan &p, hipStream_t st)
+// Every bf16 kernel variant the launch plan can choose, in one table: the plan names a variant by
+// (kernel family, head_dim, three template arguments); the table gives its launcher and the routine that raises
+// its dynamic-LDS limit.  The launch, dream_init, dream_attn_plan_describe and dream_attn_variants all read it.
+enum { FAMILY_TILE = 0, FAMILY_WAVE = 1 };
+struct Variant {
+    int family, d, p1, p2, p3;   // tile: (QG, KT, PFD); wave: (NW, DS, QT)
+    int (*launch)(const AttnArgs &, const Plan &, hipStream_t);
+    int (*ensure)();
+};
+#define TILE_VARIANT(D, QG, KT, PFD) {FAMILY_TILE, D, QG, KT, PFD, &launch_bf16<D, QG, KT, PFD>, &ensure_bf16_lds<D, QG, KT, PFD>}
+#define WAVE_VARIANT(D, NW, DS, QT) {FAMILY_WAVE, D, NW, DS, QT, &launch_wave<D, NW, DS, QT>, &ensure_wave_lds<D, NW, DS, QT>}
+const Variant VARIANTS[] = {
+    // shared-tile kernel, one query tile per wave: a short key range in one step (2-4 tiles), or streamed
+    TILE_VARIANT(64, 1, 2, 1), TILE_VARIANT(64, 1, 3, 1), TILE_VARIANT(64, 1, 4, 1), TILE_VARIANT(64, 1, 2, 2),
+    TILE_VARIANT(128, 1, 2, 1), TILE_VARIANT(128, 1, 3, 1), TILE_VARIANT(128, 1, 4, 1), TILE_VARIANT(128, 1, 1, 2),
+    TILE_VARIANT(256, 1, 1, 2),
+    // several query tiles per wave
+    TILE_VARIANT(64, 2, 1, 2), TILE_VARIANT(64, 4, 1, 2), TILE_VARIANT(128, 2, 1, 2), TILE_VARIANT(128, 4, 1, 1), TILE_VARIANT(256, 2, 1, 1),
+    // single-launch wave kernel: (waves, column slices, query tiles per workgroup); split output columns always come
+    // with 8 waves at head_dim <= 128
+    WAVE_VARIANT(64, 8, 1, 1), WAVE_VARIANT(64, 8, 2, 1), WAVE_VARIANT(64, 4, 1, 1),
+    WAVE_VARIANT(64, 8, 1, 2), WAVE_VARIANT(64, 4, 1, 2),
+    WAVE_VARIANT(128, 8, 1, 1), WAVE_VARIANT(128, 8, 2, 1), WAVE_VARIANT(128, 8, 4, 1), WAVE_VARIANT(128, 4, 1, 1),
+    WAVE_VARIANT(128, 8, 1, 2), WAVE_VARIANT(128, 4, 1, 2),
+    WAVE_VARIANT(256, 4, 1, 1), WAVE_VARIANT(256, 4, 2, 1), WAVE_VARIANT(256, 4, 4, 1),
+};
+#undef TILE_VARIANT
+#undef WAVE_VARIANT
+constexpr int N_VARIANTS = sizeof(VARIANTS) / sizeof(VARIANTS[0]);
+
+// the variant a plan asks for, or nullptr
+const Variant *find_variant(const dream_attn_desc *d, const Plan &p)
 {
-    if constexpr (D <= 128) {
-        if (p.wave_qt == 2)   // (only with unsplit output columns)
-            return p.wave_nw == 8 ? launch_wave<D, 8, 1, 2>(a, p, st) : launch_wave<D, 4, 1, 2>(a, p, st);
+    const int family = p.wave_mode ? FAMILY_WAVE : FAMILY_TILE;
+    const int p1 = p.wave_mode ? p.wave_nw : p.qg, p2 = p.wave_mode ? p.wave_ds : p.kt, p3 = p.wave_mode ? p.wave_qt : p.pfd;
+    for (int i = 0; i < N_VARIANTS; i++) {
+        const Variant &v = VARIANTS[i];
+        if (v.family == family && v.d == d->head_dim && v.p1 == p1 && v.p2 == p2 && v.p3 == p3)
+            return &v;
     }
-    if constexpr (D <= 128) {
-        if (p.wave_nw == 8) {
-            if constexpr (D >= 128) {
-                if (p.wave_ds == 4)
-                    return launch_wave<D, 8, 4>(a, p, st);
-            }
-            return p.wave_ds == 2 ? launch_wave<D, 8, 2>(a, p, st) : launch_wave<D, 8, 1>(a, p, st);
-        }
-    }
-    if constexpr (D >= 128) {
-        if (p.wave_ds == 4)
-            return launch_wave<D, 4, 4>(a, p, st);
-    }
-    return p.wave_ds == 2 ? launch_wave<D, 4, 2>(a, p, st) : launch_wave<D, 4, 1>(a, p, st);
+    return nullptr;
 }
 
-// one 16-row query tile per wave: the plan picks (tiles per step, steps in flight)
-template <int D>
-int launch_bf16_q1(const AttnArgs &a, const Plan &p, hipStream_t st)
+void variant_name(const Variant &v, char *buf, size_t n)
 {
-    if constexpr (D <= 128) {
-        if (p.pfd == 1) {
-            switch (p.kt) {
-            case 2:  return launch_bf16<D, 1, 2, 1>(a, p, st);
-            case 3:  return launch_bf16<D, 1, 3, 1>(a, p, st);
-            default: return launch_bf16<D, 1, 4, 1>(a, p, st);
-            }
-        }
-    }
-    if constexpr (D == 64)
-        return launch_bf16<D, 1, 2, 2>(a, p, st);
-    return launch_bf16<D, 1, 1, 2>(a, p, st);
+    if (v.family == FAMILY_WAVE)
+        snprintf(buf, n, "attn_wave_kernel<%d,%d,%d,%d>", v.d, v.p1, v.p2, v.p3);
+    else
+        snprintf(buf, n, "attn_bf16_kernel<%d,%d,%d,%d>", v.d, v.p1, v.p2, v.p3);
 }
 
 int run_attention(const char *who, const dream_attn_desc *d, const void *q, const void *k, const void *v,
@@ -1092,24 +1103,11 @@ int run_attention(const char *who, const dream_attn_desc *d, const void *q, cons
         return check_launch("attn_f32_kernel");
     }
 
-    if (p.wave_mode) {
-        switch (d->head_dim) {
-        case 64:  return launch_wave_d<64>(a, p, st);
-        case 128: return launch_wave_d<128>(a, p, st);
-        default:  return launch_wave_d<256>(a, p, st);
-        }
-    }
-    switch (d->head_dim * 10 + p.qg) {
-    case 641:  return launch_bf16_q1<64>(a, p, st);
-    case 642:  return launch_bf16<64, 2, 1, 2>(a, p, st);
-    case 644:  return launch_bf16<64, 4, 1, 2>(a, p, st);
-    case 1281: return launch_bf16_q1<128>(a, p, st);
-    case 1282: return launch_bf16<128, 2, 1, 2>(a, p, st);
-    case 1284: return launch_bf16<128, 4, 1, 1>(a, p, st);
-    case 2561: return launch_bf16_q1<256>(a, p, st);
-    case 2562: return launch_bf16<256, 2, 1, 1>(a, p, st);
-    default:   return fail(DREAM_ERR_UNSUPPORTED, "%s: no kernel for head_dim %d with %d query tiles per wave", who, d->head_dim, p.qg);
-    }
+    const Variant *variant = find_variant(d, p);
+    if (!variant)
+        return fail(DREAM_ERR_UNSUPPORTED, "%s: no kernel variant for head_dim %d with launch parameters (%d, %d, %d)", who, d->head_dim,
+                    p.wave_mode ? p.wave_nw : p.qg, p.wave_mode ? p.wave_ds : p.kt, p.wave_mode ? p.wave_qt : p.pfd);
+    return variant->launch(a, p, st);
 }
 
 size_t workspace_for(const dream_attn_desc *d, int n_q, int64_t max_kv_len)
@@ -1122,43 +1120,16 @@ size_t workspace_for(const dream_attn_desc *d, int n_q, int64_t max_kv_len)
     return p.total;
 }
 
-template <int D>
-int ensure_all_for_head_dim()
-{
-    int rc = DREAM_OK;
-    auto acc = [&](int r) { if (r && !rc) rc = r; };
-    if constexpr (D <= 128) {
-        acc(ensure_bf16_lds<D, 1, 2, 1>()); acc(ensure_bf16_lds<D, 1, 3, 1>()); acc(ensure_bf16_lds<D, 1, 4, 1>());
-        acc(ensure_bf16_lds<D, 2, 1, 2>());
-        acc(ensure_wave_lds<D, 8, 1, 2>()); acc(ensure_wave_lds<D, 4, 1, 2>());
-        acc(ensure_wave_lds<D, 8, 1>()); acc(ensure_wave_lds<D, 8, 2>());
-    }
-    if constexpr (D == 64) {
-        acc(ensure_bf16_lds<D, 1, 2, 2>()); acc(ensure_bf16_lds<D, 4, 1, 2>());
-    } else {
-        acc(ensure_bf16_lds<D, 1, 1, 2>());
-    }
-    if constexpr (D == 128) {
-        acc(ensure_bf16_lds<D, 4, 1, 1>()); acc(ensure_wave_lds<D, 8, 4>());
-    }
-    if constexpr (D == 256)
-        acc(ensure_bf16_lds<D, 2, 1, 1>());
-    if constexpr (D >= 128)
-        acc(ensure_wave_lds<D, 4, 4>());
-    acc(ensure_wave_lds<D, 4, 1>()); acc(ensure_wave_lds<D, 4, 2>());
-    return rc;
-}
-
 }  // namespace
 
 namespace dream {
 // every attention kernel variant the launch plan can choose (part of dream_init)
 int attn_init()
 {
-    int rc = ensure_all_for_head_dim<64>();
-    if (!rc) rc = ensure_all_for_head_dim<128>();
-    if (!rc) rc = ensure_all_for_head_dim<256>();
-    return rc;
+    for (int i = 0; i < N_VARIANTS; i++)
+        if (int rc = VARIANTS[i].ensure())
+            return rc;
+    return DREAM_OK;
 }
 }  // namespace dream
 
@@ -1176,14 +1147,38 @@ int dream_attn_plan_describe(const dream_attn_desc *desc, int32_t n_q, int64_t m
         return fail(DREAM_ERR_INVALID_ARG, "%s: need n_q >= 1 and 1 <= max_kv_len <= s_max", who);
     Plan p;
     make_plan(desc, n_q, max_kv_len, &p);
-    if (desc->dtype == DREAM_F32)
+    if (desc->dtype == DREAM_F32) {
         snprintf(buf, buf_bytes, "attn_f32_kernel workgroups=%lld", (long long)desc->batch * desc->n_q_heads * n_q);
-    else if (p.wave_mode)
-        snprintf(buf, buf_bytes, "attn_wave_kernel<%d,%d,%d%s> workgroups=%d splits=1 merge_launch=0", desc->head_dim, p.wave_nw,
-                 p.wave_ds, p.wave_qt == 2 ? ",2" : "", ceil_div(p.n_qg, p.wave_qt) * p.wave_ds * desc->n_kv_heads * desc->batch);
+        return DREAM_OK;
+    }
+    const Variant *v = find_variant(desc, p);
+    if (!v)
+        return fail(DREAM_ERR_UNSUPPORTED, "%s: the plan names a kernel variant that is not built", who);
+    char name[64];
+    variant_name(*v, name, sizeof name);
+    if (p.wave_mode)
+        snprintf(buf, buf_bytes, "%s workgroups=%d splits=1 merge_launch=0", name,
+                 ceil_div(p.n_qg, p.wave_qt) * p.wave_ds * desc->n_kv_heads * desc->batch);
     else
-        snprintf(buf, buf_bytes, "attn_bf16_kernel<%d,%d,%d,%d> workgroups=%d splits=%d merge_launch=%d", desc->head_dim, p.qg, p.kt,
-                 p.pfd, p.n_groups * p.n_splits, p.n_splits, p.n_splits > 1 ? 1 : 0);
+        snprintf(buf, buf_bytes, "%s workgroups=%d splits=%d merge_launch=%d", name, p.n_groups * p.n_splits, p.n_splits,
+                 p.n_splits > 1 ? 1 : 0);
+    return DREAM_OK;
+}
+
+int dream_attn_variants(char *buf, size_t buf_bytes)
+{
+    if (!buf || buf_bytes == 0)
+        return fail(DREAM_ERR_INVALID_ARG, "dream_attn_variants: no buffer");
+    size_t used = 0;
+    buf[0] = 0;
+    for (int i = 0; i < N_VARIANTS; i++) {
+        char name[64];
+        variant_name(VARIANTS[i], name, sizeof name);
+        const int n = snprintf(buf + used, buf_bytes - used, "%s%s", i ? ";" : "", name);
+        if (n < 0 || (size_t)n >= buf_bytes - used)
+            return fail(DREAM_ERR_INVALID_ARG, "dream_attn_variants: buffer of %zu bytes is too small", buf_bytes);
+        used += (size_t)n;
+    }
     return DREAM_OK;
 }
 

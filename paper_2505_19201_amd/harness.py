@@ -36,6 +36,16 @@ class DeviceAttn:
         self.max_kv = int(x.prefix_len.max()) + self.n_tree
 
 
+def verify_plan(x: di.AttnInputs) -> str:
+    """The launch plan run_verify(x) will get (host-only)."""
+    return dream.dream_attn_plan_describe(desc_for(x), x.parent.shape[1], int(x.prefix_len.max()) + x.parent.shape[1])
+
+
+def xattn_plan(x: di.AttnInputs, n_q: int) -> str:
+    """The launch plan run_xattn(x, rows with n_q columns, ...) will get (host-only)."""
+    return dream.dream_attn_plan_describe(desc_for(x), n_q, int(x.prefix_len.max()) + x.parent.shape[1])
+
+
 def run_verify(x: di.AttnInputs, tree_mask=None, scale: float = 0.0, want_lse: bool = True, dev: DeviceAttn = None):
     dev = dev or DeviceAttn(x)
     desc = desc_for(x, scale)

@@ -107,13 +107,13 @@ def test_launch_plans_of_the_paper_shapes(lib):
     def plan(B, hq, hkv, d, n_q, s):
         return dream.dream_attn_plan_describe(dream.attn_desc(B, hq, hkv, d, dream.BF16, s), n_q, s)
     llava = plan(1, 32, 32, 128, 60, 764)
-    assert llava.startswith("attn_wave_kernel<128,8,2>") and "workgroups=256" in llava and "merge_launch=0" in llava
+    assert llava.startswith("attn_wave_kernel<128,8,2,1>") and "workgroups=256" in llava and "merge_launch=0" in llava
     level = plan(1, 32, 32, 128, 16, 764)            # one drafted tree level: a single query tile per head
-    assert level.startswith("attn_wave_kernel<128,8,4>") and "workgroups=128" in level
+    assert level.startswith("attn_wave_kernel<128,8,4,1>") and "workgroups=128" in level
     pixtral = plan(1, 32, 8, 128, 60, 1340)
-    assert pixtral.startswith("attn_wave_kernel<128,8,2>") and "workgroups=256" in pixtral and "merge_launch=0" in pixtral
+    assert pixtral.startswith("attn_wave_kernel<128,8,2,1>") and "workgroups=256" in pixtral and "merge_launch=0" in pixtral
     gemma3 = plan(1, 16, 8, 256, 60, 1340)
-    assert gemma3.startswith("attn_wave_kernel<256,4,4>") and "workgroups=256" in gemma3
+    assert gemma3.startswith("attn_wave_kernel<256,4,4,1>") and "workgroups=256" in gemma3
     long_cache = plan(1, 32, 8, 128, 60, 4156)        # more than 64 key tiles
     assert long_cache.startswith("attn_bf16_kernel<128,1,") and "splits=8" in long_cache and "merge_launch=1" in long_cache
     batch = plan(32, 32, 32, 64, 60, 1660)
@@ -122,6 +122,37 @@ def test_launch_plans_of_the_paper_shapes(lib):
     assert f32.startswith("attn_f32_kernel")
     with pytest.raises(dream.DreamError):
         dream.dream_attn_plan_describe(dream.attn_desc(1, 32, 32, 96, dream.BF16, 764), 60, 764)
+
+
+def test_every_attention_kernel_variant_has_a_parity_case(lib):
+    """The GPU suite runs tests/attn_cases.VARIANT_CASES all elements against the oracle; here, without a GPU: the
+    list names every variant the library can dispatch to, and each case's shape really plans its variant."""
+    import dream_inputs as di
+    from tests.attn_cases import FULL_VERIFY_PLANS, FULL_XATTN_PLANS, VARIANT_CASES, variant_config, variant_prefix_lens
+    built = dream.dream_attn_variants()
+    assert len(built) == len(set(built))
+    assert sorted(c.variant for c in VARIANT_CASES) == sorted(built)
+    for case in VARIANT_CASES:
+        cfg = variant_config(case)
+        pl = variant_prefix_lens(case)
+        assert max(pl) == pl[0] == case.kv_len - case.n_tree and min(pl) >= 0
+        dream.dream_set_kv_splits(case.splits)
+        dream.dream_set_q_tiles(case.q_tiles)
+        try:
+            desc = dream.attn_desc(cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, dream.BF16, case.kv_len + 5)
+            plan = dream.dream_attn_plan_describe(desc, case.n_tree, case.kv_len)
+        finally:
+            dream.dream_set_kv_splits(0)
+            dream.dream_set_q_tiles(0)
+        assert plan.startswith(case.variant + " "), (case, plan)
+    for name, want in FULL_VERIFY_PLANS.items():
+        cfg = di.CONFIGS[name]
+        S = cfg.prefix + cfg.n_tree
+        desc = dream.attn_desc(cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, dream.BF16, S + 5)
+        assert dream.dream_attn_plan_describe(desc, cfg.n_tree, S) == want, name
+        for n_q, want_x in zip((1, 10), FULL_XATTN_PLANS[name]):
+            assert dream.dream_attn_plan_describe(desc, n_q, S) == want_x, (name, n_q)
+        assert want.split(" ")[0] in built
 
 
 def test_kv_commit_argument_errors(lib):
@@ -248,4 +279,4 @@ def test_header_compiles_as_c_and_host_calls_work(lib, tmp_path):
                     os.path.join(root, "tests", "c", "abi_check.c"), "-o", exe, "-L", libdir, "-ldream", "-Wl,-rpath," + libdir],
                    check=True, capture_output=True, text=True)
     out = subprocess.run([exe], check=True, capture_output=True, text=True).stdout
-    assert out.startswith("attn_wave_kernel<128,8,2>")
+    assert out.startswith("attn_wave_kernel<128,8,2,1>")

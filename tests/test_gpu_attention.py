@@ -5,6 +5,7 @@ import pytest
 
 import dream_inputs as di
 import oracle
+from tests.attn_cases import FULL_VERIFY_PLANS, FULL_XATTN_PLANS, VARIANT_CASES, variant_config, variant_prefix_lens
 
 pytestmark = pytest.mark.gpu
 
@@ -108,39 +109,46 @@ def test_outputs_are_reproducible_bit_for_bit(gu):
     assert np.array_equal(a, b) and np.array_equal(la, lb)
 
 
-FULL = ["llava", "pixtral", "gemma3", "smolvlm_b1", "smolvlm_b8"]
+@pytest.mark.parametrize("case", VARIANT_CASES, ids=[c.variant for c in VARIANT_CASES])
+def test_every_kernel_variant_all_elements(gu, case):
+    """One case per bf16 kernel variant the launch plan can choose (tests/test_abi.py checks the list is complete):
+    the plan must name that variant, and every output element and log-sum-exp must match the oracle."""
+    import paper_2505_19201_amd as dream
+    cfg = variant_config(case)
+    x = di.verify_inputs(cfg, prefix_len=variant_prefix_lens(case))
+    dream.dream_set_kv_splits(case.splits)
+    dream.dream_set_q_tiles(case.q_tiles)
+    try:
+        assert gu.verify_plan(x).startswith(case.variant + " "), gu.verify_plan(x)
+        got, lse = gu.run_verify(x)
+    finally:
+        dream.dream_set_kv_splits(0)
+        dream.dream_set_q_tiles(0)
+    want, want_lse = oracle.tree_attn(x.q, x.k, x.v, "bf16", x.prefix_len, x.parent, True)
+    assert np.isfinite(got).all()
+    assert np.abs(got - want).max() <= TOL["bf16"], np.abs(got - want).max()
+    assert np.abs(lse - want_lse).max() <= 2e-3
 
 
-def _sample_rows(cfg, n, seed):
-    g = di.rng(seed, 900)
-    return [(int(g.integers(0, cfg.batch)), int(g.integers(0, cfg.n_q_heads)), int(g.integers(0, cfg.n_tree)))
-            for _ in range(n)]
+FULL = ["llava", "pixtral", "gemma3", "smolvlm_b1", "smolvlm_b8", "smolvlm_b32"]
 
 
 @pytest.mark.parametrize("name", FULL)
-def test_full_size_verify_sampled_rows(gu, name):
-    """Full measurement shape, default launch configuration (the one bench.py times): 160 sampled
-    output rows against the oracle, plus finiteness of everything."""
+def test_full_size_verify_all_elements(gu, name):
+    """Full measurement shape in the launch configuration bench.py times (asserted by its plan string): every output
+    element and every log-sum-exp against the oracle (16 host threads)."""
     cfg = di.CONFIGS[name]
     x = di.verify_inputs(cfg)
+    assert gu.verify_plan(x) == FULL_VERIFY_PLANS[name]
     got, lse = gu.run_verify(x)
+    oracle.set_threads(16)
+    try:
+        want, want_lse = oracle.tree_attn(x.q, x.k, x.v, cfg.dtype, x.prefix_len, x.parent, True)
+    finally:
+        oracle.set_threads(1)
     assert np.isfinite(got).all() and np.isfinite(lse).all()
-    worst = 0.0
-    for (b, h, i) in _sample_rows(cfg, 160, cfg.seed):
-        want, wl = oracle.attn_row(x.q, x.k, x.v, cfg.dtype, x.prefix_len, x.parent, True, b, h, i)
-        worst = max(worst, np.abs(got[b, i, h] - want).max())
-        assert abs(lse[b, h, i] - wl) <= 2e-3
-    assert worst <= TOL["bf16"], worst
-
-
-def test_full_size_smolvlm_b32_sampled_rows(gu):
-    cfg = di.CONFIGS["smolvlm_b32"]
-    x = di.verify_inputs(cfg)
-    got, lse = gu.run_verify(x)
-    assert np.isfinite(got).all()
-    for (b, h, i) in _sample_rows(cfg, 200, cfg.seed):
-        want, wl = oracle.attn_row(x.q, x.k, x.v, cfg.dtype, x.prefix_len, x.parent, True, b, h, i)
-        assert np.abs(got[b, i, h] - want).max() <= TOL["bf16"]
+    assert np.abs(got - want).max() <= TOL["bf16"], np.abs(got - want).max()
+    assert np.abs(lse - want_lse).max() <= 2e-3
 
 
 # ------------------------------------------------------------------------------------------------
@@ -199,21 +207,26 @@ def test_xattn_root_with_empty_prefix_gives_zero_row(gu):
     assert np.abs(got - want).max() <= TOL["bf16"]
 
 
-@pytest.mark.parametrize("name", ["llava", "pixtral", "gemma3", "smolvlm_b8"])
-def test_full_size_xattn_round_sampled(gu, name):
-    """One drafting round at the measurement shape: a call per tree level (1,10,10,10,10,10,9 rows)."""
+@pytest.mark.parametrize("name", FULL)
+def test_full_size_xattn_round_all_elements(gu, name):
+    """One drafting round at the measurement shape: a call per tree level (1,10,10,10,10,10,9 rows), in the launch
+    configuration bench.py times (asserted by the plan strings); every output element against the oracle."""
     cfg = di.CONFIGS[name]
     x = di.xattn_inputs(cfg)
     dev = gu.DeviceAttn(x)
-    g = di.rng(cfg.seed, 901)
-    for lvl in range(cfg.depth + 1):
-        rows = np.stack([di.tree_levels(x.parent[b])[lvl] for b in range(cfg.batch)])
-        got, qsel = gu.run_xattn(x, rows, rows, dev=dev)
-        assert np.isfinite(got).all()
-        for _ in range(24):
-            b, h, r = int(g.integers(0, cfg.batch)), int(g.integers(0, cfg.n_q_heads)), int(g.integers(0, rows.shape[1]))
-            want, _ = oracle.attn_row(qsel, x.k, x.v, cfg.dtype, x.prefix_len, x.parent, False, b, h, r, node=int(rows[b, r]))
-            assert np.abs(got[b, r, h] - want).max() <= TOL["bf16"]
+    root_plan, level_plan = FULL_XATTN_PLANS[name]
+    oracle.set_threads(16)
+    try:
+        for lvl in range(cfg.depth + 1):
+            rows = np.stack([di.tree_levels(x.parent[b])[lvl] for b in range(cfg.batch)])
+            if rows.shape[1] in (1, 10):
+                assert gu.xattn_plan(x, rows.shape[1]) == (root_plan if rows.shape[1] == 1 else level_plan)
+            got, qsel = gu.run_xattn(x, rows, rows, dev=dev)
+            want, _ = oracle.tree_attn(qsel, x.k, x.v, cfg.dtype, x.prefix_len, x.parent, False, q_node=rows)
+            assert np.isfinite(got).all()
+            assert np.abs(got - want).max() <= TOL["bf16"], (lvl, np.abs(got - want).max())
+    finally:
+        oracle.set_threads(1)
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
