@@ -25,11 +25,16 @@ def _softmax(x: np.ndarray) -> np.ndarray:
 
 
 def spec_accept(target_logits_f64: np.ndarray, draft_logits_f64: np.ndarray, token: np.ndarray, parent: np.ndarray,
-                u_accept: np.ndarray, u_bonus: np.ndarray, max_depth: int, inv_temperature: float = 1.0):
+                u_accept: np.ndarray, u_bonus: np.ndarray, max_depth: int, inv_temperature: float = 1.0,
+                flip_nodes=frozenset(), draw_window: float = 0.0):
     """logits [B,T,V] float64, token/parent [B,T], u_accept [B,T], u_bonus [B] ->
     (accept_len [B], accept_path [B,max_depth+1] (-1 padded), bonus_token [B], detail) where detail[b] lists, for
     diagnostics and gap guards, every acceptance test (node, ratio, u) and the final draw (target mass, cumulative
-    sums around the drawn token)."""
+    sums around the drawn token).
+    flip_nodes / draw_window do not belong to the method: they let a test enumerate what a lower-precision
+    implementation may legitimately return when a comparison is too close to call.  The acceptance test of a node in
+    flip_nodes takes the opposite outcome; detail[b]["draw_window_tokens"] lists every token of positive probability
+    whose cumulative interval comes within draw_window (a fraction of the total mass) of the drawn point."""
     B, T, V = target_logits_f64.shape
     alen = np.zeros(B, dtype=np.int32)
     path = np.full((B, max_depth + 1), -1, dtype=np.int32)
@@ -53,7 +58,7 @@ def spec_accept(target_logits_f64: np.ndarray, draft_logits_f64: np.ndarray, tok
                     x = int(token[b, c])
                     ratio = p[x] / q[x] if q[x] > 0 else (np.inf if p[x] > 0 else 0.0)
                     tests.append((c, float(ratio), float(u_accept[b, c])))
-                    if u_accept[b, c] < min(1.0, ratio):
+                    if (u_accept[b, c] < min(1.0, ratio)) != (c in flip_nodes):
                         accepted = c
                         break
                     r = np.maximum(p - q, 0.0)
@@ -75,7 +80,12 @@ def spec_accept(target_logits_f64: np.ndarray, draft_logits_f64: np.ndarray, tok
                 t = int(np.flatnonzero(p > 0)[-1])
             bonus[b] = t
             lo = cdf[t - 1] if t > 0 else 0.0
-            detail.append({"tests": tests, "draw_margin": float(min(target - lo, cdf[t] - target) / cdf[-1]), "draw_mass": float(p[t])})
+            w = draw_window * cdf[-1]
+            first = int(np.searchsorted(cdf, target - w, side="left"))       # first token whose interval ends at or after target - w
+            last = int(np.searchsorted(cdf, target + w, side="right"))       # last token whose interval starts at or before target + w
+            near = [int(x) for x in range(max(first, 0), min(last, V - 1) + 1) if p[x] > 0]
+            detail.append({"tests": tests, "draw_margin": float(min(target - lo, cdf[t] - target) / cdf[-1]), "draw_mass": float(p[t]),
+                           "draw_window_tokens": near})
             break
         alen[b] = depth
     return alen, path, bonus, detail

@@ -148,3 +148,26 @@ def test_full_size_configs(gu, name):
     assert np.array_equal(kept, want_kept)
     assert np.array_equal(kept, oracle.topk_keep(scores, 0, cfg.keep_num, cfg.keep_den))
     assert np.array_equal(gathered, oracle.gather_rows(rows, "bf16", want_kept))
+
+
+def test_full_size_smolvlm_b32(gu):
+    """32 sequences per call, all prefill rows.  Scores of every sequence against the oracle; the kept set is the exact
+    top-k of the library's own float32 scores for every sequence, and equals the oracle's kept set wherever the
+    oracle's boundary gap is safe (decided per sequence on the oracle side; most sequences must qualify)."""
+    cfg = di.CONFIGS["smolvlm_b32"]
+    q, k = _qk(cfg, cfg.seed)
+    oracle.set_threads(min(16, oracle.hw_threads()))
+    try:
+        want = oracle.visual_scores(q, k, cfg.dtype, 0, cfg.n_visual)
+    finally:
+        oracle.set_threads(1)
+    n_keep = oracle.keep_count(cfg.n_visual, cfg.keep_num, cfg.keep_den)
+    safe = np.array([_boundary_gap(want[b:b + 1], n_keep) > GAP for b in range(cfg.batch)])
+    assert safe.sum() >= cfg.batch // 2
+    rows = di.feature_rows(cfg)
+    scores, kept, gathered = gu.run_compress("bf16", q, k, cfg.prefix, 0, cfg.n_visual, cfg.keep_num, cfg.keep_den, gather_src=rows)
+    np.testing.assert_allclose(scores, want, rtol=SCORE_RTOL["bf16"])
+    assert np.array_equal(kept, oracle.topk_keep(scores, 0, cfg.keep_num, cfg.keep_den))
+    want_kept = oracle.topk_keep(want, 0, cfg.keep_num, cfg.keep_den)
+    assert np.array_equal(kept[safe], want_kept[safe])
+    assert np.array_equal(gathered, oracle.gather_rows(rows, "bf16", kept))

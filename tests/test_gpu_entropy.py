@@ -58,7 +58,7 @@ def test_zero_queries_reproduce_log_count(gu):
     np.testing.assert_allclose(row, np.broadcast_to(np.log(np.arange(1, 301)), row.shape), atol=TOL["bf16"])
 
 
-@pytest.mark.parametrize("name", ["llava", "pixtral", "smolvlm_b8"])
+@pytest.mark.parametrize("name", ["llava", "pixtral", "gemma3", "smolvlm_b8"])
 def test_full_size_configs(gu, name):
     cfg = di.CONFIGS[name]
     _check(gu, cfg)

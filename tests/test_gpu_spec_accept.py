@@ -5,7 +5,10 @@ works in float32, so a sequence is compared only when the oracle's own run shows
 float32 error -- decided on the CPU before the GPU result is looked at: |u - min(1, ratio)| > 1e-3 for every
 acceptance test and the draw at least 2e-5 of the mass away from both ends of the drawn token's cumulative interval
 (the float32 cumulative sums are good to about 1e-6 of the mass).
-At least half of the sequences of every case must qualify, and all that qualify must match bit for bit."""
+At least half of the sequences of every case must qualify, and all that qualify must match bit for bit.
+A sequence that does not qualify is not waved through: its result must be one of the outcomes the oracle produces when
+every too-close comparison on the way is resolved either way (the undecided acceptance tests flipped, the draw landing
+on any token of positive probability whose cumulative interval is that close to the drawn point), enumerated on the CPU."""
 import numpy as np
 import pytest
 
@@ -23,9 +26,33 @@ def gu():
     return gpu_util
 
 
+RATIO_EPS, DRAW_EPS = 1e-3, 2e-5
+
+
 def _clear(detail):
-    ok = all(abs(u - min(1.0, r)) > 1e-3 for _, r, u in detail["tests"])
-    return ok and detail["draw_margin"] > 2e-5
+    ok = all(abs(u - min(1.0, r)) > RATIO_EPS for _, r, u in detail["tests"])
+    return ok and detail["draw_margin"] > DRAW_EPS
+
+
+def _legitimate_outcomes(tl64, dl64, token, parent, ua, ub, depth, inv_temperature, limit=64):
+    """Every (accept_len, path, bonus) one sequence may legitimately yield: the oracle is re-run with each acceptance
+    test that is within RATIO_EPS of its threshold taken either way (a flip changes the walk, so new close calls
+    may appear: depth-first over them); the bonus may be any token of positive probability whose cumulative interval
+    comes within DRAW_EPS of the drawn point."""
+    outcomes, stack, seen = set(), [frozenset()], set()
+    while stack and len(seen) < limit:
+        flips = stack.pop()
+        if flips in seen:
+            continue
+        seen.add(flips)
+        alen, path, bonus, detail = oracle.spec_accept(tl64, dl64, token, parent, ua, ub, depth, inv_temperature=inv_temperature,
+                                                       flip_nodes=flips, draw_window=DRAW_EPS)
+        for node, ratio, u in detail[0]["tests"]:
+            if abs(u - min(1.0, ratio)) <= RATIO_EPS and node not in flips:
+                stack.append(flips | {node})
+        for t in set(detail[0]["draw_window_tokens"]) | {int(bonus[0])}:
+            outcomes.add((int(alen[0]), tuple(path[0].tolist()), t))
+    return outcomes
 
 
 def _draft_children(parent, dl_f64, g):
@@ -44,7 +71,7 @@ def _draft_children(parent, dl_f64, g):
     return token
 
 
-def _case(gu, B, T, depth, V, dtype, seed, spread=2.0, noise=0.7, temperature=1.0, min_clear=0.5):
+def _case(gu, B, T, depth, V, dtype, seed, spread=2.0, noise=0.7, temperature=1.0, min_clear=0.5, min_compared=0):
     g = di.rng(seed, 700)
     parent = np.stack([di.random_tree(T, depth, seed, b) for b in range(B)]) if T > 1 else np.full((B, 1), -1, dtype=np.int32)
     t32 = di.normal((B, T, V), "f32", seed, di.STREAM_LOGITS) * np.float32(spread)
@@ -58,12 +85,16 @@ def _case(gu, B, T, depth, V, dtype, seed, spread=2.0, noise=0.7, temperature=1.
     want_len, want_path, want_bonus, detail = oracle.spec_accept(tl64, dl64, token, parent, ua.astype(np.float64), ub.astype(np.float64),
                                                                 depth, inv_temperature=1.0 / temperature)
     clear = np.array([_clear(d) for d in detail])
-    assert clear.mean() >= min_clear, clear.mean()
+    assert clear.mean() >= min_clear and clear.sum() >= min_compared, (clear.mean(), clear.sum())
     alen, path, bonus = gu.run_spec_accept(tl, dl, dtype, token, parent, ua, ub, depth, temperature)
     assert (alen >= 0).all() and (alen <= depth).all() and (bonus >= 0).all() and (bonus < V).all()
     assert np.array_equal(alen[clear], want_len[clear]), (alen[clear], want_len[clear])
     assert np.array_equal(path[clear], want_path[clear])
     assert np.array_equal(bonus[clear], want_bonus[clear])
+    for b in np.flatnonzero(~clear):      # too close to call in float32: any resolution of the close calls is right, nothing else
+        legit = _legitimate_outcomes(tl64[b:b + 1], dl64[b:b + 1], token[b:b + 1], parent[b:b + 1], ua[b:b + 1].astype(np.float64),
+                                     ub[b:b + 1].astype(np.float64), depth, 1.0 / temperature)
+        assert (int(alen[b]), tuple(path[b].tolist()), int(bonus[b])) in legit, (b, alen[b], path[b], bonus[b], legit)
     _case.last = (parent, detail, clear)
     return alen, clear
 
@@ -117,7 +148,9 @@ def test_trees_of_the_paper_shape(gu, dtype, temperature):
 @pytest.mark.parametrize("name", ["llava", "gemma3"])
 def test_full_size_vocabularies(gu, name):
     cfg = di.CONFIGS[name]
-    _case(gu, 4, cfg.n_tree, cfg.depth, cfg.vocab, "bf16", cfg.seed, min_clear=0.25)
+    # (at 262144 tokens an interval of the cumulative sum is a few 1e-6 of the mass wide, so few draws are DRAW_EPS clear
+    # of both ends: the batch is sized so that at least 8 sequences are compared bit for bit all the same)
+    _case(gu, 12 if cfg.vocab <= 65536 else 36, cfg.n_tree, cfg.depth, cfg.vocab, "bf16", cfg.seed, min_clear=0.2, min_compared=8)
 
 
 def test_largest_tree(gu):

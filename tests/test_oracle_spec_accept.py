@@ -34,6 +34,35 @@ def test_worked_example():
         assert bonus[0] == want
 
 
+def test_forced_resolutions_of_close_calls_on_the_worked_example():
+    """flip_nodes and draw_window (used by the GPU test to enumerate what float32 may legitimately decide when a
+    comparison is too close to call) do what they say on the hand-worked case, and nothing when not asked."""
+    p, q = np.array([0.5, 0.3, 0.2]), np.array([0.2, 0.5, 0.3])
+    tl = np.log(p)[None, None].repeat(3, axis=1)
+    dl = np.log(q)[None, None].repeat(3, axis=1)
+    parent = np.array([[-1, 0, 0]], dtype=np.int32)
+    tok, ua, ub = np.array([[9, 1, 0]]), np.array([[0, 0.5, 0.9]]), np.array([0.3])
+    base = oracle.spec_accept(tl, dl, tok, parent, ua, ub, 6)
+    same = oracle.spec_accept(tl, dl, tok, parent, ua, ub, 6, flip_nodes=frozenset(), draw_window=0.0)
+    assert all(np.array_equal(a, b) for a, b in zip(base[:3], same[:3]))
+    # u = .5 < .6 accepts child 1; flipped, it is rejected and child 2 (ratio 2.5) is accepted instead
+    alen, path, _, d = oracle.spec_accept(tl, dl, tok, parent, ua, ub, 6, flip_nodes=frozenset({1}))
+    assert alen[0] == 1 and path[0, :2].tolist() == [0, 2] and [round(t[1], 12) for t in d[0]["tests"]] == [0.6, 2.5]
+    # flipping both leaves no accepted child: the draw comes from the residual (1,0,0)
+    alen, path, bonus, _ = oracle.spec_accept(tl, dl, tok, parent, ua, ub, 6, flip_nodes=frozenset({1, 2}))
+    assert alen[0] == 0 and bonus[0] == 0
+    # a lone root: u = .51 draws token 1 of (.5,.3,.2), 0.01 above the end of token 0's interval and 0.29 below token 2's
+    one = (tl[:, :1], dl[:, :1], np.array([[9]]), np.array([[-1]], dtype=np.int32), np.array([[0.0]]), np.array([0.51]), 6)
+    for window, want in ((0.0, [1]), (0.005, [1]), (0.02, [0, 1]), (0.3, [0, 1, 2])):
+        _, _, bonus, d = oracle.spec_accept(*one, draw_window=window)
+        assert bonus[0] == 1 and d[0]["draw_window_tokens"] == want
+    # tokens of zero probability are never candidates: p = (.5, 0, .5), u = .5 sits on the boundary
+    tz = np.log(np.array([0.5, 1e-300, 0.5]))[None, None]
+    tz[0, 0, 1] = -np.inf
+    _, _, bonus, d = oracle.spec_accept(tz, tz, one[2], one[3], one[4], np.array([0.5]), 6, draw_window=0.01)
+    assert bonus[0] == 2 and d[0]["draw_window_tokens"] == [0, 2]
+
+
 @pytest.mark.parametrize("m", [1, 2, 3])
 def test_the_emitted_token_follows_the_target_distribution(m):
     """One level, m children drawn without replacement from the draft distribution: whatever the draft, the first
