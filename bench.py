@@ -1,12 +1,13 @@
 #!/usr/bin/env python3
 """Benchmark of the DREAM decode-step hot path on one MI355X.
 
-One step = one pass over the whole hot path on one batch of synthetic input:
+One step = one decode round on one batch of synthetic input:
   n_layers x dream_tree_verify_attn (one call per target layer, each over its own K/V cache)
   + 6 x dream_draft_xattn (one call per drafted tree level)
-  + dream_visual_compress (scores over all prefill rows, top-k keep, row gather)
   + dream_accept_path.
-All inputs are resident in HBM before the timed region.  The timed step is ONE HIP graph holding the four
+dream_visual_compress (scores over all prefill rows, top-k keep, row gather) runs once per request, after the
+prefill, not once per step: it is timed separately (`per_request_us`) and is not part of `value`.
+All inputs are resident in HBM before the timed region.  The timed step is ONE HIP graph holding the three
 phases (no memset nodes), replayed K times.  After the timed region the same work runs once more as one
 graph per phase with HIP events between the graph launches, on the launching stream: that gives the phase
 breakdown and the time of the verification block, from which the roofline figure of the dominant kernel
@@ -41,15 +42,23 @@ def verify_bytes_per_launch(cfg) -> int:
 
 
 def read_traffic(name: str):
-    """HBM traffic per launch measured with rocprofv3 --pmc (committed summary), or None."""
-    path = os.path.join(ROOT, "profiles", f"attn_verify_{name}_traffic.txt")
+    """HBM traffic per launch of the verification kernel, from the committed summary of the two rocprofv3 --pmc runs
+    (FETCH_SIZE, WRITE_SIZE; counters cannot be read from inside this process).  Returns (bytes or None, where the
+    figure comes from: file, the kernel it was measured on and the date of that measurement)."""
+    rel = os.path.join("profiles", f"attn_verify_{name}_traffic.txt")
+    traffic, kernel, date = None, "?", "?"
     try:
-        for line in open(path):
-            if line.startswith("traffic_bytes_per_launch:"):
-                return float(line.split(":")[1])
+        for line in open(os.path.join(ROOT, rel)):
+            key, _, val = line.partition(":")
+            if key == "traffic_bytes_per_launch":
+                traffic = float(val)
+            elif key == "kernel":
+                kernel = val.strip()
+            elif key == "measured":
+                date = val.strip()
     except OSError:
-        pass
-    return None
+        return None, "no rocprofv3 summary committed for this configuration"
+    return traffic, f"{rel} (rocprofv3 --pmc FETCH_SIZE/WRITE_SIZE, kernel {kernel}, measured {date})"
 
 
 def main() -> int:
@@ -61,6 +70,7 @@ def main() -> int:
     ap.add_argument("--layers", type=int, default=0, help="target layers per step (0 = the configuration's)")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--no-configs", action="store_true", help="skip the short runs of the other configurations")
     ap.add_argument("--splits", type=int, default=0, help="force the number of key-range splits (0 = automatic)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run plain device copies of a known size (reference for scaling rocprofv3 byte counters)")
@@ -77,12 +87,37 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     dream.load()
+    torch.cuda.set_device(0)
+    dream.dream_init()
     if args.copy_calibration:
         return copy_calibration(torch)
+    if args.splits:
+        dream.dream_set_kv_splits(args.splits)
     cfg = di.CONFIGS[args.config]
+    out = run_config(torch, dream, di, args, cfg, args.steps, args.warmup, full=True)
+    if not args.no_configs:
+        # the other measurement shapes: a short run each (same step, same graph replay), the figures the report asks for
+        out["configs"] = {}
+        for name in ("llava", "pixtral", "gemma3", "smolvlm_b1", "smolvlm_b8", "smolvlm_b32"):
+            if name == cfg.name:
+                continue
+            torch.cuda.empty_cache()
+            r = run_config(torch, dream, di, args, di.CONFIGS[name], steps=max(5, min(args.steps, 20)), warmup=3, full=False)
+            out["configs"][name] = {"step_latency_us": r["step_latency_us"], "tokens_per_s": r["value"],
+                                    "tokens_per_s_at_paper_tau": r["tokens_per_s_at_paper_tau"], "phase_us": r["phase_us"],
+                                    "per_request_us": r["per_request_us"], "roofline": r["roofline"], "read_ceiling": r["read_ceiling"],
+                                    "workload": r["config"]["workload"]}
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(cfg, args.layers or cfg.n_layers, out["config"]["tokens_per_step"])
+    print(json.dumps(out))
+    return 0
+
+
+def run_config(torch, dream, di, args, cfg, steps, warmup, full):
+    """Allocates one configuration's resident inputs, times `steps` replays of the step graph and the per-phase
+    breakdown, and returns the result line as a dict (full=True adds the legs that are reported once)."""
     L = args.layers or cfg.n_layers
     dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
     B, T, Hq, Hkv, D, P = cfg.batch, cfg.n_tree, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.prefix
     S = P + T
     s_max = S
@@ -101,8 +136,6 @@ def main() -> int:
     vv = [randn(B, Hkv, s_max, D) for _ in range(L)]
     vout = [torch.empty(B, T, Hq, D, dtype=torch.bfloat16, device=dev) for _ in range(L)]
     desc = dream.attn_desc(B, Hq, Hkv, D, dream.BF16, s_max)
-    if args.splits:
-        dream.dream_set_kv_splits(args.splits)
     ws_v = dream.alloc_workspace(dream.dream_tree_verify_attn_workspace(desc, T, S))
 
     levels = [np.stack([di.tree_levels(parents_np[b])[lv] for b in range(B)]) for lv in range(cfg.depth)]
@@ -137,17 +170,21 @@ def main() -> int:
         for i in range(len(levels)):
             dream.dream_draft_xattn(desc, xq[i], xk, xv, prefix_len, T, parent, levels[i].shape[1], xnode[i], S, xout[i], ws_x)
 
-    def phase_compress():
-        dream.dream_visual_compress(desc, pq, None, P, vk[L - 1], P, 0, cfg.n_visual, cfg.keep_num, cfg.keep_den, None,
-                                    scores, kept, rows, P, gathered, cfg.hidden, ws_c)
-
     def phase_accept():
         dream.dream_accept_path(logits, dream.BF16, B, T, cfg.vocab, token, parent, cfg.depth, node_argmax, accept_len,
                                 accept_path, bonus, ws_a)
 
-    phases = [("verify", phase_verify), ("xattn", phase_xattn), ("compress", phase_compress), ("accept", phase_accept)]
-    for _, f in phases:      # eager warm-up: also sets kernel attributes before any capture
+    def per_request_compress():
+        dream.dream_visual_compress(desc, pq, None, P, vk[L - 1], P, 0, cfg.n_visual, cfg.keep_num, cfg.keep_den, None,
+                                    scores, kept, rows, P, gathered, cfg.hidden, ws_c)
+
+    # A step is one decode round: the verification attention of every target layer, the cross-attention of every drafted
+    # level and the acceptance.  The visual-token compression runs once per request (after the prefill), not per step:
+    # it is timed on its own below and is not part of `value`.
+    phases = [("verify", phase_verify), ("xattn", phase_xattn), ("accept", phase_accept)]
+    for _, f in phases:      # eager warm-up before any capture
         f()
+    per_request_compress()
     torch.cuda.synchronize()
 
     stream = torch.cuda.Stream()
@@ -164,7 +201,7 @@ def main() -> int:
             with torch.cuda.graph(g, stream=stream):
                 f()
             runners.append(g.replay)
-        # the timed step is ONE graph holding all four phases; the per-phase graphs above only serve the breakdown
+        # the timed step is ONE graph holding all phases; the per-phase graphs above only serve the breakdown
         step_graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(step_graph, stream=stream):
             for _, f in phases:
@@ -179,64 +216,66 @@ def main() -> int:
         evs[len(runners)].record()
 
     with torch.cuda.stream(stream):
-        for _ in range(args.warmup):
+        for _ in range(warmup):
             whole_step()
         stream.synchronize()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for s in range(args.steps):
+        for s in range(steps):
             whole_step()
         stream.synchronize()
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         # phase breakdown (outside the timed region): the same work as one graph per phase with events between
-        all_evs = [[torch.cuda.Event(enable_timing=True) for _ in range(len(runners) + 1)] for _ in range(args.steps)]
-        for s in range(args.steps):
+        all_evs = [[torch.cuda.Event(enable_timing=True) for _ in range(len(runners) + 1)] for _ in range(steps)]
+        for s in range(steps):
             one_step(all_evs[s])
         stream.synchronize()
         torch.cuda.synchronize()
 
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    phase_ms = [float(np.mean([all_evs[s][i].elapsed_time(all_evs[s][i + 1]) for s in range(args.steps)]))
+    ms_per_step = (t1 - t0) * 1e3 / steps
+    phase_ms = [float(np.mean([all_evs[s][i].elapsed_time(all_evs[s][i + 1]) for s in range(steps)]))
                 for i in range(len(runners))]
     tokens_per_step = int((accept_len + 1).sum().item())
     assert tokens_per_step == B * (PLANT_DEPTH + 1), "accept_path did not return the planted path"
     value = tokens_per_step / (ms_per_step * 1e-3)
+    compress_us = graph_time_us(torch, lambda: [per_request_compress() for _ in range(4)], reps=5) / 4
 
     launch_us = phase_ms[0] * 1e3 / L
     bytes_launch = verify_bytes_per_launch(cfg)
     achieved = bytes_launch / (launch_us * 1e-6) / 1e9
     plan = dream.dream_attn_plan_describe(desc, T, S)
+    traffic, traffic_source = read_traffic(cfg.name)
     roofline = {"bound": "hbm", "kernel": "dream_tree_verify_attn: " + plan, "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": read_traffic(cfg.name), "bytes_per_launch": bytes_launch,
+                "traffic": traffic, "traffic_source": traffic_source, "bytes_per_launch": bytes_launch,
                 "launch_us": round(launch_us, 3), "launches_per_step": L}
 
     out = {
         "metric": "verify+draft step throughput (tokens/s) and latency on 1 MI355X",
-        "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": round(ms_per_step, 5), "step_latency_us": round(ms_per_step * 1e3, 2),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: B={B} Hq={Hq} Hkv={Hkv} D={D} prefix={cfg.n_visual}+{cfg.n_text} tree={T} "
                                f"depth={cfg.depth} layers={L} vocab={cfg.vocab} keep={cfg.keep_num}/{cfg.keep_den}",
+                   "step": f"{L} x dream_tree_verify_attn + {len(levels)} x dream_draft_xattn + dream_accept_path, one HIP graph",
                    "tokens_per_step": tokens_per_step, "hip_graph": not args.no_graph,
                    "kv_splits": args.splits or "auto"},
         "phase_us": {n: round(ms * 1e3, 2) for (n, _), ms in zip(phases, phase_ms)},
+        "per_request_us": {"visual_compress": round(compress_us, 2)},
+        "step_with_compress_us": round(ms_per_step * 1e3 + compress_us, 2),
         "tokens_per_s_at_paper_tau": round(B * PAPER_TAU.get(cfg.name, 0.0) / (ms_per_step * 1e-3), 1),
         "roofline": roofline,
     }
-
     out["read_ceiling"] = read_ceiling(torch, dream, bytes_launch, L)
-    out["next_rows"] = {"spec_accept": spec_accept_leg(torch, dream, logits, token, parent, cfg),
-                        "attention_entropy": entropy_leg(torch, dream, desc, pq, vk[L - 1], P),
-                        "tree_build": tree_build_leg(torch, dream, di, cfg),
-                        "project": project_leg(torch, dream, desc, xk, xv, prefix_len, xnode[1], cfg),
-                        "kv_commit": kv_commit_leg(torch, dream, desc, vk + vv, prefix_len, T, accept_path, accept_len, cfg)}
-    out["streaming_regime"] = streaming_regime(torch, dream, di, cfg)
-    if not args.no_cpu:
-        out["cpu_baseline"] = cpu_baseline(cfg, L, tokens_per_step)
-    print(json.dumps(out))
-    return 0
+    if full:
+        out["next_rows"] = {"spec_accept": spec_accept_leg(torch, dream, logits, token, parent, cfg),
+                            "attention_entropy": entropy_leg(torch, dream, desc, pq, vk[L - 1], P),
+                            "tree_build": tree_build_leg(torch, dream, di, cfg),
+                            "project": project_leg(torch, dream, desc, xk, xv, prefix_len, xnode[1], cfg),
+                            "kv_commit": kv_commit_leg(torch, dream, desc, vk + vv, prefix_len, T, accept_path, accept_len, cfg)}
+        out["streaming_regime"] = streaming_regime(torch, dream, di, cfg)
+    return out
 
 
 def graph_time_us(torch, body, reps=20, warm=3):
@@ -452,47 +491,58 @@ def streaming_regime(torch, dream, di, cfg, batch=32, iters=20):
 
 
 def cpu_baseline(cfg, L, tokens_per_step):
-    """The float64 oracle, as it stands, timed on this host: one verification layer (scaled by the layer
-    count), the six cross-attention calls, the compression call and the acceptance call."""
+    """The float64 oracle, as it stands, timed on this host, once on all the threads it can use (at most 16) and once
+    single-threaded: one verification layer (scaled by the layer count), the six cross-attention calls and the
+    acceptance call, i.e. the same step as `value`; the per-request compression is timed beside it."""
     import dream_inputs as di
     import oracle
 
-    threads = min(16, oracle.hw_threads())
-    oracle.set_threads(threads)
     x = di.verify_inputs(cfg)
     nb = min(cfg.batch, 2)   # bounded sample of the batch
     scale_b = cfg.batch / nb
+    lg, tok, par, _ = di.accept_inputs(cfg, plant_depths=[PLANT_DEPTH] * cfg.batch)
+    pq = np.ascontiguousarray(di.prefill_q(cfg)[:nb])
+    feats = di.feature_rows(cfg)[:nb]
 
     def sub(a):
         return np.ascontiguousarray(a[:nb])
 
-    t = time.perf_counter()
-    oracle.tree_attn(sub(x.q), sub(x.k), sub(x.v), cfg.dtype, x.prefix_len[:nb], x.parent[:nb], True)
-    t_verify = (time.perf_counter() - t) * scale_b
-    t = time.perf_counter()
-    for lv in range(cfg.depth):
-        rows = np.stack([di.tree_levels(x.parent[b])[lv] for b in range(nb)])
-        qsel = np.stack([x.q[b, rows[b]] for b in range(nb)])
-        oracle.tree_attn(qsel, sub(x.k), sub(x.v), cfg.dtype, x.prefix_len[:nb], x.parent[:nb], False, q_node=rows)
-    t_xattn = (time.perf_counter() - t) * scale_b
-    pq = di.prefill_q(cfg)[:nb]
-    t = time.perf_counter()
-    sc = oracle.visual_scores(np.ascontiguousarray(pq), sub(x.k), cfg.dtype, 0, cfg.n_visual)
-    kept = oracle.topk_keep(sc, 0, cfg.keep_num, cfg.keep_den)
-    oracle.gather_rows(di.feature_rows(cfg)[:nb], cfg.dtype, kept)
-    t_comp = (time.perf_counter() - t) * scale_b
-    lg, tok, par, _ = di.accept_inputs(cfg, plant_depths=[PLANT_DEPTH] * cfg.batch)
-    t = time.perf_counter()
-    oracle.accept_path(np.ascontiguousarray(lg[:nb]), cfg.dtype, tok[:nb], par[:nb], cfg.depth)
-    t_acc = (time.perf_counter() - t) * scale_b
-    oracle.set_threads(1)
-    step_s = L * t_verify + t_xattn + t_comp + t_acc
+    def timed(threads, with_compress):
+        oracle.set_threads(threads)
+        t = time.perf_counter()
+        oracle.tree_attn(sub(x.q), sub(x.k), sub(x.v), cfg.dtype, x.prefix_len[:nb], x.parent[:nb], True)
+        t_verify = (time.perf_counter() - t) * scale_b
+        t = time.perf_counter()
+        for lv in range(cfg.depth):
+            rows = np.stack([di.tree_levels(x.parent[b])[lv] for b in range(nb)])
+            qsel = np.stack([x.q[b, rows[b]] for b in range(nb)])
+            oracle.tree_attn(qsel, sub(x.k), sub(x.v), cfg.dtype, x.prefix_len[:nb], x.parent[:nb], False, q_node=rows)
+        t_xattn = (time.perf_counter() - t) * scale_b
+        t = time.perf_counter()
+        oracle.accept_path(np.ascontiguousarray(lg[:nb]), cfg.dtype, tok[:nb], par[:nb], cfg.depth)
+        t_acc = (time.perf_counter() - t) * scale_b
+        t_comp = None
+        if with_compress:
+            t = time.perf_counter()
+            sc = oracle.visual_scores(pq, sub(x.k), cfg.dtype, 0, cfg.n_visual)
+            kept = oracle.topk_keep(sc, 0, cfg.keep_num, cfg.keep_den)
+            oracle.gather_rows(feats, cfg.dtype, kept)
+            t_comp = (time.perf_counter() - t) * scale_b
+        oracle.set_threads(1)
+        step_s = L * t_verify + t_xattn + t_acc
+        return step_s, {"verify_layer": round(t_verify, 4), "xattn": round(t_xattn, 4), "accept": round(t_acc, 4),
+                        "per_request_compress": None if t_comp is None else round(t_comp, 4)}
+
+    threads = min(16, oracle.hw_threads())
+    step_s, parts = timed(threads, True)
+    step_1, parts_1 = timed(1, cfg.batch == 1)    # (the single-threaded compression of a batch would take minutes)
     return {"value": round(tokens_per_step / step_s, 3), "unit": "tokens/s", "cores": threads, "kind": "oracle",
-            "step_s": round(step_s, 3),
+            "step_s": round(step_s, 3), "host_nproc": os.cpu_count(), "host_hw_threads_seen_by_openmp": oracle.hw_threads(),
             "sample": f"{nb} of {cfg.batch} sequences; 1 of {L} verification layers timed and scaled by {L}; "
-                      f"6 cross-attention calls, compression and acceptance timed in full",
-            "parts_s": {"verify_layer": round(t_verify, 4), "xattn": round(t_xattn, 4), "compress": round(t_comp, 4),
-                        "accept": round(t_acc, 4)}}
+                      f"6 cross-attention calls and acceptance timed in full; compression (per request) timed beside the step",
+            "parts_s": parts,
+            "single_thread": {"value": round(tokens_per_step / step_1, 3), "unit": "tokens/s", "cores": 1, "step_s": round(step_1, 3),
+                              "parts_s": parts_1}}
 
 
 if __name__ == "__main__":
