@@ -3,11 +3,14 @@
 // token is discarded and decoding continues from the accepted prefix; Section 4: KV caching).
 //
 // One launch serves many caches of one shape (K and V of every layer, the draft's feature caches): the cache
-// pointers travel in the launch arguments.  One workgroup per (KV head, sequence, cache) moves the at most 64
-// accepted rows in place: every 16-byte chunk is loaded into a register first, the workgroup meets at a
-// barrier, then the chunks are stored, so a row that is both a source and a destination (path 0,2,3: row 2 is
-// written by the second entry and read by the first) is always read before it is overwritten.
-// Roofline: HBM, but the bytes are few (rows x heads x caches): the call is one launch latency.
+// pointers travel in the launch arguments.  One workgroup per (group of KV heads, sequence, cache) moves the
+// accepted rows of its heads in place: every 16-byte chunk is loaded into a register first, the workgroup meets
+// at a barrier, then the chunks are stored, so a row that is both a source and a destination (path 0,2,3: row 2
+// is written by the second entry and read by the first) is always read before it is overwritten.  A head's
+// accepted rows are only a few hundred bytes to a few KB, so a workgroup takes as many heads as its 64 KB of
+// registers hold while the grid still has about a thousand workgroups: with one head each, a launch over many
+// sequences is tens of thousands of workgroups that each keep a fifth of their threads busy for one round trip.
+// Roofline: HBM (read and write of rows x heads x caches); at one sequence the call is one launch latency.
 #include "common.h"
 
 using namespace dream;
@@ -21,39 +24,45 @@ struct CommitArgs {
     void *cache[MAX_CACHES_PER_LAUNCH];
     const int32_t *prefix_len, *path, *accept_len;
     int32_t *prefix_len_out;
-    int32_t n_kv_heads, n_tree, path_stride, chunks_per_row, first_cache;
+    int32_t n_kv_heads, n_tree, path_stride, chunks_per_row, first_cache, heads_per_wg;
     int64_t s_max;
 };
 
 __global__ __launch_bounds__(256) void kv_commit_kernel(CommitArgs a)
 {
-    const int h = blockIdx.x, b = blockIdx.y, ci = blockIdx.z;
+    const int h0 = blockIdx.x * a.heads_per_wg, b = blockIdx.y, ci = blockIdx.z;
+    const int n_heads = min(a.heads_per_wg, a.n_kv_heads - h0);
     const int tid = threadIdx.x;
     const int P = (int)min((int64_t)max(a.prefix_len[b], 0), a.s_max - a.n_tree);
     // device metadata is trusted, but stay inside the tree rows whatever it holds
     const int n = min(max(a.accept_len[b], 0), min(a.path_stride, a.n_tree) - 1);
-    if (h == 0 && ci == 0 && a.first_cache == 0 && tid == 0 && a.prefix_len_out)
+    if (blockIdx.x == 0 && ci == 0 && a.first_cache == 0 && tid == 0 && a.prefix_len_out)
         a.prefix_len_out[b] = P + n + 1;
     const int cpr = a.chunks_per_row;
-    const int total = (n + 1) * cpr;
-    u32x4 *tree = reinterpret_cast<u32x4 *>(a.cache[ci]) + (((int64_t)b * a.n_kv_heads + h) * a.s_max + P) * cpr;
+    const int per_head = (n + 1) * cpr;          // chunks of one head: destination rows 0..n of its tree area are contiguous
+    const int total = n_heads * per_head;
+    const int64_t head_stride = a.s_max * cpr;   // chunks between the same row of consecutive heads
+    u32x4 *tree = reinterpret_cast<u32x4 *>(a.cache[ci]) + (((int64_t)b * a.n_kv_heads + h0) * a.s_max + P) * cpr;
     const int32_t *path = a.path + (int64_t)b * a.path_stride;
     u32x4 r[CHUNKS_PER_THREAD];
 #pragma unroll
     for (int i = 0; i < CHUNKS_PER_THREAD; i++) {
         const int idx = tid + i * 256;
         if (idx < total) {
-            const int j = idx / cpr, c = idx - j * cpr;
+            const int hl = idx / per_head, rest = idx - hl * per_head;
+            const int j = rest / cpr, c = rest - j * cpr;
             const int node = min(max(path[j], 0), a.n_tree - 1);
-            r[i] = tree[(int64_t)node * cpr + c];
+            r[i] = tree[hl * head_stride + (int64_t)node * cpr + c];
         }
     }
-    __syncthreads();   // every source chunk of this (sequence, head, cache) is in a register
+    __syncthreads();   // every source chunk of these heads is in a register
 #pragma unroll
     for (int i = 0; i < CHUNKS_PER_THREAD; i++) {
         const int idx = tid + i * 256;
-        if (idx < total)
-            tree[idx] = r[i];   // destination rows 0..n of the tree area are contiguous
+        if (idx < total) {
+            const int hl = idx / per_head, rest = idx - hl * per_head;
+            tree[hl * head_stride + rest] = r[i];
+        }
     }
 }
 
@@ -97,12 +106,21 @@ int dream_kv_commit(const dream_attn_desc *desc, void *const *caches_host, int32
     a.prefix_len = prefix_len; a.path = accept_path; a.accept_len = accept_len; a.prefix_len_out = prefix_len_out;
     a.n_kv_heads = desc->n_kv_heads; a.n_tree = n_tree; a.path_stride = path_stride;
     a.chunks_per_row = (int)(row_bytes / 16); a.s_max = desc->s_max;
+    // heads per workgroup: as many as the registers of a workgroup hold, while about a thousand workgroups remain
+    const int64_t fit = (256 * CHUNKS_PER_THREAD) / (max_rows * a.chunks_per_row);
+    const int64_t spare = ((int64_t)desc->n_kv_heads * desc->batch * (n_caches < MAX_CACHES_PER_LAUNCH ? n_caches : MAX_CACHES_PER_LAUNCH)) / 1024;
+    int64_t hpw = fit < spare ? fit : spare;
+    if (hpw > desc->n_kv_heads)
+        hpw = desc->n_kv_heads;
+    if (hpw < 1)
+        hpw = 1;
+    a.heads_per_wg = (int)hpw;
     for (int32_t first = 0; first < n_caches; first += MAX_CACHES_PER_LAUNCH) {
         const int m = n_caches - first < MAX_CACHES_PER_LAUNCH ? n_caches - first : MAX_CACHES_PER_LAUNCH;
         for (int i = 0; i < MAX_CACHES_PER_LAUNCH; i++)
             a.cache[i] = i < m ? caches_host[first + i] : nullptr;
         a.first_cache = first;
-        hipLaunchKernelGGL(kv_commit_kernel, dim3(desc->n_kv_heads, desc->batch, m), dim3(256), 0, as_stream(stream), a);
+        hipLaunchKernelGGL(kv_commit_kernel, dim3(ceil_div(desc->n_kv_heads, a.heads_per_wg), desc->batch, m), dim3(256), 0, as_stream(stream), a);
         int rc = check_launch("kv_commit_kernel");
         if (rc)
             return rc;
