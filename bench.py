@@ -240,6 +240,15 @@ def run_config(torch, dream, di, args, cfg, steps, warmup, full):
     assert tokens_per_step == B * (PLANT_DEPTH + 1), "accept_path did not return the planted path"
     value = tokens_per_step / (ms_per_step * 1e-3)
     compress_us = graph_time_us(torch, lambda: [per_request_compress() for _ in range(4)], reps=5) / 4
+    # the same call when the caller brings the rows' log-sum-exps (what the prefill attention leaves): one score pass
+    row_lse = torch.zeros(B, Hq, P, dtype=torch.float32, device=dev)
+
+    def compress_with_lse():
+        dream.dream_visual_compress(desc, pq, None, P, vk[L - 1], P, 0, cfg.n_visual, cfg.keep_num, cfg.keep_den, None,
+                                    scores, kept, rows, P, gathered, cfg.hidden, ws_c, row_lse_in=row_lse)
+    compress_with_lse()
+    torch.cuda.synchronize()
+    compress_lse_us = graph_time_us(torch, lambda: [compress_with_lse() for _ in range(4)], reps=5) / 4
 
     launch_us = phase_ms[0] * 1e3 / L
     bytes_launch = verify_bytes_per_launch(cfg)
@@ -262,7 +271,7 @@ def run_config(torch, dream, di, args, cfg, steps, warmup, full):
                    "tokens_per_step": tokens_per_step, "hip_graph": not args.no_graph,
                    "kv_splits": args.splits or "auto"},
         "phase_us": {n: round(ms * 1e3, 2) for (n, _), ms in zip(phases, phase_ms)},
-        "per_request_us": {"visual_compress": round(compress_us, 2)},
+        "per_request_us": {"visual_compress": round(compress_us, 2), "visual_compress_given_row_lse": round(compress_lse_us, 2)},
         "step_with_compress_us": round(ms_per_step * 1e3 + compress_us, 2),
         "tokens_per_s_at_paper_tau": round(B * PAPER_TAU.get(cfg.name, 0.0) / (ms_per_step * 1e-3), 1),
         "roofline": roofline,

@@ -131,7 +131,12 @@ int dream_draft_xattn(const dream_attn_desc *desc, const void *q, const void *kx
  * gather_src[b, kept_idx[b,t], :].
  *   q          [B, n_q, Hq, D] (dtype of desc; bf16 only for stage A), q_pos nullable [B, n_q]
  *   k_cache    [B, Hkv, s_max, D]; n_keys = live key rows, every pos_r < n_keys <= s_max
- *   scores_in  nullable [B, vis_len] float32; scores_out nullable [B, vis_len] float32
+ *   scores_in  nullable [B, vis_len] float32 (skips stage A); scores_out nullable [B, vis_len] float32
+ *   row_lse_in nullable [B, Hq, n_q] float32: natural-log sum of exp of the scaled scores of every row over its causal
+ *              keys, -inf for a row without keys.  Section 3.3 takes the scores from the attention matrix the target's
+ *              last layer has just computed: an attention kernel that leaves a log-sum-exp per row (as
+ *              dream_tree_verify_attn does) already holds the normaliser of every row, and stage A then needs one pass
+ *              over q k^T instead of two.  Ignored when scores_in is given.
  *   kept_idx   [B, k] int32;  n_kept_host nullable, HOST int32 receiving k
  *   gather_src nullable [B, n_rows_src, row_elems] of desc->dtype, gather_dst [B, k, row_elems];
  *              n_rows_src is the row capacity per sequence (kept positions are < n_rows_src)
@@ -141,7 +146,7 @@ size_t dream_visual_compress_workspace(const dream_attn_desc *desc, int32_t n_q,
 int dream_visual_compress(const dream_attn_desc *desc, const void *q, const int32_t *q_pos,
                           int32_t n_q, const void *k_cache, int32_t n_keys, int32_t vis_start,
                           int32_t vis_len, int32_t keep_num, int32_t keep_den,
-                          const float *scores_in, float *scores_out, int32_t *kept_idx,
+                          const float *scores_in, const float *row_lse_in, float *scores_out, int32_t *kept_idx,
                           int32_t *n_kept_host, const void *gather_src, int64_t n_rows_src,
                           void *gather_dst, int64_t row_elems, void *workspace,
                           size_t workspace_bytes, void *stream);

@@ -171,12 +171,12 @@ def dream_visual_compress_workspace(desc: AttnDesc, n_q: int, vis_len: int) -> i
 
 def dream_visual_compress(desc: AttnDesc, q, q_pos, n_q: int, k_cache, n_keys: int, vis_start: int, vis_len: int,
                           keep_num: int, keep_den: int, scores_in, scores_out, kept_idx, gather_src, n_rows_src: int,
-                          gather_dst, row_elems: int, workspace, stream=None) -> int:
+                          gather_dst, row_elems: int, workspace, stream=None, row_lse_in=None) -> int:
     """Returns k, the kept count the library reports through its host out-parameter."""
     n_kept = C.c_int32(-1)
     _check(load().dream_visual_compress(C.byref(desc), _dev(q), _dev(q_pos), C.c_int32(n_q), _dev(k_cache),
                                         C.c_int32(n_keys), C.c_int32(vis_start), C.c_int32(vis_len),
-                                        C.c_int32(keep_num), C.c_int32(keep_den), _dev(scores_in), _dev(scores_out),
+                                        C.c_int32(keep_num), C.c_int32(keep_den), _dev(scores_in), _dev(row_lse_in), _dev(scores_out),
                                         _dev(kept_idx), C.byref(n_kept), _dev(gather_src), C.c_int64(n_rows_src),
                                         _dev(gather_dst), C.c_int64(row_elems), _dev(workspace),
                                         C.c_size_t(workspace.numel() * workspace.element_size()), _stream(stream)))

@@ -23,6 +23,7 @@ struct ScoreArgs {
     const void *q, *k;
     const int32_t *q_pos;
     float *lse2;   // [ns1, B, Hq, n_q_pad]  log2-domain log-sum-exp of each row over the keys of split s (-inf: none)
+    const float *lse_in;   // nullable [B, Hq, n_q]: the caller's natural-log log-sum-exp of every row (pass 1 is skipped)
     float *part;   // [B, Hq, ns2, vis_len]  column sums per head and row split
     int32_t n_q, n_q_pad, n_keys, n_q_heads, n_kv_heads, vis_start, vis_len;
     float *ent_part;    // [ns1, B, Hq, n_q_pad]  expected score of the row under its attention weights, per split (entropy only)
@@ -289,9 +290,13 @@ __global__ __launch_bounds__(256) void scores_colsum_bf16_kernel(ScoreArgs a)
         if (tid < 32) {
             const int r = t * 32 + tid;
             const bool live = r < a.n_q;
+            if (a.lse_in) {      // (only with NS1 = 1) natural logarithm -> the log2 units of the scores here
+                lr[0] = live ? a.lse_in[((int64_t)b * a.n_q_heads + h) * a.n_q + r] * 1.4426950408889634f : -INFINITY;
+            } else {
 #pragma unroll
-            for (int s = 0; s < NS1; s++)
-                lr[s] = live ? lrow[s * a.lse_split_stride + r] : -INFINITY;
+                for (int s = 0; s < NS1; s++)
+                    lr[s] = live ? lrow[s * a.lse_split_stride + r] : -INFINITY;
+            }
             pr = live ? (a.q_pos ? a.q_pos[(int64_t)b * a.n_q + r] : r) : -1;
         }
     };
@@ -444,10 +449,10 @@ __global__ __launch_bounds__(64) void scores_colsum_f32_kernel(ScoreArgs a, int 
     float cs = 0.0f;
     if (key < a.n_keys) {
         const float *kr = reinterpret_cast<const float *>(a.k) + (((int64_t)b * a.n_kv_heads + kvh) * a.s_max + key) * D;
-        const float *lrow = a.lse2 + ((int64_t)b * a.n_q_heads + h) * a.n_q_pad;
+        const float *lrow = a.lse_in ? a.lse_in + ((int64_t)b * a.n_q_heads + h) * a.n_q : a.lse2 + ((int64_t)b * a.n_q_heads + h) * a.n_q_pad;
         for (int row = 0; row < a.n_q; row++) {
             int pos = a.q_pos ? a.q_pos[(int64_t)b * a.n_q + row] : row;
-            if (key > pos)
+            if (key > pos || lrow[row] == -INFINITY)   // (a caller's log-sum-exp of a row that sees no key)
                 continue;
             const float *q = reinterpret_cast<const float *>(a.q) + (((int64_t)b * a.n_q + row) * a.n_q_heads + h) * D;
             float dot = 0.0f;
@@ -692,8 +697,8 @@ size_t dream_visual_compress_workspace(const dream_attn_desc *desc, int32_t n_q,
 
 int dream_visual_compress(const dream_attn_desc *desc, const void *q, const int32_t *q_pos, int32_t n_q,
                           const void *k_cache, int32_t n_keys, int32_t vis_start, int32_t vis_len,
-                          int32_t keep_num, int32_t keep_den, const float *scores_in, float *scores_out,
-                          int32_t *kept_idx, int32_t *n_kept_host, const void *gather_src, int64_t n_rows_src,
+                          int32_t keep_num, int32_t keep_den, const float *scores_in, const float *row_lse_in,
+                          float *scores_out, int32_t *kept_idx, int32_t *n_kept_host, const void *gather_src, int64_t n_rows_src,
                           void *gather_dst, int64_t row_elems, void *workspace, size_t workspace_bytes, void *stream)
 {
     const char *who = "dream_visual_compress";
@@ -740,7 +745,7 @@ int dream_visual_compress(const dream_attn_desc *desc, const void *q, const int3
         a.lse2 = reinterpret_cast<float *>(static_cast<char *>(workspace) + p.off_lse);
         a.part = reinterpret_cast<float *>(static_cast<char *>(workspace) + p.off_part);
         a.n_q = n_q; a.n_q_pad = p.n_q_pad; a.n_keys = n_keys;
-        a.ns1 = p.ns1; a.ns2 = p.ns2; a.ent_part = nullptr;
+        a.ns1 = row_lse_in ? 1 : p.ns1; a.ns2 = p.ns2; a.ent_part = nullptr; a.lse_in = row_lse_in;
         a.lse_split_stride = (int64_t)desc->batch * desc->n_q_heads * p.n_q_pad;
         a.n_q_heads = desc->n_q_heads; a.n_kv_heads = desc->n_kv_heads;
         a.vis_start = vis_start; a.vis_len = vis_len; a.s_max = desc->s_max;
@@ -750,24 +755,33 @@ int dream_visual_compress(const dream_attn_desc *desc, const void *q, const int3
             if ((int64_t)desc->batch * (p.ns1 > p.ns2 ? p.ns1 : p.ns2) > 65535 || ceil_div(n_q, 64) > 65535)
                 return fail(DREAM_ERR_UNSUPPORTED, "%s: batch %d or n_q %d too large for the score grids", who, desc->batch, n_q);
             dim3 g1(desc->n_q_heads, ceil_div(n_q, 64), desc->batch * p.ns1), g2(desc->n_q_heads, ceil_div(vis_len, 64), desc->batch * p.ns2);
+            // pass 1 (the rows' log-sum-exps) only when the caller does not bring them
             switch (desc->head_dim) {
             case 64:
-                hipLaunchKernelGGL((scores_lse_bf16_kernel<64, false>), g1, dim3(256), 0, st, a);
-                launch_colsum<64>(p.ns1, g2, st, a);
+                if (!row_lse_in) {
+                    hipLaunchKernelGGL((scores_lse_bf16_kernel<64, false>), g1, dim3(256), 0, st, a);
+                }
+                launch_colsum<64>(a.ns1, g2, st, a);
                 break;
             case 128:
-                hipLaunchKernelGGL((scores_lse_bf16_kernel<128, false>), g1, dim3(256), 0, st, a);
-                launch_colsum<128>(p.ns1, g2, st, a);
+                if (!row_lse_in) {
+                    hipLaunchKernelGGL((scores_lse_bf16_kernel<128, false>), g1, dim3(256), 0, st, a);
+                }
+                launch_colsum<128>(a.ns1, g2, st, a);
                 break;
             default:
-                hipLaunchKernelGGL((scores_lse_bf16_kernel<256, false>), g1, dim3(256), 0, st, a);
-                launch_colsum<256>(p.ns1, g2, st, a);
+                if (!row_lse_in) {
+                    hipLaunchKernelGGL((scores_lse_bf16_kernel<256, false>), g1, dim3(256), 0, st, a);
+                }
+                launch_colsum<256>(a.ns1, g2, st, a);
                 break;
             }
         } else {
             if (n_q > 65535 * 1)
                 return fail(DREAM_ERR_UNSUPPORTED, "%s: too many rows for the float32 path", who);
-            hipLaunchKernelGGL(scores_lse_f32_kernel, dim3(n_q, desc->n_q_heads, desc->batch), dim3(256), 0, st, a, desc->head_dim);
+            if (!row_lse_in) {
+                hipLaunchKernelGGL(scores_lse_f32_kernel, dim3(n_q, desc->n_q_heads, desc->batch), dim3(256), 0, st, a, desc->head_dim);
+            }
             hipLaunchKernelGGL(scores_colsum_f32_kernel, dim3(ceil_div(vis_len, 64), desc->n_q_heads, desc->batch), dim3(64), 0, st, a, desc->head_dim);
         }
         int rc = check_launch("visual score kernels");
@@ -836,6 +850,7 @@ int dream_attention_entropy(const dream_attn_desc *desc, const void *q, const in
     ScoreArgs a;
     a.q = q; a.k = k_cache; a.q_pos = q_pos;
     a.lse2 = reinterpret_cast<float *>(static_cast<char *>(workspace) + DREAM_WORKSPACE_MIN_BYTES);
+    a.lse_in = nullptr;
     a.ent_part = reinterpret_cast<float *>(static_cast<char *>(workspace) + DREAM_WORKSPACE_MIN_BYTES + part);
     a.part = nullptr;
     a.n_q = n_q; a.n_q_pad = p.n_q_pad; a.n_keys = n_keys;

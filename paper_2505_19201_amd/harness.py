@@ -90,7 +90,7 @@ def run_accept(logits: np.ndarray, dtype: str, token: np.ndarray, parent: np.nda
 
 
 def run_compress(dtype: str, q, k, n_keys, vis_start, vis_len, keep_num, keep_den, q_pos=None, scores_in=None,
-                 gather_src=None, scale: float = 0.0, want_scores: bool = True):
+                 gather_src=None, scale: float = 0.0, want_scores: bool = True, row_lse=None):
     """Returns (scores [B,v] float32 or None, kept [B,k] int32, gathered or None)."""
     if scores_in is None:
         B, n_q, Hq, D = q.shape
@@ -114,8 +114,9 @@ def run_compress(dtype: str, q, k, n_keys, vis_start, vis_len, keep_num, keep_de
         n_rows_src, row_elems = gather_src.shape[1], gather_src.shape[2]
         gdst = torch.zeros((B, max(k_keep, 1), row_elems), dtype=TORCH_DT[dtype], device="cuda")
     ws = dream.alloc_workspace(dream.dream_visual_compress_workspace(desc, n_q, vis_len))
+    dlse = None if row_lse is None else dream.to_device(np.ascontiguousarray(row_lse, dtype=np.float32))
     k_rep = dream.dream_visual_compress(desc, dq, dpos, n_q, dk, n_keys, vis_start, vis_len, keep_num, keep_den, dsi,
-                                        sc_out, kept, gsrc, n_rows_src, gdst, row_elems, ws)
+                                        sc_out, kept, gsrc, n_rows_src, gdst, row_elems, ws, row_lse_in=dlse)
     torch.cuda.synchronize()
     assert k_rep == k_keep
     scores = None if sc_out is None else sc_out.cpu().numpy()[:, :vis_len]

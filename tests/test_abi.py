@@ -76,14 +76,14 @@ def test_host_side_argument_errors(lib):
              one, C.c_size_t(1 << 30), None) == -1
     h = lib.dream_visual_compress
     base = [C.byref(d), one, None, C.c_int32(64), one, C.c_int32(64), C.c_int32(0), C.c_int32(32), C.c_int32(1), C.c_int32(2),
-            None, None, one, None, None, C.c_int64(0), None, C.c_int64(0), one, C.c_size_t(1 << 30), None]
+            None, None, None, one, None, None, C.c_int64(0), None, C.c_int64(0), one, C.c_size_t(1 << 30), None]
     bad = list(base); bad[9] = C.c_int32(0)
     assert h(*bad) == -1                                                          # keep_den
     bad = list(base); bad[8] = C.c_int32(3)
     assert h(*bad) == -1                                                          # keep_num > keep_den
     bad = list(base); bad[6] = C.c_int32(40)
     assert h(*bad) == -1                                                          # span beyond keys
-    bad = list(base); bad[19] = C.c_size_t(16)
+    bad = list(base); bad[20] = C.c_size_t(16)
     assert h(*bad) == -3
 
 

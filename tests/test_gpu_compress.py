@@ -171,3 +171,65 @@ def test_full_size_smolvlm_b32(gu):
     want_kept = oracle.topk_keep(want, 0, cfg.keep_num, cfg.keep_den)
     assert np.array_equal(kept[safe], want_kept[safe])
     assert np.array_equal(gathered, oracle.gather_rows(rows, "bf16", kept))
+
+
+def _causal_row_lse(q, k, dtype, scale=None, q_pos=None):
+    """Natural-log sum of exp of the scaled scores of every row over keys 0..pos(row), float64 numpy: [B, Hq, n_q].
+    (What an attention kernel with a log-sum-exp output leaves; written out here so that nothing comes from the GPU.)"""
+    qf, kf = di.as_f64(q, dtype), di.as_f64(k, dtype)
+    B, n_q, Hq, D = qf.shape
+    Hkv = kf.shape[1]
+    scale = 1.0 / np.sqrt(D) if scale is None else scale
+    out = np.empty((B, Hq, n_q))
+    for b in range(B):
+        pos = np.arange(n_q) if q_pos is None else np.asarray(q_pos)[b]
+        for h in range(Hq):
+            s = qf[b, :, h, :] @ kf[b, h // (Hq // Hkv)].T * scale            # [n_q, n_keys]
+            s = np.where(np.arange(s.shape[1])[None, :] <= pos[:, None], s, -np.inf)
+            m = s.max(axis=1)
+            out[b, h] = m + np.log(np.exp(s - m[:, None]).sum(axis=1))
+    return out
+
+
+@pytest.mark.parametrize("case", SMALL, ids=[c[0] for c in SMALL])
+def test_caller_supplied_row_lse_small(gu, case):
+    """With the rows' log-sum-exps given, stage A is one pass: same scores (to tolerance) and the same kept set."""
+    name, B, Hq, Hkv, D, v, qt, vs, (num, den) = case
+    cfg = di.Config(name, "bf16", B, Hq, Hkv, D, 64, v, qt, 8, 3, num, den, 100, 1, 60)
+    seed, q, k, want = _pick_seed(cfg, vs, v)
+    lse = _causal_row_lse(q, k, "bf16")
+    scores, kept, _ = gu.run_compress("bf16", q, k, cfg.prefix, vs, v, num, den, row_lse=lse)
+    np.testing.assert_allclose(scores, want, rtol=SCORE_RTOL["bf16"])
+    assert np.array_equal(kept, oracle.topk_keep(want, vs, num, den))
+
+
+def test_caller_supplied_row_lse_tiny_f32_and_positions(gu):
+    cfg = di.CONFIGS["tiny"]
+    seed, q, k, want = _pick_seed(cfg, 0, cfg.n_visual)
+    lse = _causal_row_lse(q, k, "f32")
+    scores, kept, _ = gu.run_compress("f32", q, k, cfg.prefix, 0, cfg.n_visual, cfg.keep_num, cfg.keep_den, row_lse=lse)
+    np.testing.assert_allclose(scores, want, rtol=SCORE_RTOL["f32"])
+    assert np.array_equal(kept, oracle.topk_keep(want, 0, cfg.keep_num, cfg.keep_den))
+    # explicit, shuffled row positions (bf16)
+    c2 = di.Config("pos_lse", "bf16", 2, 4, 2, 128, 512, 100, 60, 8, 3, 1, 2, 100, 1, 62)
+    q, k = _qk(c2, 5, n_q=90)
+    g = di.rng(63, 902)
+    q_pos = np.stack([g.permutation(c2.prefix)[:90] for _ in range(c2.batch)]).astype(np.int32)
+    want = oracle.visual_scores(q, k, "bf16", 10, 80, q_pos=q_pos)
+    lse = _causal_row_lse(q, k, "bf16", q_pos=q_pos)
+    scores, kept, _ = gu.run_compress("bf16", q, k, c2.prefix, 10, 80, 1, 2, q_pos=q_pos, row_lse=lse)
+    np.testing.assert_allclose(scores, want, rtol=SCORE_RTOL["bf16"])
+
+
+@pytest.mark.parametrize("name", ["llava", "gemma3"])
+def test_caller_supplied_row_lse_full_size(gu, name):
+    cfg = di.CONFIGS[name]
+    oracle.set_threads(min(16, oracle.hw_threads()))
+    try:
+        seed, q, k, want = _pick_seed(cfg, 0, cfg.n_visual)
+    finally:
+        oracle.set_threads(1)
+    lse = _causal_row_lse(q, k, "bf16")
+    scores, kept, _ = gu.run_compress("bf16", q, k, cfg.prefix, 0, cfg.n_visual, cfg.keep_num, cfg.keep_den, row_lse=lse)
+    np.testing.assert_allclose(scores, want, rtol=SCORE_RTOL["bf16"])
+    assert np.array_equal(kept, oracle.topk_keep(want, 0, cfg.keep_num, cfg.keep_den))
