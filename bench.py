@@ -459,10 +459,11 @@ def copy_calibration(torch):
     return 0
 
 
-def streaming_regime(torch, dream, di, cfg, batch=32, iters=20):
+def streaming_regime(torch, dream, di, cfg, batch=32, iters=40, warm=60):
     """The same verification kernel on the same shape with `batch` sequences per launch: one launch then
     moves hundreds of MB, so its duration measures streaming efficiency rather than launch latency.
-    Two cache sets are alternated so that nothing is served from the last-level cache."""
+    Two cache sets are alternated so that nothing is served from the last-level cache.  The warm-up is long enough
+    (several ms of back-to-back launches) for the clocks to settle: the first launches after a pause run 5-10 % slower."""
     big = cfg.with_batch(batch) if cfg.batch < batch else cfg
     B, T, Hq, Hkv, D, P = big.batch, big.n_tree, big.n_q_heads, big.n_kv_heads, big.head_dim, big.prefix
     S = P + T
@@ -482,7 +483,7 @@ def streaming_regime(torch, dream, di, cfg, batch=32, iters=20):
         q, k, v = sets[i & 1]
         dream.dream_tree_verify_attn(desc, q, k, v, pl, T, parent, None, S, out, None, ws)
 
-    for i in range(4):
+    for i in range(warm):
         run(i)
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

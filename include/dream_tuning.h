@@ -21,7 +21,6 @@ extern "C" {
  * it again after changing either, and change neither while another thread is inside an attention call. */
 void dream_set_kv_splits(int32_t n_splits);
 void dream_set_q_tiles(int32_t q_tiles);
-void dream_set_experiment(int32_t bits);
 
 /* Host-only: the names of all bf16 attention kernel variants the launch plan can choose, separated by ';', in the
  * spelling dream_attn_plan_describe uses ("attn_wave_kernel<128,8,2,1>": head_dim, waves, column slices, query tiles

@@ -51,7 +51,6 @@ struct AttnArgs {
     int32_t n_streams;       // B * Hkv * n_splits
     int64_t s_max;
     float scale, scale_log2;
-    int32_t experiment;
 };
 
 __device__ __forceinline__ uint64_t visible_nodes(const AttnArgs &a, int b, int node, const int32_t *lds_parent)
@@ -1096,7 +1095,6 @@ int run_attention(const char *who, const dream_attn_desc *d, const void *q, cons
     a.s_max = d->s_max;
     a.scale = d->scale != 0.0f ? d->scale : 1.0f / sqrtf((float)d->head_dim);
     a.scale_log2 = a.scale * 1.4426950408889634f;
-    a.experiment = experiment_override();
     hipStream_t st = as_stream(stream);
 
     if (d->dtype == DREAM_F32) {
