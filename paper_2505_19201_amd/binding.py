@@ -21,7 +21,7 @@ EXPORTED_SYMBOLS = (
     "dream_init", "dream_tree_verify_attn_workspace", "dream_tree_verify_attn",
     "dream_draft_xattn_workspace", "dream_draft_xattn", "dream_visual_compress_workspace",
     "dream_visual_compress", "dream_accept_path_workspace", "dream_accept_path",
-    "dream_tree_validate_host", "dream_last_error", "dream_set_kv_splits", "dream_set_q_tiles", "dream_attn_variants",
+    "dream_tree_validate_host", "dream_last_error", "dream_set_kv_splits", "dream_set_q_tiles", "dream_set_tile_waves", "dream_attn_variants",
     "dream_attn_plan_describe", "dream_stream_read", "dream_kv_commit",
     "dream_tree_expand_workspace", "dream_tree_expand_level", "dream_tree_finalize",
     "dream_attention_entropy_workspace", "dream_attention_entropy", "dream_spec_accept_workspace", "dream_spec_accept",
@@ -69,6 +69,7 @@ def load() -> C.CDLL:
         lib.dream_last_error.restype = C.c_char_p
         lib.dream_set_kv_splits.restype = None
         lib.dream_set_q_tiles.restype = None
+        lib.dream_set_tile_waves.restype = None
         _lib = lib
     return _lib
 
@@ -103,6 +104,10 @@ def dream_set_kv_splits(n_splits: int) -> None:
 
 def dream_set_q_tiles(q_tiles: int) -> None:
     load().dream_set_q_tiles(C.c_int32(q_tiles))
+
+
+def dream_set_tile_waves(waves: int) -> None:
+    load().dream_set_tile_waves(C.c_int32(waves))
 
 
 def dream_stream_read(src: torch.Tensor, nbytes: int, sink: torch.Tensor, offset_bytes: int = 0, stream=None) -> None:

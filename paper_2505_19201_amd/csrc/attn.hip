@@ -105,9 +105,9 @@ __device__ __forceinline__ void state_store(const WaveState<QG, NDT> &s, float *
 struct RowOwner {
     int row, head;
 };
-__device__ __forceinline__ RowOwner row_owner(const AttnArgs &a, int kvh, int qg, int wave, int QG, int qt, int c)
+__device__ __forceinline__ RowOwner row_owner(const AttnArgs &a, int kvh, int qg, int wave, int QG, int qt, int c, int nw = 4)
 {
-    int tq = (qg * 4 + wave) * QG + qt;
+    int tq = (qg * nw + wave) * QG + qt;
     int hh = tq / a.tiles_per_head, nt = tq % a.tiles_per_head;
     int row = nt * 16 + c;
     bool valid = tq < a.group * a.tiles_per_head && row < a.n_q;
@@ -123,39 +123,47 @@ __device__ __forceinline__ RowOwner row_owner(const AttnArgs &a, int kvh, int qg
 #ifndef DREAM_Q1_WAVES
 #define DREAM_Q1_WAVES 2
 #endif
+#ifndef DREAM_W8Q1_WAVES
+#define DREAM_W8Q1_WAVES 1
+#endif
+#ifndef DREAM_W8_PFD
+#define DREAM_W8_PFD 2   // steps in flight of the 8-wave shared-tile form
+#endif
 
 // Online softmax of KT 32-key tiles for the QG query tiles of a wave.  sacc holds the raw scores S^T (lane owns
 // query column c and key rows g*4+r of every 16-key block); on return pf holds the probabilities as the bf16 B
 // operand of O^T += V^T P^T, and the running (reference, sum, accumulators) of `st` are updated.
+// Only the first part depends on whether the step needs the visibility test (one wave-uniform branch per step, not
+// one per score): a step wholly inside the prefix takes the maximum over the raw scores and leaves the scaling to
+// the exponent's fused multiply-add; the general path scales and masks the scores in place.
+// softmax_prepare: visibility test, maxima, and the (rare) raise of the references with the rescaling of the
+// accumulators; returns what still multiplies the stored scores.  softmax_exponentials: the straight-line rest.
 template <int QG, int KT, int NDT>
-__device__ __forceinline__ void softmax_tiles(f32x4 (&sacc)[KT][2][QG], bf16x8 (&pf)[KT][QG], WaveState<QG, NDT> &st,
-                                              const uint64_t (&qmask)[QG], bool needs_mask, int key0, int P, int key_end, int n_tree,
-                                              float scale_log2, int g)
+__device__ __forceinline__ float softmax_prepare(f32x4 (&sacc)[KT][2][QG], WaveState<QG, NDT> &st, const uint64_t (&qmask)[QG],
+                                                 bool needs_mask, int key0, int P, int key_end, int n_tree, float scale_log2, int g)
 {
-    bool raise = false;
+    float mx_q[QG];
+    if (needs_mask) {
 #pragma unroll
-    for (int qt = 0; qt < QG; qt++) {
-        float mx = -INFINITY;
+        for (int qt = 0; qt < QG; qt++) {
+            float mx = -INFINITY;
 #pragma unroll
-        for (int kt = 0; kt < KT; kt++) {
+            for (int kt = 0; kt < KT; kt++) {
 #pragma unroll
-            for (int e = 0; e < 8; e++) {
-                float x = sacc[kt][e >> 2][qt][e & 3] * scale_log2;
-                if (needs_mask) {
+                for (int e = 0; e < 8; e++) {
+                    float x = sacc[kt][e >> 2][qt][e & 3] * scale_log2;
                     const int key = key0 + kt * 32 + (e >> 2) * 16 + g * 4 + (e & 3);
                     const int rel = key - P;
                     const uint32_t bit = (uint32_t)(qmask[qt] >> (rel & 63)) & 1u;
                     const uint32_t vis = ((uint32_t)(rel < 0) | ((uint32_t)(rel < n_tree) & bit)) & (uint32_t)(key < key_end);
                     x = vis ? x : -INFINITY;
+                    sacc[kt][e >> 2][qt][e & 3] = x;
+                    mx = fmaxf(mx, x);
                 }
-                sacc[kt][e >> 2][qt][e & 3] = x;
-                mx = fmaxf(mx, x);
             }
+            mx_q[qt] = mx;
         }
-        raise = raise || (mx > st.m[qt] + DREAM_SOFTMAX_SLACK);
-    }
-    if (__any(raise)) {
-        // rare: some column's reference is raised to the true maximum over its 4 row groups
+    } else {
 #pragma unroll
         for (int qt = 0; qt < QG; qt++) {
             float mx = -INFINITY;
@@ -164,6 +172,19 @@ __device__ __forceinline__ void softmax_tiles(f32x4 (&sacc)[KT][2][QG], bf16x8 (
 #pragma unroll
                 for (int e = 0; e < 8; e++)
                     mx = fmaxf(mx, sacc[kt][e >> 2][qt][e & 3]);
+            mx_q[qt] = mx * scale_log2;   // scale_log2 >= 0 on this path
+        }
+    }
+    const float mult = needs_mask ? 1.0f : scale_log2;   // what still multiplies the stored scores
+    bool raise = false;
+#pragma unroll
+    for (int qt = 0; qt < QG; qt++)
+        raise = raise || (mx_q[qt] > st.m[qt] + DREAM_SOFTMAX_SLACK);
+    if (__any(raise)) {
+        // rare: some column's reference is raised to the true maximum over its 4 row groups
+#pragma unroll
+        for (int qt = 0; qt < QG; qt++) {
+            float mx = mx_q[qt];
             mx = fmaxf(mx, __shfl_xor(mx, 16));
             mx = fmaxf(mx, __shfl_xor(mx, 32));
             if (mx > st.m[qt] + DREAM_SOFTMAX_SLACK) {
@@ -176,15 +197,21 @@ __device__ __forceinline__ void softmax_tiles(f32x4 (&sacc)[KT][2][QG], bf16x8 (
             }
         }
     }
+    return mult;
+}
+
+template <int QG, int KT, int NDT>
+__device__ __forceinline__ void softmax_exponentials(const f32x4 (&sacc)[KT][2][QG], bf16x8 (&pf)[KT][QG], WaveState<QG, NDT> &st, float mult)
+{
 #pragma unroll
     for (int qt = 0; qt < QG; qt++) {
-        const float m_safe = (st.m[qt] == -INFINITY) ? 0.0f : st.m[qt];
+        const float neg_m = (st.m[qt] == -INFINITY) ? 0.0f : -st.m[qt];
         float psum = 0.0f;
 #pragma unroll
         for (int kt = 0; kt < KT; kt++) {
 #pragma unroll
             for (int e = 0; e < 8; e++) {
-                float p = __builtin_amdgcn_exp2f(sacc[kt][e >> 2][qt][e & 3] - m_safe);
+                float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kt][e >> 2][qt][e & 3], mult, neg_m));
                 psum += p;
                 pf[kt][qt][e] = (__bf16)p;
             }
@@ -193,19 +220,13 @@ __device__ __forceinline__ void softmax_tiles(f32x4 (&sacc)[KT][2][QG], bf16x8 (
     }
 }
 
-// QK^T, online softmax and PV for KT consecutive 32-key tiles held in LDS at `stage` (K tile, then V tile,
-// per 32 keys), for the QG query tiles of this wave.  key0 is the global key index of the first row.
+// S^T = K Q^T for the KT 32-key tiles held in LDS at `stage` (K tile, then V tile, per 32 keys) x the (16 * QG) query
+// columns of this wave; independent accumulators keep the MFMA pipe full.
 template <int D, int QG, int KT, int DV = D>
-__device__ __forceinline__ void tiles_compute(const uint16_t *stage, int key0, int P, int key_end, int n_tree, float scale_log2,
-                                              const bf16x8 (&qf)[QG][D / 32], const uint64_t (&qmask)[QG],
-                                              WaveState<QG, DV / 16> &st, int c, int g)
+__device__ __forceinline__ void tiles_scores(const uint16_t *stage, const bf16x8 (&qf)[QG][D / 32], f32x4 (&sacc)[KT][2][QG], int c, int g)
 {
     using G = Geom<D, QG, KT, DV>;
-    constexpr int KSTR = G::KSTR, VSTR = G::VSTR, NDT = G::NDT, NKS = G::NKS;
-    const bool needs_mask = key0 + KT * 32 > min(P, key_end);   // step touches tree rows, the ragged end or the next split
-
-    // ---- S^T = K Q^T for KT*32 keys x (16 * QG) query columns; independent accumulators keep the MFMA pipe full
-    f32x4 sacc[KT][2][QG];
+    constexpr int KSTR = G::KSTR, NKS = G::NKS;
 #pragma unroll
     for (int kt = 0; kt < KT; kt++) {
         const uint16_t *sk = stage + kt * G::TILE_ELEMS;
@@ -229,7 +250,17 @@ __device__ __forceinline__ void tiles_compute(const uint16_t *stage, int key0, i
             }
         }
     }
-    __builtin_amdgcn_sched_barrier(0);
+}
+
+// Online softmax of the raw scores `sacc` of the KT tiles at `stage` (first key key0) and O^T += V^T P^T.
+template <int D, int QG, int KT, int DV = D>
+__device__ __forceinline__ void tiles_softmax_pv(const uint16_t *stage, int key0, int P, int key_end, int n_tree, float scale_log2,
+                                                 f32x4 (&sacc)[KT][2][QG], const uint64_t (&qmask)[QG], WaveState<QG, DV / 16> &st, int c, int g)
+{
+    using G = Geom<D, QG, KT, DV>;
+    constexpr int KSTR = G::KSTR, VSTR = G::VSTR, NDT = G::NDT;
+    // step touches tree rows, the ragged end or the next split (a negative scale also goes the general way)
+    const bool needs_mask = key0 + KT * 32 > min(P, key_end) || scale_log2 < 0.0f;
     // ---- V^T fragments of the first tile (first half of the head dimension for D = 256) are requested
     // now, so their LDS latency hides behind the softmax arithmetic
     constexpr int VH = DV == 256 ? 2 : 1, NDH = NDT / VH;
@@ -246,7 +277,8 @@ __device__ __forceinline__ void tiles_compute(const uint16_t *stage, int key0, i
     read_v(0, 0);
     // ---- online softmax; lane owns query column c and key rows g*4+r of every 16-key block
     bf16x8 pf[KT][QG];
-    softmax_tiles<QG, KT, NDT>(sacc, pf, st, qmask, needs_mask, key0, P, key_end, n_tree, scale_log2, g);
+    const float mult = softmax_prepare<QG, KT, NDT>(sacc, st, qmask, needs_mask, key0, P, key_end, n_tree, scale_log2, g);
+    softmax_exponentials<QG, KT, NDT>(sacc, pf, st, mult);
     // ---- O^T += V^T P^T
 #pragma unroll
     for (int kt = 0; kt < KT; kt++) {
@@ -266,12 +298,29 @@ __device__ __forceinline__ void tiles_compute(const uint16_t *stage, int key0, i
     }
 }
 
-// KT: 32-key tiles handled per step (per barrier, per softmax update); PFD: steps kept in flight in registers.
-template <int D, int QG, int KT, int PFD>
-__global__ __launch_bounds__(256, (QG == 1 && D <= 128) ? DREAM_Q1_WAVES : 1) void attn_bf16_kernel(AttnArgs a)
+// QK^T, online softmax and PV for KT consecutive 32-key tiles held in LDS at `stage`, for the QG query tiles of this
+// wave.  key0 is the global key index of the first row.
+template <int D, int QG, int KT, int DV = D>
+__device__ __forceinline__ void tiles_compute(const uint16_t *stage, int key0, int P, int key_end, int n_tree, float scale_log2,
+                                              const bf16x8 (&qf)[QG][D / 32], const uint64_t (&qmask)[QG],
+                                              WaveState<QG, DV / 16> &st, int c, int g)
+{
+    f32x4 sacc[KT][2][QG];
+    tiles_scores<D, QG, KT, DV>(stage, qf, sacc, c, g);
+    __builtin_amdgcn_sched_barrier(0);
+    tiles_softmax_pv<D, QG, KT, DV>(stage, key0, P, key_end, n_tree, scale_log2, sacc, qmask, st, c, g);
+}
+
+// KT: 32-key tiles handled per step (per barrier, per softmax update); PFD: steps kept in flight in registers;
+// NW: waves per workgroup (4, or 8 when the key range is not split: twice the query tiles share one LDS tile).
+template <int D, int QG, int KT, int PFD, int NW = 4>
+__global__ __launch_bounds__(64 * NW, (QG == 1 && D <= 128) ? (NW == 4 ? DREAM_Q1_WAVES : DREAM_W8Q1_WAVES) : 1) void attn_bf16_kernel(AttnArgs a)
 {
     using G = Geom<D, QG, KT>;
-    constexpr int KSTR = G::KSTR, VSTR = G::VSTR, CH = G::CH, NDT = G::NDT, NKS = G::NKS;
+    constexpr int KSTR = G::KSTR, VSTR = G::VSTR, NDT = G::NDT, NKS = G::NKS;
+    constexpr int CH = 32 * D / 8 / (64 * NW);   // 16-byte chunks per thread per tensor per tile
+    constexpr int ROWS = 64 * NW * 8 / D;        // tile rows one pass of the workgroup covers
+    static_assert(CH >= 1 && CH * ROWS == 32, "a tile is a whole number of passes");
     constexpr int NLD = KT * CH;   // 16-byte chunks per thread per tensor per step
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     uint16_t *lds = reinterpret_cast<uint16_t *>(smem_raw);
@@ -320,7 +369,7 @@ __global__ __launch_bounds__(256, (QG == 1 && D <= 128) ? DREAM_Q1_WAVES : 1) vo
             const int t = min(t_begin + i * KT + kt, t_end - 1);
 #pragma unroll
             for (int j = 0; j < CH; j++) {
-                const int key = min(t * 32 + ld_row + j * (2048 / D), kv_len - 1);
+                const int key = min(t * 32 + ld_row + j * ROWS, kv_len - 1);
                 kr[kt * CH + j] = *reinterpret_cast<const u32x4 *>(kbase + (int64_t)key * D + ld_col * 8);
                 vr[kt * CH + j] = *reinterpret_cast<const u32x4 *>(vbase + (int64_t)key * D + ld_col * 8);
             }
@@ -339,7 +388,7 @@ __global__ __launch_bounds__(256, (QG == 1 && D <= 128) ? DREAM_Q1_WAVES : 1) vo
     bool wave_active = false;
 #pragma unroll
     for (int qt = 0; qt < QG; qt++) {
-        RowOwner ro = row_owner(a, kvh, qg, wave, QG, qt, c);
+        RowOwner ro = row_owner(a, kvh, qg, wave, QG, qt, c, NW);
         q_valid[qt] = ro.row >= 0;
         wave_active = wave_active || q_valid[qt];
         const int row = q_valid[qt] ? ro.row : 0;
@@ -387,8 +436,8 @@ __global__ __launch_bounds__(256, (QG == 1 && D <= 128) ? DREAM_Q1_WAVES : 1) vo
             for (int kt = 0; kt < KT; kt++) {
 #pragma unroll
                 for (int j = 0; j < CH; j++) {
-                    *reinterpret_cast<u32x4 *>(dk + kt * G::TILE_ELEMS + j * (2048 / D) * KSTR) = kr[kt * CH + j];
-                    *reinterpret_cast<u32x4 *>(dv + kt * G::TILE_ELEMS + j * (2048 / D) * VSTR) = vr[kt * CH + j];
+                    *reinterpret_cast<u32x4 *>(dk + kt * G::TILE_ELEMS + j * ROWS * KSTR) = kr[kt * CH + j];
+                    *reinterpret_cast<u32x4 *>(dv + kt * G::TILE_ELEMS + j * ROWS * VSTR) = vr[kt * CH + j];
                 }
             }
         }
@@ -426,8 +475,8 @@ __global__ __launch_bounds__(256, (QG == 1 && D <= 128) ? DREAM_Q1_WAVES : 1) vo
         l += __shfl_xor(l, 32);
         st.l[qt] = l;
     }
-    if (nsplit > 1) {
-        // several splits: publish this wave's state for attn_merge_kernel
+    if (NW == 4 && nsplit > 1) {
+        // several splits: publish this wave's state for attn_merge_kernel (the launch plan never splits the 8-wave form)
         const int64_t grp = ((int64_t)b * a.n_kv_heads + kvh) * a.n_qg + qg;
         state_store<QG, NDT>(st, a.part + ((grp * nsplit + split) * 4 + wave) * StateGeom<D, QG>::STATE_FLOATS, lane);
         return;
@@ -435,7 +484,7 @@ __global__ __launch_bounds__(256, (QG == 1 && D <= 128) ? DREAM_Q1_WAVES : 1) vo
     constexpr float LN2 = 0.6931471805599453f;
 #pragma unroll
     for (int qt = 0; qt < QG; qt++) {
-        RowOwner ro = row_owner(a, kvh, qg, wave, QG, qt, c);
+        RowOwner ro = row_owner(a, kvh, qg, wave, QG, qt, c, NW);
         if (ro.row < 0)
             continue;
         const float l = st.l[qt];
@@ -819,6 +868,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(AttnArgs a, int D)
 // ------------------------------------------------------------------------------------------------
 struct Plan {
     int tiles_per_head, qg, n_qg, n_splits, n_streams, grid, n_groups, kt, pfd;
+    int nw;           // waves per workgroup of the shared-tile kernel (4 or 8)
     bool wave_mode;   // one query tile per workgroup, waves split the keys, no key split (attn_wave_kernel)
     int wave_nw;      // waves per workgroup in that mode
     int wave_ds;      // workgroups that share the output columns of a query tile in that mode (1, 2 or 4)
@@ -856,12 +906,13 @@ int make_plan(const dream_attn_desc *d, int n_q, int64_t max_kv_len, Plan *p)
     if (qg != 1 && qg != 2 && qg != 4)
         qg = 1;
     p->qg = qg;
+    p->nw = 4;
     p->n_qg = ceil_div(n_qtiles, 4 * qg);
     // few, short streams with at most 16 query tiles each: a workgroup per query tile fills at least half the chip
     // without splitting keys, which saves the merge launch (short: up to 64 key tiles at head_dim 128, twice that
     // at 64: the measured crossover against the key-split path, which comes a little later for grouped-query
     // shapes because their split states are larger)
-    p->wave_mode = q_tiles_override() == 0 && kv_splits_override() == 0 &&
+    p->wave_mode = q_tiles_override() == 0 && kv_splits_override() == 0 && tile_waves_override() == 0 &&
                    d->dtype == DREAM_BF16 && n_qtiles <= 16 && G <= 4 && base * n_qtiles <= 512 && base * n_qtiles >= 32 &&
                    (base * n_qtiles <= 256 || d->head_dim <= 128) && (int64_t)tiles * d->head_dim <= (G > 1 ? 12288 : 8192) &&
                    d->s_max * d->head_dim < (1ll << 31);
@@ -888,7 +939,25 @@ int make_plan(const dream_attn_desc *d, int n_q, int64_t max_kv_len, Plan *p)
         p->total = DREAM_WORKSPACE_MIN_BYTES;
         return 0;
     }
+    // grouped-query shapes with enough streams to give every CU a workgroup without splitting keys: 8 waves share
+    // one LDS tile, so the 8-16 query tiles of a KV head are served by ONE workgroup (K/V leave L2 once per head
+    // instead of once per 4 query tiles) while the CU still holds 8 waves.  head_dim 64 tiles are too small to
+    // spread over 512 threads; with more than 16 (8 at head_dim 256) query tiles a KV head takes several workgroups.
+    {
+        const int tw = tile_waves_override();
+        const int qg8_max = d->head_dim == 256 ? 1 : 2;
+        int qg8 = q_tiles_override() > 0 ? (q_tiles_override() > qg8_max ? qg8_max : q_tiles_override()) : (n_qtiles > 8 ? qg8_max : 1);
+        const bool can8 = d->dtype == DREAM_BF16 && d->head_dim >= 128 && kv_splits_override() <= 1 && tw != 4;
+        const bool want8 = tw == 8 || (q_tiles_override() == 0 && n_qtiles > 4 && base * ceil_div(n_qtiles, 8 * qg8) >= 256);
+        if (can8 && want8) {
+            p->nw = 8;
+            p->qg = qg = qg8;
+            p->n_qg = ceil_div(n_qtiles, 8 * qg8);
+        }
+    }
     int s = kv_splits_override();
+    if (p->nw == 8)
+        s = 1;
     if (s <= 0) {
         s = ceil_div(256, base * p->n_qg);   // one workgroup per CU before anything is split further
         if (s > 8)
@@ -899,7 +968,7 @@ int make_plan(const dream_attn_desc *d, int n_q, int64_t max_kv_len, Plan *p)
     if (s < 1)
         s = 1;
     const int64_t groups = base * p->n_qg;
-    if (groups * qg * 4 > 0x7fffffff)
+    if (groups * qg * p->nw > 0x7fffffff)
         s = 1;
     p->n_splits = s;
     p->n_groups = (int)groups;
@@ -918,6 +987,10 @@ int make_plan(const dream_attn_desc *d, int n_q, int64_t max_kv_len, Plan *p)
         // longer fit the 512 registers of a wave (same speed, no spills)
         if ((qg == 4 && d->head_dim == 128) || (qg == 2 && d->head_dim == 256))
             p->pfd = 1;
+    }
+    if (p->nw == 8) {
+        p->kt = 1;
+        p->pfd = DREAM_W8_PFD;
     }
     p->state_floats = (size_t)qg * (d->head_dim / 16) * 256 + (size_t)qg * 2 * 64;
     p->off_part = DREAM_WORKSPACE_MIN_BYTES;
@@ -946,13 +1019,13 @@ int validate_desc(const dream_attn_desc *d, const char *who)
 
 // The dynamic-LDS limit of a kernel is raised once (dream_init does it for every variant up front; a variant
 // that is reached first by a call does it then).  Two threads may both set it once: harmless.
-template <int D, int QG, int KT, int PFD>
+template <int D, int QG, int KT, int PFD, int NW = 4>
 int ensure_bf16_lds()
 {
     using G = Geom<D, QG, KT>;
     static std::atomic<bool> attr_set{false};
     if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_kernel<D, QG, KT, PFD>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_kernel<D, QG, KT, PFD, NW>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)G::LDS_BYTES) != hipSuccess)
             return fail(DREAM_ERR_HIP, "attention: cannot reserve %zu bytes of LDS", G::LDS_BYTES);
         attr_set = true;
@@ -960,13 +1033,15 @@ int ensure_bf16_lds()
     return DREAM_OK;
 }
 
-template <int D, int QG, int KT, int PFD>
+template <int D, int QG, int KT, int PFD, int NW = 4>
 int launch_bf16(const AttnArgs &a, const Plan &p, hipStream_t st)
 {
     using G = Geom<D, QG, KT>;
-    if (int rc = ensure_bf16_lds<D, QG, KT, PFD>())
+    if (int rc = ensure_bf16_lds<D, QG, KT, PFD, NW>())
         return rc;
-    hipLaunchKernelGGL((attn_bf16_kernel<D, QG, KT, PFD>), dim3(p.grid), dim3(256), G::LDS_BYTES, st, a);
+    if (NW != 4 && p.n_splits != 1)
+        return fail(DREAM_ERR_INVALID_ARG, "attention: the 8-wave shared-tile kernel does not split the key range");
+    hipLaunchKernelGGL((attn_bf16_kernel<D, QG, KT, PFD, NW>), dim3(p.grid), dim3(64 * NW), G::LDS_BYTES, st, a);
     int rc = check_launch("attn_bf16_kernel");
     if (rc || p.n_splits == 1)
         return rc;
@@ -1013,12 +1088,13 @@ int launch_wave(const AttnArgs &a, const Plan &p, hipStream_t st)
 // its dynamic-LDS limit.  The launch, dream_init, dream_attn_plan_describe and dream_attn_variants all read it.
 enum { FAMILY_TILE = 0, FAMILY_WAVE = 1 };
 struct Variant {
-    int family, d, p1, p2, p3;   // tile: (QG, KT, PFD); wave: (NW, DS, QT)
+    int family, d, p1, p2, p3, p4;   // tile: (QG, KT, PFD, waves); wave: (NW, DS, QT, 0)
     int (*launch)(const AttnArgs &, const Plan &, hipStream_t);
     int (*ensure)();
 };
-#define TILE_VARIANT(D, QG, KT, PFD) {FAMILY_TILE, D, QG, KT, PFD, &launch_bf16<D, QG, KT, PFD>, &ensure_bf16_lds<D, QG, KT, PFD>}
-#define WAVE_VARIANT(D, NW, DS, QT) {FAMILY_WAVE, D, NW, DS, QT, &launch_wave<D, NW, DS, QT>, &ensure_wave_lds<D, NW, DS, QT>}
+#define TILE_VARIANT(D, QG, KT, PFD) {FAMILY_TILE, D, QG, KT, PFD, 4, &launch_bf16<D, QG, KT, PFD>, &ensure_bf16_lds<D, QG, KT, PFD>}
+#define TILE8_VARIANT(D, QG, KT, PFD) {FAMILY_TILE, D, QG, KT, PFD, 8, &launch_bf16<D, QG, KT, PFD, 8>, &ensure_bf16_lds<D, QG, KT, PFD, 8>}
+#define WAVE_VARIANT(D, NW, DS, QT) {FAMILY_WAVE, D, NW, DS, QT, 0, &launch_wave<D, NW, DS, QT>, &ensure_wave_lds<D, NW, DS, QT>}
 const Variant VARIANTS[] = {
     // shared-tile kernel, one query tile per wave: a short key range in one step (2-4 tiles), or streamed
     TILE_VARIANT(64, 1, 2, 1), TILE_VARIANT(64, 1, 3, 1), TILE_VARIANT(64, 1, 4, 1), TILE_VARIANT(64, 1, 2, 2),
@@ -1026,6 +1102,8 @@ const Variant VARIANTS[] = {
     TILE_VARIANT(256, 1, 1, 2),
     // several query tiles per wave
     TILE_VARIANT(64, 2, 1, 2), TILE_VARIANT(64, 4, 1, 2), TILE_VARIANT(128, 2, 1, 2), TILE_VARIANT(128, 4, 1, 1), TILE_VARIANT(256, 2, 1, 1),
+    // 8 waves per workgroup (unsplit key range, grouped queries): a fifth name argument 8
+    TILE8_VARIANT(128, 1, 1, DREAM_W8_PFD), TILE8_VARIANT(128, 2, 1, DREAM_W8_PFD), TILE8_VARIANT(256, 1, 1, DREAM_W8_PFD),
     // single-launch wave kernel: (waves, column slices, query tiles per workgroup); split output columns always come
     // with 8 waves at head_dim <= 128
     WAVE_VARIANT(64, 8, 1, 1), WAVE_VARIANT(64, 8, 2, 1), WAVE_VARIANT(64, 4, 1, 1),
@@ -1035,6 +1113,7 @@ const Variant VARIANTS[] = {
     WAVE_VARIANT(256, 4, 1, 1), WAVE_VARIANT(256, 4, 2, 1), WAVE_VARIANT(256, 4, 4, 1),
 };
 #undef TILE_VARIANT
+#undef TILE8_VARIANT
 #undef WAVE_VARIANT
 constexpr int N_VARIANTS = sizeof(VARIANTS) / sizeof(VARIANTS[0]);
 
@@ -1043,9 +1122,10 @@ const Variant *find_variant(const dream_attn_desc *d, const Plan &p)
 {
     const int family = p.wave_mode ? FAMILY_WAVE : FAMILY_TILE;
     const int p1 = p.wave_mode ? p.wave_nw : p.qg, p2 = p.wave_mode ? p.wave_ds : p.kt, p3 = p.wave_mode ? p.wave_qt : p.pfd;
+    const int p4 = p.wave_mode ? 0 : p.nw;
     for (int i = 0; i < N_VARIANTS; i++) {
         const Variant &v = VARIANTS[i];
-        if (v.family == family && v.d == d->head_dim && v.p1 == p1 && v.p2 == p2 && v.p3 == p3)
+        if (v.family == family && v.d == d->head_dim && v.p1 == p1 && v.p2 == p2 && v.p3 == p3 && v.p4 == p4)
             return &v;
     }
     return nullptr;
@@ -1055,6 +1135,8 @@ void variant_name(const Variant &v, char *buf, size_t n)
 {
     if (v.family == FAMILY_WAVE)
         snprintf(buf, n, "attn_wave_kernel<%d,%d,%d,%d>", v.d, v.p1, v.p2, v.p3);
+    else if (v.p4 != 4)
+        snprintf(buf, n, "attn_bf16_kernel<%d,%d,%d,%d,%d>", v.d, v.p1, v.p2, v.p3, v.p4);
     else
         snprintf(buf, n, "attn_bf16_kernel<%d,%d,%d,%d>", v.d, v.p1, v.p2, v.p3);
 }

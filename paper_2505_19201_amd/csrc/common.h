@@ -19,6 +19,7 @@ inline int ceil_div(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 
 int kv_splits_override();
 int q_tiles_override();
+int tile_waves_override();
 
 // per-file parts of dream_init()
 int attn_init();

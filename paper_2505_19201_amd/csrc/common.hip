@@ -9,6 +9,7 @@ namespace dream {
 static thread_local char g_error[512] = "";
 static std::atomic<int> g_kv_splits{0};
 static std::atomic<int> g_q_tiles{0};
+static std::atomic<int> g_tile_waves{0};
 
 char *error_buffer() { return g_error; }
 
@@ -31,6 +32,7 @@ int check_launch(const char *what)
 
 int kv_splits_override() { return g_kv_splits.load(std::memory_order_relaxed); }
 int q_tiles_override() { return g_q_tiles.load(std::memory_order_relaxed); }
+int tile_waves_override() { return g_tile_waves.load(std::memory_order_relaxed); }
 
 // Reads n16 16-byte words once, grid-stride, and folds them into one word per thread; the fold is stored only
 // if it equals a value the caller does not expect, which keeps the loads alive without a write stream.
@@ -56,6 +58,8 @@ const char *dream_last_error(void) { return error_buffer(); }
 void dream_set_kv_splits(int32_t n_splits) { dream::g_kv_splits.store(n_splits < 0 ? 0 : n_splits, std::memory_order_relaxed); }
 
 void dream_set_q_tiles(int32_t q_tiles) { dream::g_q_tiles.store(q_tiles < 0 ? 0 : q_tiles, std::memory_order_relaxed); }
+
+void dream_set_tile_waves(int32_t waves) { dream::g_tile_waves.store(waves == 4 || waves == 8 ? waves : 0, std::memory_order_relaxed); }
 
 int dream_init(void)
 {

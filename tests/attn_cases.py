@@ -7,7 +7,8 @@ from collections import namedtuple
 import dream_inputs as di
 
 # kv_len = prefix + n_tree is the longest sequence of the case; shorter ones are mixed in by the GPU test.
-VariantCase = namedtuple("VariantCase", "variant batch n_q_heads n_kv_heads head_dim n_tree depth kv_len splits q_tiles")
+# splits / q_tiles / waves are the launch-shape overrides the case needs (0 = automatic).
+VariantCase = namedtuple("VariantCase", "variant batch n_q_heads n_kv_heads head_dim n_tree depth kv_len splits q_tiles waves", defaults=(0,))
 
 VARIANT_CASES = [
     VariantCase("attn_bf16_kernel<64,1,2,1>", 1, 2, 2, 64, 17, 4, 150, 0, 0),
@@ -24,6 +25,10 @@ VARIANT_CASES = [
     VariantCase("attn_bf16_kernel<128,2,1,2>", 1, 2, 2, 128, 60, 6, 150, 0, 2),
     VariantCase("attn_bf16_kernel<128,4,1,1>", 2, 8, 2, 128, 60, 6, 150, 0, 4),
     VariantCase("attn_bf16_kernel<256,2,1,1>", 1, 4, 2, 256, 60, 6, 150, 0, 2),
+    # 8 waves per workgroup: 8 query tiles of a KV head (one per wave), 16 (two per wave), head_dim 256
+    VariantCase("attn_bf16_kernel<128,1,1,2,8>", 2, 4, 2, 128, 60, 6, 150, 0, 0, 8),
+    VariantCase("attn_bf16_kernel<128,2,1,2,8>", 2, 8, 2, 128, 60, 6, 150, 0, 0, 8),
+    VariantCase("attn_bf16_kernel<256,1,1,2,8>", 2, 4, 2, 256, 60, 6, 150, 0, 0, 8),
     VariantCase("attn_wave_kernel<64,8,1,1>", 3, 24, 8, 64, 17, 4, 1340, 0, 0),
     VariantCase("attn_wave_kernel<64,8,2,1>", 8, 2, 2, 64, 17, 4, 150, 0, 0),
     VariantCase("attn_wave_kernel<64,4,1,1>", 3, 24, 8, 64, 17, 4, 150, 0, 0),
@@ -48,6 +53,21 @@ FULL_VERIFY_PLANS = {
     "smolvlm_b1": "attn_wave_kernel<64,8,2,1> workgroups=256 splits=1 merge_launch=0",
     "smolvlm_b8": "attn_bf16_kernel<64,1,2,2> workgroups=256 splits=1 merge_launch=0",
     "smolvlm_b32": "attn_bf16_kernel<64,1,2,2> workgroups=1024 splits=1 merge_launch=0",
+}
+
+# 8-wave shapes beyond the one-case-per-variant list: idle waves (6 query tiles), two workgroups per KV head (20 query
+# tiles), and a long ragged key range
+EXTRA_W8_CASES = [
+    VariantCase("attn_bf16_kernel<128,1,1,2,8>", 2, 6, 2, 128, 17, 4, 700, 0, 0, 8),
+    VariantCase("attn_bf16_kernel<128,2,1,2,8>", 1, 10, 2, 128, 60, 6, 333, 0, 0, 8),
+    VariantCase("attn_bf16_kernel<256,1,1,2,8>", 3, 6, 2, 256, 33, 5, 410, 0, 0, 8),
+]
+
+# The 32-sequence launches bench.py times as the streaming regime of the grouped-query configurations
+STREAMING_PLANS = {
+    "llava": "attn_bf16_kernel<128,1,1,2> workgroups=1024 splits=1 merge_launch=0",
+    "pixtral": "attn_bf16_kernel<128,2,1,2,8> workgroups=256 splits=1 merge_launch=0",
+    "gemma3": "attn_bf16_kernel<256,1,1,2,8> workgroups=256 splits=1 merge_launch=0",
 }
 
 # dream_draft_xattn at each full-size configuration: (plan of the root call, plan of a 10-row level call)

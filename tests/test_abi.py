@@ -128,22 +128,25 @@ def test_every_attention_kernel_variant_has_a_parity_case(lib):
     """The GPU suite runs tests/attn_cases.VARIANT_CASES all elements against the oracle; here, without a GPU: the
     list names every variant the library can dispatch to, and each case's shape really plans its variant."""
     import dream_inputs as di
-    from tests.attn_cases import FULL_VERIFY_PLANS, FULL_XATTN_PLANS, VARIANT_CASES, variant_config, variant_prefix_lens
+    from tests.attn_cases import (EXTRA_W8_CASES, FULL_VERIFY_PLANS, FULL_XATTN_PLANS, STREAMING_PLANS, VARIANT_CASES, variant_config,
+                                  variant_prefix_lens)
     built = dream.dream_attn_variants()
     assert len(built) == len(set(built))
     assert sorted(c.variant for c in VARIANT_CASES) == sorted(built)
-    for case in VARIANT_CASES:
+    for case in VARIANT_CASES + EXTRA_W8_CASES:
         cfg = variant_config(case)
         pl = variant_prefix_lens(case)
         assert max(pl) == pl[0] == case.kv_len - case.n_tree and min(pl) >= 0
         dream.dream_set_kv_splits(case.splits)
         dream.dream_set_q_tiles(case.q_tiles)
+        dream.dream_set_tile_waves(case.waves)
         try:
             desc = dream.attn_desc(cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, dream.BF16, case.kv_len + 5)
             plan = dream.dream_attn_plan_describe(desc, case.n_tree, case.kv_len)
         finally:
             dream.dream_set_kv_splits(0)
             dream.dream_set_q_tiles(0)
+            dream.dream_set_tile_waves(0)
         assert plan.startswith(case.variant + " "), (case, plan)
     for name, want in FULL_VERIFY_PLANS.items():
         cfg = di.CONFIGS[name]
@@ -153,6 +156,11 @@ def test_every_attention_kernel_variant_has_a_parity_case(lib):
         for n_q, want_x in zip((1, 10), FULL_XATTN_PLANS[name]):
             assert dream.dream_attn_plan_describe(desc, n_q, S) == want_x, (name, n_q)
         assert want.split(" ")[0] in built
+    for name, want in STREAMING_PLANS.items():
+        cfg = di.CONFIGS[name].with_batch(32)
+        S = cfg.prefix + cfg.n_tree
+        desc = dream.attn_desc(cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, dream.BF16, S)
+        assert dream.dream_attn_plan_describe(desc, cfg.n_tree, S) == want, name
 
 
 def test_kv_commit_argument_errors(lib):

@@ -5,7 +5,8 @@ import pytest
 
 import dream_inputs as di
 import oracle
-from tests.attn_cases import FULL_VERIFY_PLANS, FULL_XATTN_PLANS, VARIANT_CASES, variant_config, variant_prefix_lens
+from tests.attn_cases import (EXTRA_W8_CASES, FULL_VERIFY_PLANS, FULL_XATTN_PLANS, STREAMING_PLANS, VARIANT_CASES, variant_config,
+                              variant_prefix_lens)
 
 pytestmark = pytest.mark.gpu
 
@@ -109,7 +110,7 @@ def test_outputs_are_reproducible_bit_for_bit(gu):
     assert np.array_equal(a, b) and np.array_equal(la, lb)
 
 
-@pytest.mark.parametrize("case", VARIANT_CASES, ids=[c.variant for c in VARIANT_CASES])
+@pytest.mark.parametrize("case", VARIANT_CASES + EXTRA_W8_CASES, ids=[c.variant for c in VARIANT_CASES] + ["extra-" + c.variant for c in EXTRA_W8_CASES])
 def test_every_kernel_variant_all_elements(gu, case):
     """One case per bf16 kernel variant the launch plan can choose (tests/test_abi.py checks the list is complete):
     the plan must name that variant, and every output element and log-sum-exp must match the oracle."""
@@ -118,12 +119,14 @@ def test_every_kernel_variant_all_elements(gu, case):
     x = di.verify_inputs(cfg, prefix_len=variant_prefix_lens(case))
     dream.dream_set_kv_splits(case.splits)
     dream.dream_set_q_tiles(case.q_tiles)
+    dream.dream_set_tile_waves(case.waves)
     try:
         assert gu.verify_plan(x).startswith(case.variant + " "), gu.verify_plan(x)
         got, lse = gu.run_verify(x)
     finally:
         dream.dream_set_kv_splits(0)
         dream.dream_set_q_tiles(0)
+        dream.dream_set_tile_waves(0)
     want, want_lse = oracle.tree_attn(x.q, x.k, x.v, "bf16", x.prefix_len, x.parent, True)
     assert np.isfinite(got).all()
     assert np.abs(got - want).max() <= TOL["bf16"], np.abs(got - want).max()
