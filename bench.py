@@ -545,12 +545,21 @@ def cpu_baseline(cfg, L, tokens_per_step):
 
     threads = min(16, oracle.hw_threads())
     step_s, parts = timed(threads, True)
+    # the other reading of Section 3.3's score (a token's own attention weight left out): how many kept indices change
+    oracle.set_threads(threads)
+    sc_a = oracle.visual_scores(pq, sub(x.k), cfg.dtype, 0, cfg.n_visual)
+    sc_b = oracle.visual_scores(pq, sub(x.k), cfg.dtype, 0, cfg.n_visual, include_diag=False)
+    oracle.set_threads(1)
+    kept_a, kept_b = oracle.topk_keep(sc_a, 0, cfg.keep_num, cfg.keep_den), oracle.topk_keep(sc_b, 0, cfg.keep_num, cfg.keep_den)
+    diag_report = {"sequences": nb, "kept_per_sequence": int(kept_a.shape[1]),
+                   "kept_indices_that_change": int(sum(len(set(kept_a[b]) - set(kept_b[b])) for b in range(nb)))}
     step_1, parts_1 = timed(1, cfg.batch == 1)    # (the single-threaded compression of a batch would take minutes)
     return {"value": round(tokens_per_step / step_s, 3), "unit": "tokens/s", "cores": threads, "kind": "oracle",
             "step_s": round(step_s, 3), "host_nproc": os.cpu_count(), "host_hw_threads_seen_by_openmp": oracle.hw_threads(),
             "sample": f"{nb} of {cfg.batch} sequences; 1 of {L} verification layers timed and scaled by {L}; "
                       f"6 cross-attention calls and acceptance timed in full; compression (per request) timed beside the step",
             "parts_s": parts,
+            "exclude_diagonal_reading": diag_report,
             "single_thread": {"value": round(tokens_per_step / step_1, 3), "unit": "tokens/s", "cores": 1, "step_s": round(step_1, 3),
                               "parts_s": parts_1}}
 

@@ -23,12 +23,40 @@ _DT = {"f32": F32, "bf16": BF16}
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (-O2, OpenMP for the batched loops)."""
+    if os.environ.get("DREAM_ORACLE_UBSAN") == "1":
+        return build_sanitized()["library"]
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         tmp = _LIB + ".tmp.%d" % os.getpid()
         subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-Wall", "-Wextra",
                                "-o", tmp, _SRC, "-lm"])
         os.replace(tmp, _LIB)
     return _LIB
+
+
+def build_sanitized(run_selftest: bool = False) -> dict:
+    """Host-side sanitizer builds of the oracle (gcc; nothing here touches a GPU):
+    - oracle/selftest_asan: dream_oracle.c + selftest.c as an executable under -fsanitize=address,undefined; it calls
+      every entry point on exact-size heap buffers (an AddressSanitizer library cannot be loaded into an interpreter
+      that was not started with it, hence the separate executable);
+    - oracle/liboracle_ubsan.so: the shared library under -fsanitize=undefined with errors fatal; the test suite uses it
+      when DREAM_ORACLE_UBSAN=1 is set in the environment."""
+    exe = os.path.join(_HERE, "selftest_asan")
+    ubsan = os.path.join(_HERE, "liboracle_ubsan.so")
+    common = ["-O1", "-g", "-std=c11", "-fopenmp", "-Wall", "-Wextra", "-fno-omit-frame-pointer"]
+    subprocess.check_call(["gcc", *common, "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-o", exe,
+                           _SRC, os.path.join(_HERE, "selftest.c"), "-lm"])
+    tmp = ubsan + ".tmp.%d" % os.getpid()
+    subprocess.check_call(["gcc", *common, "-fPIC", "-shared", "-fsanitize=undefined", "-fno-sanitize-recover=all",
+                           "-o", tmp, _SRC, "-lm"])
+    os.replace(tmp, ubsan)
+    out = {"selftest": exe, "library": ubsan}
+    if run_selftest:
+        env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+        p = subprocess.run([exe], env=env, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        out["selftest_output"] = p.stdout
+        if p.returncode != 0:
+            raise RuntimeError("oracle selftest under AddressSanitizer/UBSan failed:\n" + p.stdout)
+    return out
 
 
 _lib = None

@@ -137,3 +137,30 @@ def test_gather_rows_is_a_row_copy():
     got = oracle.gather_rows(src, "bf16", kept)
     for b in range(2):
         assert np.array_equal(got[b], src[b, kept[b]])
+
+
+@pytest.mark.parametrize("name", ["llava", "pixtral", "gemma3", "smolvlm_b1"])
+def test_diagonal_reading_report(name, record_property, capsys):
+    """Section 3.3 sums a token's attention weights "across all other tokens"; the library includes the diagonal term
+    A_jj (a reading of this build).  This reports, on the seeded full-size inputs, how many kept indices change when
+    the diagonal is excluded, and checks what must hold either way: the two scores differ by the diagonal terms, one in
+    [0, 1] per head."""
+    cfg = di.CONFIGS[name]
+    q, k = di.prefill_q(cfg), di.verify_inputs(cfg).k
+    oracle.set_threads(8)
+    try:
+        with_diag = oracle.visual_scores(q, k, cfg.dtype, 0, cfg.n_visual)
+        without = oracle.visual_scores(q, k, cfg.dtype, 0, cfg.n_visual, include_diag=False)
+    finally:
+        oracle.set_threads(1)
+    gap = with_diag - without
+    assert (gap >= -1e-12).all() and (gap <= cfg.n_q_heads + 1e-12).all()
+    kept_a = oracle.topk_keep(with_diag, 0, cfg.keep_num, cfg.keep_den)
+    kept_b = oracle.topk_keep(without, 0, cfg.keep_num, cfg.keep_den)
+    assert kept_a.shape == kept_b.shape
+    changed = int(sum(len(set(kept_a[b]) - set(kept_b[b])) for b in range(cfg.batch)))
+    record_property("kept", int(kept_a.shape[1]))
+    record_property("kept_indices_that_change_without_the_diagonal", changed)
+    with capsys.disabled():
+        print(f"\n[diagonal reading] {name}: {kept_a.shape[1]} of {cfg.n_visual} visual tokens kept; "
+              f"{changed} kept indices change when A_jj is excluded")
