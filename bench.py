@@ -103,7 +103,10 @@ def main() -> int:
                 continue
             torch.cuda.empty_cache()
             r = run_config(torch, dream, di, args, di.CONFIGS[name], steps=max(5, min(args.steps, 20)), warmup=3, full=False)
-            out["configs"][name] = {"step_latency_us": r["step_latency_us"], "tokens_per_s": r["value"],
+            if di.CONFIGS[name].batch == 1:
+                torch.cuda.empty_cache()
+                r["streaming_regime"] = streaming_regime(torch, dream, di, di.CONFIGS[name], iters=20, warm=40)
+            out["configs"][name] = {"step_latency_us": r["step_latency_us"], "tokens_per_s": r["value"], "streaming_regime": r.get("streaming_regime"),
                                     "tokens_per_s_at_paper_tau": r["tokens_per_s_at_paper_tau"], "phase_us": r["phase_us"],
                                     "per_request_us": r["per_request_us"], "roofline": r["roofline"], "read_ceiling": r["read_ceiling"],
                                     "workload": r["config"]["workload"]}
@@ -495,9 +498,11 @@ def streaming_regime(torch, dream, di, cfg, batch=32, iters=40, warm=60):
     us = e0.elapsed_time(e1) * 1e3 / iters
     nbytes = verify_bytes_per_launch(big)
     gbs = nbytes / us / 1e3
+    tflops = 4.0 * B * Hq * T * S * D / us / 1e6   # QK^T and PV, 2 flops per multiply-add, over all (row, key) pairs
     return {"workload": f"{big.name}: same shape, {B} sequences per launch", "bytes_per_launch": nbytes,
+            "kernel": dream.dream_attn_plan_describe(desc, T, S),
             "launch_us": round(us, 2), "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": round(gbs / HBM_PEAK_GBS, 4)}
+            "frac": round(gbs / HBM_PEAK_GBS, 4), "mfma_tflops": round(tflops, 1), "mfma_frac_of_2500": round(tflops / 2500.0, 4)}
 
 
 def cpu_baseline(cfg, L, tokens_per_step):
