@@ -59,7 +59,7 @@ typedef enum {
 } dream_status;
 
 #define DREAM_WORKSPACE_MIN_BYTES 256
-#define DREAM_MAX_TREE 64       /* tree nodes per sequence handled by the attention calls      */
+#define DREAM_MAX_TREE 256      /* tree nodes per sequence handled by the attention calls      */
 #define DREAM_MAX_TREE_ACCEPT 1024 /* tree nodes per sequence handled by dream_accept_path     */
 #define DREAM_MAX_TREE_WIDTH 16     /* children per node / frontier rows of one tree-expansion level */
 #define DREAM_MAX_POOL 1024         /* candidates (root included) dream_tree_finalize ranks */
@@ -83,9 +83,9 @@ typedef struct {
  *   v_cache    [B, Hkv, s_max, D]
  *   prefix_len [B] int32            P_b
  *   parent     [B, n_tree] int32
- *   tree_mask  nullable, [B, n_tree] uint64: bit a of word i set iff tree node a is visible to
- *              node i.  When given it replaces the mask derived from `parent`
- *              (node i sees itself and its ancestors).
+ *   tree_mask  nullable, [B, n_tree, W] uint64 with W = ceil(n_tree / 64) words per node: bit (a % 64)
+ *              of word a / 64 of node i set iff tree node a is visible to node i.  When given it
+ *              replaces the mask derived from `parent` (node i sees itself and its ancestors).
  *   max_kv_len host-known upper bound of P_b + n_tree over the batch (<= s_max); only used to
  *              choose the launch shape, pass s_max if unknown.
  *   out        [B, n_tree, Hq, D]   same dtype as q
@@ -329,6 +329,8 @@ const char *dream_last_error(void);
 /* Host-only: writes a short description of the launch plan the attention calls would use for n_q query
  * rows per sequence and keys up to max_kv_len (kernel and its template arguments, workgroups, key splits,
  * whether a merge launch follows) into buf (NUL-terminated, truncated to buf_bytes).  Needs no GPU.
+ * More than 64 query rows are taken as a verification call over a tree of n_q nodes (the plan of a tree above 64
+ * nodes differs: four mask words per node, see DREAM_MAX_TREE).
  * DREAM_OK, or DREAM_ERR_INVALID_ARG / DREAM_ERR_UNSUPPORTED for a descriptor the attention calls reject. */
 int dream_attn_plan_describe(const dream_attn_desc *desc, int32_t n_q, int64_t max_kv_len, char *buf,
                              size_t buf_bytes);

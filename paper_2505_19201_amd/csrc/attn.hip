@@ -39,7 +39,7 @@ namespace {
 struct AttnArgs {
     const void *q, *k, *v;
     const int32_t *prefix_len, *parent, *q_node;
-    const uint64_t *tree_mask;
+    const uint64_t *tree_mask;   // [B, n_tree, mask_words] when given
     void *out;
     float *lse;
     float *part;             // [groups, splits, 4 waves, state] per-wave states of every split
@@ -47,19 +47,74 @@ struct AttnArgs {
     int32_t n_q, n_tree, include_self;
     int32_t tiles_per_head;  // 16-row query tiles per head
     int32_t n_qg;            // query groups per KV head
+    int32_t mask_words;      // 64-bit words of a node's visibility mask: ceil(n_tree / 64)
     int32_t n_splits;
     int32_t n_streams;       // B * Hkv * n_splits
     int64_t s_max;
     float scale, scale_log2;
 };
 
-__device__ __forceinline__ uint64_t visible_nodes(const AttnArgs &a, int b, int node, const int32_t *lds_parent)
+// Visibility of the tree nodes to one query: bit (a % 64) of word a / 64 is set iff node a is visible.  MW = 1 serves
+// trees of up to 64 nodes, MW = 4 up to 256.
+template <int MW>
+struct NodeMask {
+    uint64_t w[MW];
+};
+
+template <int MW>
+__device__ __forceinline__ void mask_set(NodeMask<MW> &m, int node)
 {
-    if (a.tree_mask)
-        return a.tree_mask[(int64_t)b * a.n_tree + node];
-    uint64_t m = a.include_self ? (1ull << node) : 0ull;
+    if (MW == 1) {
+        m.w[0] |= 1ull << node;
+    } else {
+#pragma unroll
+        for (int i = 0; i < MW; i++)
+            m.w[i] |= (node >> 6) == i ? 1ull << (node & 63) : 0ull;
+    }
+}
+
+// bit `rel` of the mask (the caller has already excluded rel outside [0, n_tree))
+template <int MW>
+__device__ __forceinline__ uint32_t mask_bit(const NodeMask<MW> &m, int rel)
+{
+    if (MW == 1)
+        return (uint32_t)(m.w[0] >> (rel & 63)) & 1u;
+    // (kept as arithmetic on all words: a per-lane choice of the word would become an indexed private array)
+    uint32_t bit = 0u;
+#pragma unroll
+    for (int i = 0; i < MW; i++)
+        bit |= (uint32_t)(m.w[i] >> (rel & 63)) & (uint32_t)((rel >> 6) == i);
+    return bit & 1u;
+}
+
+template <int MW>
+__device__ __forceinline__ NodeMask<MW> visible_nodes(const AttnArgs &a, int b, int node, const int32_t *lds_parent)
+{
+    NodeMask<MW> m;
+#pragma unroll
+    for (int i = 0; i < MW; i++)
+        m.w[i] = 0ull;
+    if (a.tree_mask) {
+#pragma unroll
+        for (int i = 0; i < MW; i++)
+            if (i < a.mask_words)
+                m.w[i] = a.tree_mask[((int64_t)b * a.n_tree + node) * a.mask_words + i];
+        return m;
+    }
+    if (a.include_self)
+        mask_set(m, node);
     for (int p = lds_parent[node]; p >= 0; p = lds_parent[p])
-        m |= 1ull << p;
+        mask_set(m, p);
+    return m;
+}
+
+template <int MW>
+__device__ __forceinline__ NodeMask<MW> empty_mask()
+{
+    NodeMask<MW> m;
+#pragma unroll
+    for (int i = 0; i < MW; i++)
+        m.w[i] = 0ull;
     return m;
 }
 
@@ -138,8 +193,8 @@ __device__ __forceinline__ RowOwner row_owner(const AttnArgs &a, int kvh, int qg
 // the exponent's fused multiply-add; the general path scales and masks the scores in place.
 // softmax_prepare: visibility test, maxima, and the (rare) raise of the references with the rescaling of the
 // accumulators; returns what still multiplies the stored scores.  softmax_exponentials: the straight-line rest.
-template <int QG, int KT, int NDT>
-__device__ __forceinline__ float softmax_prepare(f32x4 (&sacc)[KT][2][QG], WaveState<QG, NDT> &st, const uint64_t (&qmask)[QG],
+template <int QG, int KT, int NDT, int MW>
+__device__ __forceinline__ float softmax_prepare(f32x4 (&sacc)[KT][2][QG], WaveState<QG, NDT> &st, const NodeMask<MW> (&qmask)[QG],
                                                  bool needs_mask, int key0, int P, int key_end, int n_tree, float scale_log2, int g)
 {
     float mx_q[QG];
@@ -154,7 +209,7 @@ __device__ __forceinline__ float softmax_prepare(f32x4 (&sacc)[KT][2][QG], WaveS
                     float x = sacc[kt][e >> 2][qt][e & 3] * scale_log2;
                     const int key = key0 + kt * 32 + (e >> 2) * 16 + g * 4 + (e & 3);
                     const int rel = key - P;
-                    const uint32_t bit = (uint32_t)(qmask[qt] >> (rel & 63)) & 1u;
+                    const uint32_t bit = mask_bit(qmask[qt], rel);
                     const uint32_t vis = ((uint32_t)(rel < 0) | ((uint32_t)(rel < n_tree) & bit)) & (uint32_t)(key < key_end);
                     x = vis ? x : -INFINITY;
                     sacc[kt][e >> 2][qt][e & 3] = x;
@@ -253,9 +308,9 @@ __device__ __forceinline__ void tiles_scores(const uint16_t *stage, const bf16x8
 }
 
 // Online softmax of the raw scores `sacc` of the KT tiles at `stage` (first key key0) and O^T += V^T P^T.
-template <int D, int QG, int KT, int DV = D>
+template <int D, int QG, int KT, int DV = D, int MW>
 __device__ __forceinline__ void tiles_softmax_pv(const uint16_t *stage, int key0, int P, int key_end, int n_tree, float scale_log2,
-                                                 f32x4 (&sacc)[KT][2][QG], const uint64_t (&qmask)[QG], WaveState<QG, DV / 16> &st, int c, int g)
+                                                 f32x4 (&sacc)[KT][2][QG], const NodeMask<MW> (&qmask)[QG], WaveState<QG, DV / 16> &st, int c, int g)
 {
     using G = Geom<D, QG, KT, DV>;
     constexpr int KSTR = G::KSTR, VSTR = G::VSTR, NDT = G::NDT;
@@ -277,7 +332,7 @@ __device__ __forceinline__ void tiles_softmax_pv(const uint16_t *stage, int key0
     read_v(0, 0);
     // ---- online softmax; lane owns query column c and key rows g*4+r of every 16-key block
     bf16x8 pf[KT][QG];
-    const float mult = softmax_prepare<QG, KT, NDT>(sacc, st, qmask, needs_mask, key0, P, key_end, n_tree, scale_log2, g);
+    const float mult = softmax_prepare<QG, KT, NDT, MW>(sacc, st, qmask, needs_mask, key0, P, key_end, n_tree, scale_log2, g);
     softmax_exponentials<QG, KT, NDT>(sacc, pf, st, mult);
     // ---- O^T += V^T P^T
 #pragma unroll
@@ -300,20 +355,21 @@ __device__ __forceinline__ void tiles_softmax_pv(const uint16_t *stage, int key0
 
 // QK^T, online softmax and PV for KT consecutive 32-key tiles held in LDS at `stage`, for the QG query tiles of this
 // wave.  key0 is the global key index of the first row.
-template <int D, int QG, int KT, int DV = D>
+template <int D, int QG, int KT, int DV = D, int MW>
 __device__ __forceinline__ void tiles_compute(const uint16_t *stage, int key0, int P, int key_end, int n_tree, float scale_log2,
-                                              const bf16x8 (&qf)[QG][D / 32], const uint64_t (&qmask)[QG],
+                                              const bf16x8 (&qf)[QG][D / 32], const NodeMask<MW> (&qmask)[QG],
                                               WaveState<QG, DV / 16> &st, int c, int g)
 {
     f32x4 sacc[KT][2][QG];
     tiles_scores<D, QG, KT, DV>(stage, qf, sacc, c, g);
     __builtin_amdgcn_sched_barrier(0);
-    tiles_softmax_pv<D, QG, KT, DV>(stage, key0, P, key_end, n_tree, scale_log2, sacc, qmask, st, c, g);
+    tiles_softmax_pv<D, QG, KT, DV, MW>(stage, key0, P, key_end, n_tree, scale_log2, sacc, qmask, st, c, g);
 }
 
 // KT: 32-key tiles handled per step (per barrier, per softmax update); PFD: steps kept in flight in registers;
-// NW: waves per workgroup (4, or 8 when the key range is not split: twice the query tiles share one LDS tile).
-template <int D, int QG, int KT, int PFD, int NW = 4>
+// NW: waves per workgroup (4, or 8 when the key range is not split: twice the query tiles share one LDS tile);
+// MW: 64-bit words of a node's visibility mask (1: trees of up to 64 nodes; 4: up to 256).
+template <int D, int QG, int KT, int PFD, int NW = 4, int MW = 1>
 __global__ __launch_bounds__(64 * NW, (QG == 1 && D <= 128) ? (NW == 4 ? DREAM_Q1_WAVES : DREAM_W8Q1_WAVES) : 1) void attn_bf16_kernel(AttnArgs a)
 {
     using G = Geom<D, QG, KT>;
@@ -404,10 +460,10 @@ __global__ __launch_bounds__(64 * NW, (QG == 1 && D <= 128) ? (NW == 4 ? DREAM_Q
         lds_parent[tid] = my_parent < tid ? my_parent : -1;   // a walk up the tree always ends
     __syncthreads();   // parents staged
 
-    uint64_t qmask[QG];
+    NodeMask<MW> qmask[QG];
 #pragma unroll
     for (int qt = 0; qt < QG; qt++) {
-        qmask[qt] = q_valid[qt] ? visible_nodes(a, b, q_node_of[qt], lds_parent) : 0ull;
+        qmask[qt] = q_valid[qt] ? visible_nodes<MW>(a, b, q_node_of[qt], lds_parent) : empty_mask<MW>();
         if (!q_valid[qt]) {
 #pragma unroll
             for (int ks = 0; ks < NKS; ks++)
@@ -445,7 +501,7 @@ __global__ __launch_bounds__(64 * NW, (QG == 1 && D <= 128) ? (NW == 4 ? DREAM_Q
         load_step(i + PFD, kr, vr);
         if (!wave_active)
             return;
-        tiles_compute<D, QG, KT>(stage, (t_begin + i * KT) * 32, P, key_end, a.n_tree, a.scale_log2, qf, qmask, st, c, g);
+        tiles_compute<D, QG, KT, D, MW>(stage, (t_begin + i * KT) * 32, P, key_end, a.n_tree, a.scale_log2, qf, qmask, st, c, g);
     };
 
     // every load issued so far (queries, masks, first tiles) has to land before the loop: the in-order
@@ -618,11 +674,11 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a)
     if (!a.tree_mask && tid < a.n_tree)
         lds_parent[tid] = my_parent < tid ? my_parent : -1;   // a walk up the tree always ends
     __syncthreads();
-    uint64_t qmask[QT];
+    NodeMask<1> qmask[QT];
     WaveState<QT, NDT> st;
 #pragma unroll
     for (int qt = 0; qt < QT; qt++) {
-        qmask[qt] = valid[qt] ? visible_nodes(a, b, node[qt], lds_parent) : 0ull;
+        qmask[qt] = valid[qt] ? visible_nodes<1>(a, b, node[qt], lds_parent) : empty_mask<1>();
         if (!valid[qt]) {
 #pragma unroll
             for (int ks = 0; ks < NKS; ks++)
@@ -650,7 +706,7 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a)
             *reinterpret_cast<u32x4 *>(dv + j * (512 / DV) * VSTR) = vr[j];
         wave_lds_fence();
         issue(t + NW);
-        tiles_compute<D, QT, 1, DV>(wt, t * 32, P, kv_len, a.n_tree, a.scale_log2, qf, qmask, st, c, g);
+        tiles_compute<D, QT, 1, DV, 1>(wt, t * 32, P, kv_len, a.n_tree, a.scale_log2, qf, qmask, st, c, g);
         wave_lds_fence();
     }
 #pragma unroll
@@ -785,7 +841,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(AttnArgs a, int D)
     __shared__ float sq[256];
     __shared__ float sp[256];
     __shared__ float red[8];
-    __shared__ uint64_t smask;
+    __shared__ uint64_t smask[4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int row = blockIdx.x, hq = blockIdx.y, b = blockIdx.z;
     const int kvh = hq / a.group;
@@ -798,24 +854,29 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(AttnArgs a, int D)
         sq[tid] = q[tid];
     if (tid == 0) {
         const int node = a.q_node ? min(max(a.q_node[(int64_t)b * a.n_q + row], 0), a.n_tree - 1) : row;
-        uint64_t m;
+        NodeMask<4> m = empty_mask<4>();
         if (a.tree_mask) {
-            m = a.tree_mask[(int64_t)b * a.n_tree + node];
+#pragma unroll
+            for (int i = 0; i < 4; i++)
+                if (i < a.mask_words)
+                    m.w[i] = a.tree_mask[((int64_t)b * a.n_tree + node) * a.mask_words + i];
         } else {
             const int32_t *par = a.parent + (int64_t)b * a.n_tree;
-            m = a.include_self ? (1ull << node) : 0ull;
+            if (a.include_self)
+                mask_set(m, node);
             for (int prev = node, p = par[node]; p >= 0 && p < prev; prev = p, p = par[p])   // parents decrease: the walk ends
-                m |= 1ull << p;
+                mask_set(m, p);
         }
-        smask = m;
+#pragma unroll
+        for (int i = 0; i < 4; i++)
+            smask[i] = m.w[i];
     }
     __syncthreads();
-    const uint64_t mask = smask;
     float m_run = -INFINITY, l_run = 0.0f, o = 0.0f;
     for (int k0 = 0; k0 < kv_len; k0 += 256) {
         int key = k0 + tid;
         float s = -INFINITY;
-        bool vis = key < P || (key < kv_len && ((mask >> ((key - P) & 63)) & 1ull));
+        bool vis = key < P || (key < kv_len && ((smask[((key - P) >> 6) & 3] >> ((key - P) & 63)) & 1ull));
         if (vis) {
             const float4 *kr = reinterpret_cast<const float4 *>(kb + (int64_t)key * D);
             float dot = 0.0f;
@@ -869,6 +930,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(AttnArgs a, int D)
 struct Plan {
     int tiles_per_head, qg, n_qg, n_splits, n_streams, grid, n_groups, kt, pfd;
     int nw;           // waves per workgroup of the shared-tile kernel (4 or 8)
+    int mw;           // 64-bit words of a node's visibility mask (1, or 4 for trees above 64 nodes)
     bool wave_mode;   // one query tile per workgroup, waves split the keys, no key split (attn_wave_kernel)
     int wave_nw;      // waves per workgroup in that mode
     int wave_ds;      // workgroups that share the output columns of a query tile in that mode (1, 2 or 4)
@@ -907,6 +969,7 @@ int make_plan(const dream_attn_desc *d, int n_q, int64_t max_kv_len, Plan *p)
         qg = 1;
     p->qg = qg;
     p->nw = 4;
+    p->mw = 1;
     p->n_qg = ceil_div(n_qtiles, 4 * qg);
     // few, short streams with at most 16 query tiles each: a workgroup per query tile fills at least half the chip
     // without splitting keys, which saves the merge launch (short: up to 64 key tiles at head_dim 128, twice that
@@ -1000,6 +1063,30 @@ int make_plan(const dream_attn_desc *d, int n_q, int64_t max_kv_len, Plan *p)
     return 0;
 }
 
+// Trees above 64 nodes: the shared-tile kernel with four mask words, one query tile per wave, the key range unsplit
+// (no split states, so the workspace need never exceeds what the query for any other shape returns), streamed.
+void make_wide_plan(const dream_attn_desc *d, int n_q, Plan *p)
+{
+    const int G = d->n_q_heads / d->n_kv_heads;
+    const int64_t base = (int64_t)d->batch * d->n_kv_heads;
+    p->tiles_per_head = ceil_div(n_q, 16);
+    p->wave_mode = false;
+    p->wave_nw = p->wave_ds = p->wave_qt = 0;
+    p->qg = 1;
+    p->nw = 4;
+    p->mw = 4;
+    p->n_qg = ceil_div(G * p->tiles_per_head, 4);
+    p->n_splits = 1;
+    p->n_groups = (int)(base * p->n_qg);
+    p->n_streams = (int)base;
+    p->grid = ceil_div(p->n_streams, 8) * 8 * p->n_qg;
+    p->kt = d->head_dim == 64 ? 2 : 1;
+    p->pfd = 2;
+    p->state_floats = 0;
+    p->off_part = DREAM_WORKSPACE_MIN_BYTES;
+    p->total = DREAM_WORKSPACE_MIN_BYTES;
+}
+
 int validate_desc(const dream_attn_desc *d, const char *who)
 {
     if (!d)
@@ -1019,13 +1106,13 @@ int validate_desc(const dream_attn_desc *d, const char *who)
 
 // The dynamic-LDS limit of a kernel is raised once (dream_init does it for every variant up front; a variant
 // that is reached first by a call does it then).  Two threads may both set it once: harmless.
-template <int D, int QG, int KT, int PFD, int NW = 4>
+template <int D, int QG, int KT, int PFD, int NW = 4, int MW = 1>
 int ensure_bf16_lds()
 {
     using G = Geom<D, QG, KT>;
     static std::atomic<bool> attr_set{false};
     if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_kernel<D, QG, KT, PFD, NW>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_kernel<D, QG, KT, PFD, NW, MW>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)G::LDS_BYTES) != hipSuccess)
             return fail(DREAM_ERR_HIP, "attention: cannot reserve %zu bytes of LDS", G::LDS_BYTES);
         attr_set = true;
@@ -1033,15 +1120,17 @@ int ensure_bf16_lds()
     return DREAM_OK;
 }
 
-template <int D, int QG, int KT, int PFD, int NW = 4>
+template <int D, int QG, int KT, int PFD, int NW = 4, int MW = 1>
 int launch_bf16(const AttnArgs &a, const Plan &p, hipStream_t st)
 {
     using G = Geom<D, QG, KT>;
-    if (int rc = ensure_bf16_lds<D, QG, KT, PFD, NW>())
+    if (int rc = ensure_bf16_lds<D, QG, KT, PFD, NW, MW>())
         return rc;
     if (NW != 4 && p.n_splits != 1)
         return fail(DREAM_ERR_INVALID_ARG, "attention: the 8-wave shared-tile kernel does not split the key range");
-    hipLaunchKernelGGL((attn_bf16_kernel<D, QG, KT, PFD, NW>), dim3(p.grid), dim3(64 * NW), G::LDS_BYTES, st, a);
+    if (a.mask_words > MW)
+        return fail(DREAM_ERR_INVALID_ARG, "attention: a tree of %d nodes needs %d mask words, this kernel has %d", a.n_tree, a.mask_words, MW);
+    hipLaunchKernelGGL((attn_bf16_kernel<D, QG, KT, PFD, NW, MW>), dim3(p.grid), dim3(64 * NW), G::LDS_BYTES, st, a);
     int rc = check_launch("attn_bf16_kernel");
     if (rc || p.n_splits == 1)
         return rc;
@@ -1088,13 +1177,14 @@ int launch_wave(const AttnArgs &a, const Plan &p, hipStream_t st)
 // its dynamic-LDS limit.  The launch, dream_init, dream_attn_plan_describe and dream_attn_variants all read it.
 enum { FAMILY_TILE = 0, FAMILY_WAVE = 1 };
 struct Variant {
-    int family, d, p1, p2, p3, p4;   // tile: (QG, KT, PFD, waves); wave: (NW, DS, QT, 0)
+    int family, d, p1, p2, p3, p4, p5;   // tile: (QG, KT, PFD, waves, mask words); wave: (NW, DS, QT, 0, 1)
     int (*launch)(const AttnArgs &, const Plan &, hipStream_t);
     int (*ensure)();
 };
-#define TILE_VARIANT(D, QG, KT, PFD) {FAMILY_TILE, D, QG, KT, PFD, 4, &launch_bf16<D, QG, KT, PFD>, &ensure_bf16_lds<D, QG, KT, PFD>}
-#define TILE8_VARIANT(D, QG, KT, PFD) {FAMILY_TILE, D, QG, KT, PFD, 8, &launch_bf16<D, QG, KT, PFD, 8>, &ensure_bf16_lds<D, QG, KT, PFD, 8>}
-#define WAVE_VARIANT(D, NW, DS, QT) {FAMILY_WAVE, D, NW, DS, QT, 0, &launch_wave<D, NW, DS, QT>, &ensure_wave_lds<D, NW, DS, QT>}
+#define TILE_VARIANT(D, QG, KT, PFD) {FAMILY_TILE, D, QG, KT, PFD, 4, 1, &launch_bf16<D, QG, KT, PFD>, &ensure_bf16_lds<D, QG, KT, PFD>}
+#define WIDE_VARIANT(D, QG, KT, PFD) {FAMILY_TILE, D, QG, KT, PFD, 4, 4, &launch_bf16<D, QG, KT, PFD, 4, 4>, &ensure_bf16_lds<D, QG, KT, PFD, 4, 4>}
+#define TILE8_VARIANT(D, QG, KT, PFD) {FAMILY_TILE, D, QG, KT, PFD, 8, 1, &launch_bf16<D, QG, KT, PFD, 8>, &ensure_bf16_lds<D, QG, KT, PFD, 8>}
+#define WAVE_VARIANT(D, NW, DS, QT) {FAMILY_WAVE, D, NW, DS, QT, 0, 1, &launch_wave<D, NW, DS, QT>, &ensure_wave_lds<D, NW, DS, QT>}
 const Variant VARIANTS[] = {
     // shared-tile kernel, one query tile per wave: a short key range in one step (2-4 tiles), or streamed
     TILE_VARIANT(64, 1, 2, 1), TILE_VARIANT(64, 1, 3, 1), TILE_VARIANT(64, 1, 4, 1), TILE_VARIANT(64, 1, 2, 2),
@@ -1104,6 +1194,8 @@ const Variant VARIANTS[] = {
     TILE_VARIANT(64, 2, 1, 2), TILE_VARIANT(64, 4, 1, 2), TILE_VARIANT(128, 2, 1, 2), TILE_VARIANT(128, 4, 1, 1), TILE_VARIANT(256, 2, 1, 1),
     // 8 waves per workgroup (unsplit key range, grouped queries): a fifth name argument 8
     TILE8_VARIANT(128, 1, 1, DREAM_W8_PFD), TILE8_VARIANT(128, 2, 1, DREAM_W8_PFD), TILE8_VARIANT(256, 1, 1, DREAM_W8_PFD),
+    // trees of 65-256 nodes (four mask words): a sixth name argument 4
+    WIDE_VARIANT(64, 1, 2, 2), WIDE_VARIANT(128, 1, 1, 2), WIDE_VARIANT(256, 1, 1, 2),
     // single-launch wave kernel: (waves, column slices, query tiles per workgroup); split output columns always come
     // with 8 waves at head_dim <= 128
     WAVE_VARIANT(64, 8, 1, 1), WAVE_VARIANT(64, 8, 2, 1), WAVE_VARIANT(64, 4, 1, 1),
@@ -1114,6 +1206,7 @@ const Variant VARIANTS[] = {
 };
 #undef TILE_VARIANT
 #undef TILE8_VARIANT
+#undef WIDE_VARIANT
 #undef WAVE_VARIANT
 constexpr int N_VARIANTS = sizeof(VARIANTS) / sizeof(VARIANTS[0]);
 
@@ -1122,10 +1215,10 @@ const Variant *find_variant(const dream_attn_desc *d, const Plan &p)
 {
     const int family = p.wave_mode ? FAMILY_WAVE : FAMILY_TILE;
     const int p1 = p.wave_mode ? p.wave_nw : p.qg, p2 = p.wave_mode ? p.wave_ds : p.kt, p3 = p.wave_mode ? p.wave_qt : p.pfd;
-    const int p4 = p.wave_mode ? 0 : p.nw;
+    const int p4 = p.wave_mode ? 0 : p.nw, p5 = p.wave_mode ? 1 : p.mw;
     for (int i = 0; i < N_VARIANTS; i++) {
         const Variant &v = VARIANTS[i];
-        if (v.family == family && v.d == d->head_dim && v.p1 == p1 && v.p2 == p2 && v.p3 == p3 && v.p4 == p4)
+        if (v.family == family && v.d == d->head_dim && v.p1 == p1 && v.p2 == p2 && v.p3 == p3 && v.p4 == p4 && v.p5 == p5)
             return &v;
     }
     return nullptr;
@@ -1135,6 +1228,8 @@ void variant_name(const Variant &v, char *buf, size_t n)
 {
     if (v.family == FAMILY_WAVE)
         snprintf(buf, n, "attn_wave_kernel<%d,%d,%d,%d>", v.d, v.p1, v.p2, v.p3);
+    else if (v.p5 != 1)
+        snprintf(buf, n, "attn_bf16_kernel<%d,%d,%d,%d,%d,%d>", v.d, v.p1, v.p2, v.p3, v.p4, v.p5);
     else if (v.p4 != 4)
         snprintf(buf, n, "attn_bf16_kernel<%d,%d,%d,%d,%d>", v.d, v.p1, v.p2, v.p3, v.p4);
     else
@@ -1163,6 +1258,8 @@ int run_attention(const char *who, const dream_attn_desc *d, const void *q, cons
         return fail(DREAM_ERR_INVALID_ARG, "%s: max_kv_len %lld outside [n_tree, s_max]", who, (long long)max_kv_len);
     Plan p;
     make_plan(d, n_q, max_kv_len, &p);
+    if (n_tree > 64 && d->dtype == DREAM_BF16)
+        make_wide_plan(d, n_q, &p);
     if (!ws || ws_bytes < p.total)
         return fail(DREAM_ERR_WORKSPACE, "%s: workspace of %zu bytes, %zu needed", who, ws_bytes, p.total);
 
@@ -1173,6 +1270,7 @@ int run_attention(const char *who, const dream_attn_desc *d, const void *q, cons
     a.part = reinterpret_cast<float *>(static_cast<char *>(ws) + p.off_part);
     a.n_q_heads = d->n_q_heads; a.n_kv_heads = d->n_kv_heads; a.group = d->n_q_heads / d->n_kv_heads;
     a.n_q = n_q; a.n_tree = n_tree; a.include_self = include_self;
+    a.mask_words = ceil_div(n_tree, 64);
     a.tiles_per_head = p.tiles_per_head; a.n_qg = p.n_qg; a.n_splits = p.n_splits; a.n_streams = p.n_streams;
     a.s_max = d->s_max;
     a.scale = d->scale != 0.0f ? d->scale : 1.0f / sqrtf((float)d->head_dim);
@@ -1229,6 +1327,8 @@ int dream_attn_plan_describe(const dream_attn_desc *desc, int32_t n_q, int64_t m
         return fail(DREAM_ERR_INVALID_ARG, "%s: need n_q >= 1 and 1 <= max_kv_len <= s_max", who);
     Plan p;
     make_plan(desc, n_q, max_kv_len, &p);
+    if (n_q > 64 && desc->dtype == DREAM_BF16)   // more than 64 query rows: taken as a verification call over a tree of n_q nodes
+        make_wide_plan(desc, n_q, &p);
     if (desc->dtype == DREAM_F32) {
         snprintf(buf, buf_bytes, "attn_f32_kernel workgroups=%lld", (long long)desc->batch * desc->n_q_heads * n_q);
         return DREAM_OK;

@@ -29,6 +29,10 @@ VARIANT_CASES = [
     VariantCase("attn_bf16_kernel<128,1,1,2,8>", 2, 4, 2, 128, 60, 6, 150, 0, 0, 8),
     VariantCase("attn_bf16_kernel<128,2,1,2,8>", 2, 8, 2, 128, 60, 6, 150, 0, 0, 8),
     VariantCase("attn_bf16_kernel<256,1,1,2,8>", 2, 4, 2, 256, 60, 6, 150, 0, 0, 8),
+    # trees of 65-256 nodes (four mask words per node): 100, 200 and 256 nodes
+    VariantCase("attn_bf16_kernel<64,1,2,2,4,4>", 2, 4, 4, 64, 100, 7, 333, 0, 0),
+    VariantCase("attn_bf16_kernel<128,1,1,2,4,4>", 2, 4, 2, 128, 200, 9, 410, 0, 0),
+    VariantCase("attn_bf16_kernel<256,1,1,2,4,4>", 1, 4, 2, 256, 256, 12, 300, 0, 0),
     VariantCase("attn_wave_kernel<64,8,1,1>", 3, 24, 8, 64, 17, 4, 1340, 0, 0),
     VariantCase("attn_wave_kernel<64,8,2,1>", 8, 2, 2, 64, 17, 4, 150, 0, 0),
     VariantCase("attn_wave_kernel<64,4,1,1>", 3, 24, 8, 64, 17, 4, 150, 0, 0),

@@ -62,7 +62,7 @@ def test_host_side_argument_errors(lib):
     assert f(*args(d, q=None)) == -1
     assert f(*args(dream.attn_desc(1, 6, 4, 64, dream.BF16, 128))) == -1          # Hq % Hkv
     assert f(*args(dream.attn_desc(1, 4, 4, 96, dream.BF16, 128))) == -2          # head_dim
-    assert f(*args(d, n_tree=65)) == -2
+    assert f(*args(d, n_tree=257)) == -2
     assert f(*args(d, n_tree=0)) == -2
     assert f(*args(d, maxkv=129)) == -1                                           # beyond s_max
     big = dream.attn_desc(1, 32, 8, 128, dream.BF16, 4200)                        # a long cache with few KV heads: key splits need a workspace

@@ -93,6 +93,38 @@ def test_explicit_tree_mask_matches_parent_derived_mask(gu):
     assert np.abs(got2 - base).max() > 1e-3
 
 
+def test_trees_above_64_nodes(gu):
+    """130-node trees (three mask words in use): the mask derived from `parent`, the same mask given explicitly
+    ([B, n_tree, 3] words), a foreign explicit mask, and cross-attention levels whose few query rows name nodes of the
+    wide tree; float32 tensors as well."""
+    cfg = _cfg("wide130", "bf16", 2, 4, 2, 128, 90, 21, 130, 9, 44)
+    x = di.verify_inputs(cfg, prefix_len=[111, 60])
+    assert gu.verify_plan(x).startswith("attn_bf16_kernel<128,1,1,2,4,4> ")
+    base, lse = gu.run_verify(x)
+    want, want_lse = oracle.tree_attn(x.q, x.k, x.v, "bf16", x.prefix_len, x.parent, True)
+    assert np.abs(base - want).max() <= TOL["bf16"] and np.abs(lse - want_lse).max() <= 2e-3
+    masks = np.stack([di.ancestor_mask_bits(x.parent[b], True) for b in range(cfg.batch)])
+    assert masks.shape == (cfg.batch, 130, 3)
+    got, _ = gu.run_verify(x, tree_mask=masks)
+    assert np.array_equal(got, base)
+    star = di.star_tree(cfg.n_tree)
+    got2, _ = gu.run_verify(x, tree_mask=np.stack([di.ancestor_mask_bits(star, True)] * cfg.batch))
+    want2, _ = oracle.tree_attn(x.q, x.k, x.v, "bf16", x.prefix_len, np.stack([star] * cfg.batch), True)
+    assert np.abs(got2 - want2).max() <= TOL["bf16"]
+    # draft cross-attention: 10 query rows per call that name deep nodes of the wide tree (strict ancestors)
+    xx = di.verify_inputs(cfg, prefix_len=[111, 60], streams=(di.STREAM_XQ, di.STREAM_XK, di.STREAM_XV))
+    rows = np.stack([np.arange(120, 130, dtype=np.int32)] * cfg.batch)
+    gotx, qsel = gu.run_xattn(xx, rows, rows)
+    wantx, _ = oracle.tree_attn(qsel, xx.k, xx.v, "bf16", xx.prefix_len, xx.parent, False, q_node=rows)
+    assert np.abs(gotx - wantx).max() <= TOL["bf16"]
+    # float32 tensors
+    cfg32 = _cfg("wide130_f32", "f32", 1, 2, 2, 64, 40, 9, 130, 9, 45)
+    x32 = di.verify_inputs(cfg32)
+    got32, _ = gu.run_verify(x32)
+    want32, _ = oracle.tree_attn(x32.q, x32.k, x32.v, "f32", x32.prefix_len, x32.parent, True)
+    assert np.abs(got32 - want32).max() <= TOL["f32"]
+
+
 def test_custom_scale(gu):
     cfg = _cfg("scale", "bf16", 1, 4, 4, 64, 80, 20, 30, 5, 42)
     x = di.verify_inputs(cfg)
