@@ -105,7 +105,7 @@ def main() -> int:
             r = run_config(torch, dream, di, args, di.CONFIGS[name], steps=max(5, min(args.steps, 20)), warmup=3, full=False)
             if di.CONFIGS[name].batch == 1:
                 torch.cuda.empty_cache()
-                r["streaming_regime"] = streaming_regime(torch, dream, di, di.CONFIGS[name], iters=20, warm=40)
+                r["streaming_regime"] = streaming_regime(torch, dream, di, di.CONFIGS[name])
             out["configs"][name] = {"step_latency_us": r["step_latency_us"], "tokens_per_s": r["value"], "streaming_regime": r.get("streaming_regime"),
                                     "tokens_per_s_at_paper_tau": r["tokens_per_s_at_paper_tau"], "phase_us": r["phase_us"],
                                     "per_request_us": r["per_request_us"], "roofline": r["roofline"], "read_ceiling": r["read_ceiling"],
@@ -462,11 +462,12 @@ def copy_calibration(torch):
     return 0
 
 
-def streaming_regime(torch, dream, di, cfg, batch=32, iters=40, warm=60):
+def streaming_regime(torch, dream, di, cfg, batch=32, iters=80, warm=320):
     """The same verification kernel on the same shape with `batch` sequences per launch: one launch then
     moves hundreds of MB, so its duration measures streaming efficiency rather than launch latency.
-    Two cache sets are alternated so that nothing is served from the last-level cache.  The warm-up is long enough
-    (several ms of back-to-back launches) for the clocks to settle: the first launches after a pause run 5-10 % slower."""
+    Two cache sets are alternated so that nothing is served from the last-level cache; the launches are replayed as a
+    HIP graph of 8.  The warm-up is 320 launches (about 25 ms): the launch time keeps falling for the first 15-20 ms of
+    sustained load (5-10 % in all) while the clocks settle."""
     big = cfg.with_batch(batch) if cfg.batch < batch else cfg
     B, T, Hq, Hkv, D, P = big.batch, big.n_tree, big.n_q_heads, big.n_kv_heads, big.head_dim, big.prefix
     S = P + T
@@ -486,16 +487,10 @@ def streaming_regime(torch, dream, di, cfg, batch=32, iters=40, warm=60):
         q, k, v = sets[i & 1]
         dream.dream_tree_verify_attn(desc, q, k, v, pl, T, parent, None, S, out, None, ws)
 
-    for i in range(warm):
-        run(i)
+    run(0)
     torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for i in range(iters):
-        run(i)
-    e1.record()
-    torch.cuda.synchronize()
-    us = e0.elapsed_time(e1) * 1e3 / iters
+    per_graph = 8   # replayed as a graph, so that the host's launch path cannot be what is timed
+    us = graph_time_us(torch, lambda: [run(i) for i in range(per_graph)], reps=max(1, iters // per_graph), warm=max(1, warm // per_graph)) / per_graph
     nbytes = verify_bytes_per_launch(big)
     gbs = nbytes / us / 1e3
     tflops = 4.0 * B * Hq * T * S * D / us / 1e6   # QK^T and PV, 2 flops per multiply-add, over all (row, key) pairs
