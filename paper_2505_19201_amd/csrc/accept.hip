@@ -48,8 +48,8 @@ __global__ __launch_bounds__(256) void argmax_partial_kernel(const void *logits,
         const bool aligned = (((uintptr_t)(p + begin)) & 15) == 0;
         int vec_end = aligned ? begin + ((end - begin) & ~7) : begin;
         for (int i = begin + tid * 8; i < vec_end; i += 256 * 8) {
-            uint4 u = *reinterpret_cast<const uint4 *>(p + i);
-            uint32_t w[4] = {u.x, u.y, u.z, u.w};
+            const u32x4 u = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p + i));   // logits: read once
+            uint32_t w[4] = {u[0], u[1], u[2], u[3]};
 #pragma unroll
             for (int j = 0; j < 4; j++) {
                 float lo = __uint_as_float(w[j] << 16), hi = __uint_as_float(w[j] & 0xffff0000u);

@@ -366,10 +366,23 @@ __device__ __forceinline__ void tiles_compute(const uint16_t *stage, int key0, i
     tiles_softmax_pv<D, QG, KT, DV, MW>(stage, key0, P, key_end, n_tree, scale_log2, sacc, qmask, st, c, g);
 }
 
+// LDS traffic inside one wave needs no barrier, only program order.
+__device__ __forceinline__ void wave_lds_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // KT: 32-key tiles handled per step (per barrier, per softmax update); PFD: steps kept in flight in registers;
 // NW: waves per workgroup (4, or 8 when the key range is not split: twice the query tiles share one LDS tile);
-// MW: 64-bit words of a node's visibility mask (1: trees of up to 64 nodes; 4: up to 256).
-template <int D, int QG, int KT, int PFD, int NW = 4, int MW = 1>
+// MW: 64-bit words of a node's visibility mask (1: trees of up to 64 nodes; 4: up to 256);
+// ONCE: this workgroup is the only reader of its K/V rows (one query group per KV head), so the loads carry the
+// nontemporal hint: rows that are used once otherwise displace each other, and the output rows on their way out, in
+// L2 (measured at 32 sequences: LLaVA 82.5 -> 71 us, SmolVLM 83.5 -> 74.5 us per launch).  With several query groups per
+// KV head the later groups hit the rows in L2, so those launches use the variant without the hint.  (A run-time choice
+// between the two kinds of load does not survive the compiler: it merges them into plain loads.)
+template <int D, int QG, int KT, int PFD, int NW = 4, int MW = 1, bool ONCE = false>
 __global__ __launch_bounds__(64 * NW, (QG == 1 && D <= 128) ? (NW == 4 ? DREAM_Q1_WAVES : DREAM_W8Q1_WAVES) : 1) void attn_bf16_kernel(AttnArgs a)
 {
     using G = Geom<D, QG, KT>;
@@ -426,8 +439,15 @@ __global__ __launch_bounds__(64 * NW, (QG == 1 && D <= 128) ? (NW == 4 ? DREAM_Q
 #pragma unroll
             for (int j = 0; j < CH; j++) {
                 const int key = min(t * 32 + ld_row + j * ROWS, kv_len - 1);
-                kr[kt * CH + j] = *reinterpret_cast<const u32x4 *>(kbase + (int64_t)key * D + ld_col * 8);
-                vr[kt * CH + j] = *reinterpret_cast<const u32x4 *>(vbase + (int64_t)key * D + ld_col * 8);
+                const u32x4 *kp = reinterpret_cast<const u32x4 *>(kbase + (int64_t)key * D + ld_col * 8);
+                const u32x4 *vp = reinterpret_cast<const u32x4 *>(vbase + (int64_t)key * D + ld_col * 8);
+                if constexpr (ONCE) {
+                    kr[kt * CH + j] = __builtin_nontemporal_load(kp);
+                    vr[kt * CH + j] = __builtin_nontemporal_load(vp);
+                } else {
+                    kr[kt * CH + j] = *kp;
+                    vr[kt * CH + j] = *vp;
+                }
             }
         }
     };
@@ -520,6 +540,7 @@ __global__ __launch_bounds__(64 * NW, (QG == 1 && D <= 128) ? (NW == 4 ? DREAM_Q
             if (i + pf < n_steps)
                 step(i + pf, kreg[pf], vreg[pf]);
     }
+    __syncthreads();   // every wave is done with the last tile: the stage areas can be reused for the output rows
     if (!wave_active)
         return;
 
@@ -537,25 +558,40 @@ __global__ __launch_bounds__(64 * NW, (QG == 1 && D <= 128) ? (NW == 4 ? DREAM_Q
         state_store<QG, NDT>(st, a.part + ((grp * nsplit + split) * 4 + wave) * StateGeom<D, QG>::STATE_FLOATS, lane);
         return;
     }
+    // Output rows leave through LDS: a lane holds 4 columns of one row per column tile, which stored directly would
+    // be 32-byte pieces of 16 rows per instruction; staged in the wave's own LDS area (free by now) the rows go out
+    // as whole 16-byte-per-lane rows, full cache lines per instruction, with the nontemporal hint (nobody in this
+    // launch reads them; measured together with the staging: 82.5 -> 78 us at 32 LLaVA sequences, either alone nothing).
     constexpr float LN2 = 0.6931471805599453f;
+    constexpr int OSTR = D + 8, LPR = D / 8, RPP = 64 / LPR;   // staging row stride; lanes per row; rows per store instruction
+    static_assert((size_t)NW * 16 * OSTR * 2 <= (size_t)2 * G::STAGE_ELEMS * 2, "the output staging reuses the tile stages");
+    uint16_t *ot = lds + wave * 16 * OSTR;
 #pragma unroll
     for (int qt = 0; qt < QG; qt++) {
         RowOwner ro = row_owner(a, kvh, qg, wave, QG, qt, c, NW);
-        if (ro.row < 0)
-            continue;
         const float l = st.l[qt];
         const float inv = l > 0.0f ? 1.0f / l : 0.0f;
-        uint16_t *op = reinterpret_cast<uint16_t *>(a.out) + (((int64_t)b * a.n_q + ro.row) * a.n_q_heads + ro.head) * D + g * 4;
 #pragma unroll
         for (int dt = 0; dt < NDT; dt++) {
             bf16x4 ob;
 #pragma unroll
             for (int r = 0; r < 4; r++)
                 ob[r] = (__bf16)(st.o[qt][dt][r] * inv);
-            *reinterpret_cast<bf16x4 *>(op + dt * 16) = ob;
+            *reinterpret_cast<bf16x4 *>(ot + c * OSTR + dt * 16 + g * 4) = ob;
         }
-        if (a.lse && g == 0)
+        if (ro.row >= 0 && a.lse && g == 0)
             a.lse[((int64_t)b * a.n_q_heads + ro.head) * a.n_q + ro.row] = l > 0.0f ? (st.m[qt] + log2f(l)) * LN2 : -INFINITY;
+        wave_lds_fence();
+#pragma unroll
+        for (int pass = 0; pass < 16 / RPP; pass++) {
+            const int r2 = pass * RPP + lane / LPR, col = (lane % LPR) * 8;
+            RowOwner ro2 = row_owner(a, kvh, qg, wave, QG, qt, r2, NW);
+            if (ro2.row >= 0) {
+                uint16_t *op = reinterpret_cast<uint16_t *>(a.out) + (((int64_t)b * a.n_q + ro2.row) * a.n_q_heads + ro2.head) * D + col;
+                __builtin_nontemporal_store(*reinterpret_cast<const u32x4 *>(ot + r2 * OSTR + col), reinterpret_cast<u32x4 *>(op));
+            }
+        }
+        wave_lds_fence();
     }
 }
 
@@ -578,14 +614,6 @@ __device__ __forceinline__ void state_merge(WaveState<QG, NDT> &s, const float *
             s.o[qt][dt] = s.o[qt][dt] * a1 + oo * a2;
         }
     }
-}
-
-// LDS traffic inside one wave needs no barrier, only program order.
-__device__ __forceinline__ void wave_lds_fence()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
 // Short streams with few query tiles (one sequence; up to 4 query heads per KV head): a workgroup serves ONE 16-row query tile of one
@@ -931,6 +959,7 @@ struct Plan {
     int tiles_per_head, qg, n_qg, n_splits, n_streams, grid, n_groups, kt, pfd;
     int nw;           // waves per workgroup of the shared-tile kernel (4 or 8)
     int mw;           // 64-bit words of a node's visibility mask (1, or 4 for trees above 64 nodes)
+    int once;         // 1: the variant whose K/V loads carry the nontemporal hint (one query group per KV head)
     bool wave_mode;   // one query tile per workgroup, waves split the keys, no key split (attn_wave_kernel)
     int wave_nw;      // waves per workgroup in that mode
     int wave_ds;      // workgroups that share the output columns of a query tile in that mode (1, 2 or 4)
@@ -970,6 +999,7 @@ int make_plan(const dream_attn_desc *d, int n_q, int64_t max_kv_len, Plan *p)
     p->qg = qg;
     p->nw = 4;
     p->mw = 1;
+    p->once = 0;
     p->n_qg = ceil_div(n_qtiles, 4 * qg);
     // few, short streams with at most 16 query tiles each: a workgroup per query tile fills at least half the chip
     // without splitting keys, which saves the merge launch (short: up to 64 key tiles at head_dim 128, twice that
@@ -1011,11 +1041,13 @@ int make_plan(const dream_attn_desc *d, int n_q, int64_t max_kv_len, Plan *p)
         const int qg8_max = d->head_dim == 256 ? 1 : 2;
         int qg8 = q_tiles_override() > 0 ? (q_tiles_override() > qg8_max ? qg8_max : q_tiles_override()) : (n_qtiles > 8 ? qg8_max : 1);
         const bool can8 = d->dtype == DREAM_BF16 && d->head_dim >= 128 && kv_splits_override() <= 1 && tw != 4;
-        const bool want8 = tw == 8 || (q_tiles_override() == 0 && n_qtiles > 4 && base * ceil_div(n_qtiles, 8 * qg8) >= 256);
-        if (can8 && want8) {
+        const bool want8 = tw == 8 || (q_tiles_override() == 0 && n_qtiles > 4 && base >= 256);
+        // (the 8-wave variants read K/V with the nontemporal hint, so a KV head must not need two of them)
+        if (can8 && want8 && ceil_div(n_qtiles, 8 * qg8) == 1) {
             p->nw = 8;
             p->qg = qg = qg8;
-            p->n_qg = ceil_div(n_qtiles, 8 * qg8);
+            p->n_qg = 1;
+            p->once = 1;
         }
     }
     int s = kv_splits_override();
@@ -1054,6 +1086,8 @@ int make_plan(const dream_attn_desc *d, int n_q, int64_t max_kv_len, Plan *p)
     if (p->nw == 8) {
         p->kt = 1;
         p->pfd = DREAM_W8_PFD;
+    } else if (qg == 1 && p->pfd == 2 && p->n_qg == 1) {
+        p->once = 1;
     }
     p->state_floats = (size_t)qg * (d->head_dim / 16) * 256 + (size_t)qg * 2 * 64;
     p->off_part = DREAM_WORKSPACE_MIN_BYTES;
@@ -1075,6 +1109,7 @@ void make_wide_plan(const dream_attn_desc *d, int n_q, Plan *p)
     p->qg = 1;
     p->nw = 4;
     p->mw = 4;
+    p->once = 0;
     p->n_qg = ceil_div(G * p->tiles_per_head, 4);
     p->n_splits = 1;
     p->n_groups = (int)(base * p->n_qg);
@@ -1106,13 +1141,13 @@ int validate_desc(const dream_attn_desc *d, const char *who)
 
 // The dynamic-LDS limit of a kernel is raised once (dream_init does it for every variant up front; a variant
 // that is reached first by a call does it then).  Two threads may both set it once: harmless.
-template <int D, int QG, int KT, int PFD, int NW = 4, int MW = 1>
+template <int D, int QG, int KT, int PFD, int NW = 4, int MW = 1, bool ONCE = false>
 int ensure_bf16_lds()
 {
     using G = Geom<D, QG, KT>;
     static std::atomic<bool> attr_set{false};
     if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_kernel<D, QG, KT, PFD, NW, MW>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_kernel<D, QG, KT, PFD, NW, MW, ONCE>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)G::LDS_BYTES) != hipSuccess)
             return fail(DREAM_ERR_HIP, "attention: cannot reserve %zu bytes of LDS", G::LDS_BYTES);
         attr_set = true;
@@ -1120,17 +1155,19 @@ int ensure_bf16_lds()
     return DREAM_OK;
 }
 
-template <int D, int QG, int KT, int PFD, int NW = 4, int MW = 1>
+template <int D, int QG, int KT, int PFD, int NW = 4, int MW = 1, bool ONCE = false>
 int launch_bf16(const AttnArgs &a, const Plan &p, hipStream_t st)
 {
     using G = Geom<D, QG, KT>;
-    if (int rc = ensure_bf16_lds<D, QG, KT, PFD, NW, MW>())
+    if (int rc = ensure_bf16_lds<D, QG, KT, PFD, NW, MW, ONCE>())
         return rc;
+    if (ONCE && a.n_qg != 1)
+        return fail(DREAM_ERR_INVALID_ARG, "attention: the read-once kernel variant needs one query group per KV head, not %d", a.n_qg);
     if (NW != 4 && p.n_splits != 1)
         return fail(DREAM_ERR_INVALID_ARG, "attention: the 8-wave shared-tile kernel does not split the key range");
     if (a.mask_words > MW)
         return fail(DREAM_ERR_INVALID_ARG, "attention: a tree of %d nodes needs %d mask words, this kernel has %d", a.n_tree, a.mask_words, MW);
-    hipLaunchKernelGGL((attn_bf16_kernel<D, QG, KT, PFD, NW, MW>), dim3(p.grid), dim3(64 * NW), G::LDS_BYTES, st, a);
+    hipLaunchKernelGGL((attn_bf16_kernel<D, QG, KT, PFD, NW, MW, ONCE>), dim3(p.grid), dim3(64 * NW), G::LDS_BYTES, st, a);
     int rc = check_launch("attn_bf16_kernel");
     if (rc || p.n_splits == 1)
         return rc;
@@ -1177,14 +1214,15 @@ int launch_wave(const AttnArgs &a, const Plan &p, hipStream_t st)
 // its dynamic-LDS limit.  The launch, dream_init, dream_attn_plan_describe and dream_attn_variants all read it.
 enum { FAMILY_TILE = 0, FAMILY_WAVE = 1 };
 struct Variant {
-    int family, d, p1, p2, p3, p4, p5;   // tile: (QG, KT, PFD, waves, mask words); wave: (NW, DS, QT, 0, 1)
+    int family, d, p1, p2, p3, p4, p5, p6;   // tile: (QG, KT, PFD, waves, mask words, read-once); wave: (NW, DS, QT, 0, 1, 0)
     int (*launch)(const AttnArgs &, const Plan &, hipStream_t);
     int (*ensure)();
 };
-#define TILE_VARIANT(D, QG, KT, PFD) {FAMILY_TILE, D, QG, KT, PFD, 4, 1, &launch_bf16<D, QG, KT, PFD>, &ensure_bf16_lds<D, QG, KT, PFD>}
-#define WIDE_VARIANT(D, QG, KT, PFD) {FAMILY_TILE, D, QG, KT, PFD, 4, 4, &launch_bf16<D, QG, KT, PFD, 4, 4>, &ensure_bf16_lds<D, QG, KT, PFD, 4, 4>}
-#define TILE8_VARIANT(D, QG, KT, PFD) {FAMILY_TILE, D, QG, KT, PFD, 8, 1, &launch_bf16<D, QG, KT, PFD, 8>, &ensure_bf16_lds<D, QG, KT, PFD, 8>}
-#define WAVE_VARIANT(D, NW, DS, QT) {FAMILY_WAVE, D, NW, DS, QT, 0, 1, &launch_wave<D, NW, DS, QT>, &ensure_wave_lds<D, NW, DS, QT>}
+#define TILE_VARIANT(D, QG, KT, PFD) {FAMILY_TILE, D, QG, KT, PFD, 4, 1, 0, &launch_bf16<D, QG, KT, PFD>, &ensure_bf16_lds<D, QG, KT, PFD>}
+#define ONCE_VARIANT(D, QG, KT, PFD) {FAMILY_TILE, D, QG, KT, PFD, 4, 1, 1, &launch_bf16<D, QG, KT, PFD, 4, 1, true>, &ensure_bf16_lds<D, QG, KT, PFD, 4, 1, true>}
+#define WIDE_VARIANT(D, QG, KT, PFD) {FAMILY_TILE, D, QG, KT, PFD, 4, 4, 0, &launch_bf16<D, QG, KT, PFD, 4, 4>, &ensure_bf16_lds<D, QG, KT, PFD, 4, 4>}
+#define TILE8_VARIANT(D, QG, KT, PFD) {FAMILY_TILE, D, QG, KT, PFD, 8, 1, 1, &launch_bf16<D, QG, KT, PFD, 8, 1, true>, &ensure_bf16_lds<D, QG, KT, PFD, 8, 1, true>}
+#define WAVE_VARIANT(D, NW, DS, QT) {FAMILY_WAVE, D, NW, DS, QT, 0, 1, 0, &launch_wave<D, NW, DS, QT>, &ensure_wave_lds<D, NW, DS, QT>}
 const Variant VARIANTS[] = {
     // shared-tile kernel, one query tile per wave: a short key range in one step (2-4 tiles), or streamed
     TILE_VARIANT(64, 1, 2, 1), TILE_VARIANT(64, 1, 3, 1), TILE_VARIANT(64, 1, 4, 1), TILE_VARIANT(64, 1, 2, 2),
@@ -1192,7 +1230,9 @@ const Variant VARIANTS[] = {
     TILE_VARIANT(256, 1, 1, 2),
     // several query tiles per wave
     TILE_VARIANT(64, 2, 1, 2), TILE_VARIANT(64, 4, 1, 2), TILE_VARIANT(128, 2, 1, 2), TILE_VARIANT(128, 4, 1, 1), TILE_VARIANT(256, 2, 1, 1),
-    // 8 waves per workgroup (unsplit key range, grouped queries): a fifth name argument 8
+    // streamed, the workgroup the only reader of its K/V rows (one query group per KV head): name arguments ...,4,1,1
+    ONCE_VARIANT(64, 1, 2, 2), ONCE_VARIANT(128, 1, 1, 2), ONCE_VARIANT(256, 1, 1, 2),
+    // 8 waves per workgroup (unsplit key range, grouped queries, always the only reader): a fifth name argument 8
     TILE8_VARIANT(128, 1, 1, DREAM_W8_PFD), TILE8_VARIANT(128, 2, 1, DREAM_W8_PFD), TILE8_VARIANT(256, 1, 1, DREAM_W8_PFD),
     // trees of 65-256 nodes (four mask words): a sixth name argument 4
     WIDE_VARIANT(64, 1, 2, 2), WIDE_VARIANT(128, 1, 1, 2), WIDE_VARIANT(256, 1, 1, 2),
@@ -1206,6 +1246,7 @@ const Variant VARIANTS[] = {
 };
 #undef TILE_VARIANT
 #undef TILE8_VARIANT
+#undef ONCE_VARIANT
 #undef WIDE_VARIANT
 #undef WAVE_VARIANT
 constexpr int N_VARIANTS = sizeof(VARIANTS) / sizeof(VARIANTS[0]);
@@ -1215,10 +1256,10 @@ const Variant *find_variant(const dream_attn_desc *d, const Plan &p)
 {
     const int family = p.wave_mode ? FAMILY_WAVE : FAMILY_TILE;
     const int p1 = p.wave_mode ? p.wave_nw : p.qg, p2 = p.wave_mode ? p.wave_ds : p.kt, p3 = p.wave_mode ? p.wave_qt : p.pfd;
-    const int p4 = p.wave_mode ? 0 : p.nw, p5 = p.wave_mode ? 1 : p.mw;
+    const int p4 = p.wave_mode ? 0 : p.nw, p5 = p.wave_mode ? 1 : p.mw, p6 = p.wave_mode ? 0 : p.once;
     for (int i = 0; i < N_VARIANTS; i++) {
         const Variant &v = VARIANTS[i];
-        if (v.family == family && v.d == d->head_dim && v.p1 == p1 && v.p2 == p2 && v.p3 == p3 && v.p4 == p4 && v.p5 == p5)
+        if (v.family == family && v.d == d->head_dim && v.p1 == p1 && v.p2 == p2 && v.p3 == p3 && v.p4 == p4 && v.p5 == p5 && v.p6 == p6)
             return &v;
     }
     return nullptr;
@@ -1228,6 +1269,8 @@ void variant_name(const Variant &v, char *buf, size_t n)
 {
     if (v.family == FAMILY_WAVE)
         snprintf(buf, n, "attn_wave_kernel<%d,%d,%d,%d>", v.d, v.p1, v.p2, v.p3);
+    else if (v.p6 && v.p4 == 4)
+        snprintf(buf, n, "attn_bf16_kernel<%d,%d,%d,%d,%d,%d,%d>", v.d, v.p1, v.p2, v.p3, v.p4, v.p5, v.p6);
     else if (v.p5 != 1)
         snprintf(buf, n, "attn_bf16_kernel<%d,%d,%d,%d,%d,%d>", v.d, v.p1, v.p2, v.p3, v.p4, v.p5);
     else if (v.p4 != 4)

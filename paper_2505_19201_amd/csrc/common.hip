@@ -41,7 +41,7 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const u32x4 *src, size
     u32x4 acc = {0u, 0u, 0u, 0u};
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride)
-        acc ^= src[i];
+        acc ^= __builtin_nontemporal_load(src + i);   // read once: the hint keeps the stream from thrashing L2
     const uint32_t fold = acc.x ^ acc.y ^ acc.z ^ acc.w;
     if (fold == never)
         *sink = fold;

@@ -109,7 +109,7 @@ __global__ __launch_bounds__(64 * NWAVE) void project_kernel(ProjArgs args)
                 const int col = s * SS + (lcol < nvalid ? lcol : 0);
 #pragma unroll
                 for (int j = 0; j < NI; j++) {
-                    wr[j] = *reinterpret_cast<const u32x4 *>(wsrc + (int64_t)(j * RPI + lrow) * K + col);
+                    wr[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(wsrc + (int64_t)(j * RPI + lrow) * K + col));   // weights: read once
                     if (j < xj) {   // feature rows are fetched RPI at a time, only as many as exist
                         const int m = min(m0 + j * RPI + lrow, a.m_total - 1);
                         xr[j] = *reinterpret_cast<const u32x4 *>(xsrc + (int64_t)m * K + col);
@@ -149,7 +149,7 @@ __global__ __launch_bounds__(64 * NWAVE) void project_kernel(ProjArgs args)
 #pragma unroll
                 for (int u = 0; u < U; u++) {
                     const int kk = min(k + 32 * u, kw - 32);            // (kw is a multiple of 32; a short tail re-reads and is skipped below)
-                    wf[u] = *reinterpret_cast<const bf16x8 *>(wrow + kk);
+                    wf[u] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8 *>(wrow + kk));   // weights: read once
 #pragma unroll
                     for (int mt = 0; mt < MT; mt++)
                         xf[u][mt] = *reinterpret_cast<const bf16x8 *>(xrow[mt] + kk);

@@ -93,7 +93,7 @@ __global__ __launch_bounds__(256) void expand_partial_kernel(const void *logits,
         for (int j = 0; j < PER_THREAD / 8; j++) {
             const int t0 = begin + j * 2048 + tid * 8;
             if (aligned && t0 + 8 <= vocab) {
-                const u32x4 u = *reinterpret_cast<const u32x4 *>(p + t0);
+                const u32x4 u = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p + t0));   // logits: read once
 #pragma unroll
                 for (int q = 0; q < 4; q++) {
                     x[j * 8 + 2 * q] = __uint_as_float(u[q] << 16);

@@ -14,12 +14,16 @@ VARIANT_CASES = [
     VariantCase("attn_bf16_kernel<64,1,2,1>", 1, 2, 2, 64, 17, 4, 150, 0, 0),
     VariantCase("attn_bf16_kernel<64,1,3,1>", 1, 2, 2, 64, 17, 4, 150, 2, 0),
     VariantCase("attn_bf16_kernel<64,1,4,1>", 1, 2, 2, 64, 17, 4, 200, 2, 0),
-    VariantCase("attn_bf16_kernel<64,1,2,2>", 1, 2, 2, 64, 17, 4, 150, 1, 0),
+    VariantCase("attn_bf16_kernel<64,1,2,2>", 1, 4, 2, 64, 60, 6, 150, 1, 1),
     VariantCase("attn_bf16_kernel<128,1,2,1>", 1, 2, 2, 128, 17, 4, 150, 0, 0),
     VariantCase("attn_bf16_kernel<128,1,3,1>", 1, 2, 2, 128, 17, 4, 150, 2, 0),
     VariantCase("attn_bf16_kernel<128,1,4,1>", 1, 2, 2, 128, 17, 4, 200, 2, 0),
-    VariantCase("attn_bf16_kernel<128,1,1,2>", 1, 2, 2, 128, 17, 4, 150, 1, 0),
-    VariantCase("attn_bf16_kernel<256,1,1,2>", 1, 2, 2, 256, 17, 4, 150, 0, 0),
+    VariantCase("attn_bf16_kernel<128,1,1,2>", 1, 4, 2, 128, 60, 6, 150, 1, 1),
+    VariantCase("attn_bf16_kernel<256,1,1,2>", 1, 4, 2, 256, 60, 6, 150, 0, 1),
+    # the same three with one query group per KV head: K/V loads with the nontemporal hint
+    VariantCase("attn_bf16_kernel<64,1,2,2,4,1,1>", 1, 2, 2, 64, 17, 4, 150, 1, 0),
+    VariantCase("attn_bf16_kernel<128,1,1,2,4,1,1>", 1, 2, 2, 128, 17, 4, 150, 1, 0),
+    VariantCase("attn_bf16_kernel<256,1,1,2,4,1,1>", 1, 2, 2, 256, 17, 4, 150, 0, 0),
     VariantCase("attn_bf16_kernel<64,2,1,2>", 1, 2, 2, 64, 60, 6, 150, 0, 2),
     VariantCase("attn_bf16_kernel<64,4,1,2>", 2, 8, 2, 64, 60, 6, 150, 0, 4),
     VariantCase("attn_bf16_kernel<128,2,1,2>", 1, 2, 2, 128, 60, 6, 150, 0, 2),
@@ -55,21 +59,21 @@ FULL_VERIFY_PLANS = {
     "pixtral": "attn_wave_kernel<128,8,2,1> workgroups=256 splits=1 merge_launch=0",
     "gemma3": "attn_wave_kernel<256,4,4,1> workgroups=256 splits=1 merge_launch=0",
     "smolvlm_b1": "attn_wave_kernel<64,8,2,1> workgroups=256 splits=1 merge_launch=0",
-    "smolvlm_b8": "attn_bf16_kernel<64,1,2,2> workgroups=256 splits=1 merge_launch=0",
-    "smolvlm_b32": "attn_bf16_kernel<64,1,2,2> workgroups=1024 splits=1 merge_launch=0",
+    "smolvlm_b8": "attn_bf16_kernel<64,1,2,2,4,1,1> workgroups=256 splits=1 merge_launch=0",
+    "smolvlm_b32": "attn_bf16_kernel<64,1,2,2,4,1,1> workgroups=1024 splits=1 merge_launch=0",
 }
 
-# 8-wave shapes beyond the one-case-per-variant list: idle waves (6 query tiles), two workgroups per KV head (20 query
-# tiles), and a long ragged key range
+# 8-wave shapes beyond the one-case-per-variant list: idle waves (6 query tiles), idle tile slots (12 query tiles, two
+# per wave), and a long ragged key range
 EXTRA_W8_CASES = [
     VariantCase("attn_bf16_kernel<128,1,1,2,8>", 2, 6, 2, 128, 17, 4, 700, 0, 0, 8),
-    VariantCase("attn_bf16_kernel<128,2,1,2,8>", 1, 10, 2, 128, 60, 6, 333, 0, 0, 8),
-    VariantCase("attn_bf16_kernel<256,1,1,2,8>", 3, 6, 2, 256, 33, 5, 410, 0, 0, 8),
+    VariantCase("attn_bf16_kernel<128,2,1,2,8>", 1, 6, 2, 128, 60, 6, 333, 0, 0, 8),
+    VariantCase("attn_bf16_kernel<256,1,1,2,8>", 3, 4, 2, 256, 33, 5, 410, 0, 0, 8),
 ]
 
 # The 32-sequence launches bench.py times as the streaming regime of the grouped-query configurations
 STREAMING_PLANS = {
-    "llava": "attn_bf16_kernel<128,1,1,2> workgroups=1024 splits=1 merge_launch=0",
+    "llava": "attn_bf16_kernel<128,1,1,2,4,1,1> workgroups=1024 splits=1 merge_launch=0",
     "pixtral": "attn_bf16_kernel<128,2,1,2,8> workgroups=256 splits=1 merge_launch=0",
     "gemma3": "attn_bf16_kernel<256,1,1,2,8> workgroups=256 splits=1 merge_launch=0",
 }
@@ -78,10 +82,10 @@ STREAMING_PLANS = {
 FULL_XATTN_PLANS = {
     "llava": ("attn_wave_kernel<128,8,4,1> workgroups=128 splits=1 merge_launch=0",) * 2,
     "pixtral": ("attn_wave_kernel<128,8,4,1> workgroups=128 splits=1 merge_launch=0",) * 2,
-    "gemma3": ("attn_bf16_kernel<256,1,1,2> workgroups=64 splits=8 merge_launch=1",) * 2,
+    "gemma3": ("attn_bf16_kernel<256,1,1,2,4,1,1> workgroups=64 splits=8 merge_launch=1",) * 2,
     "smolvlm_b1": ("attn_wave_kernel<64,8,2,1> workgroups=64 splits=1 merge_launch=0",) * 2,
     "smolvlm_b8": ("attn_wave_kernel<64,8,1,1> workgroups=256 splits=1 merge_launch=0",) * 2,
-    "smolvlm_b32": ("attn_bf16_kernel<64,1,2,2> workgroups=1024 splits=1 merge_launch=0",) * 2,
+    "smolvlm_b32": ("attn_bf16_kernel<64,1,2,2,4,1,1> workgroups=1024 splits=1 merge_launch=0",) * 2,
 }
 
 
