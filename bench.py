@@ -41,10 +41,11 @@ def verify_bytes_per_launch(cfg) -> int:
     return 2 * cfg.batch * cfg.n_kv_heads * S * cfg.head_dim * e + 2 * cfg.batch * cfg.n_q_heads * cfg.n_tree * cfg.head_dim * e
 
 
-def read_traffic(name: str):
+def read_traffic(name: str, plan: str):
     """HBM traffic per launch of the verification kernel, from the committed summary of the two rocprofv3 --pmc runs
     (FETCH_SIZE, WRITE_SIZE; counters cannot be read from inside this process).  Returns (bytes or None, where the
-    figure comes from: file, the kernel it was measured on and the date of that measurement)."""
+    figure comes from: file, the kernel it was measured on and the date of that measurement).  A figure measured on
+    another kernel than the one the launch plan names now is stale: it is dropped and the source says so."""
     rel = os.path.join("profiles", f"attn_verify_{name}_traffic.txt")
     traffic, kernel, date = None, "?", "?"
     try:
@@ -58,6 +59,8 @@ def read_traffic(name: str):
                 date = val.strip()
     except OSError:
         return None, "no rocprofv3 summary committed for this configuration"
+    if kernel != plan.split(" ")[0]:
+        return None, f"{rel} is stale: measured on {kernel} ({date}), the plan now names {plan.split(' ')[0]}"
     return traffic, f"{rel} (rocprofv3 --pmc FETCH_SIZE/WRITE_SIZE, kernel {kernel}, measured {date})"
 
 
@@ -257,7 +260,7 @@ def run_config(torch, dream, di, args, cfg, steps, warmup, full):
     bytes_launch = verify_bytes_per_launch(cfg)
     achieved = bytes_launch / (launch_us * 1e-6) / 1e9
     plan = dream.dream_attn_plan_describe(desc, T, S)
-    traffic, traffic_source = read_traffic(cfg.name)
+    traffic, traffic_source = read_traffic(cfg.name, plan)
     roofline = {"bound": "hbm", "kernel": "dream_tree_verify_attn: " + plan, "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": traffic, "traffic_source": traffic_source, "bytes_per_launch": bytes_launch,
