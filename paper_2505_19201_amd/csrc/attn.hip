@@ -178,6 +178,9 @@ __device__ __forceinline__ RowOwner row_owner(const AttnArgs &a, int kvh, int qg
 #ifndef DREAM_Q1_WAVES
 #define DREAM_Q1_WAVES 2
 #endif
+#ifndef DREAM_KG2_MAX_WG
+#define DREAM_KG2_MAX_WG 1   // two key groups while a CU would get at most this many 4-wave workgroups (measured: -5 % at 1, +3 % at 4)
+#endif
 #ifndef DREAM_W8Q1_WAVES
 #define DREAM_W8Q1_WAVES 1
 #endif
@@ -382,21 +385,30 @@ __device__ __forceinline__ void wave_lds_fence()
 // L2 (measured at 32 sequences: LLaVA 82.5 -> 71 us, SmolVLM 83.5 -> 74.5 us per launch).  With several query groups per
 // KV head the later groups hit the rows in L2, so those launches use the variant without the hint.  (A run-time choice
 // between the two kinds of load does not survive the compiler: it merges them into plain loads.)
-template <int D, int QG, int KT, int PFD, int NW = 4, int MW = 1, bool ONCE = false>
+template <int QG, int NDT>
+__device__ __forceinline__ void state_merge(WaveState<QG, NDT> &s, const float *src, int lane);
+
+// KG: key groups (1 or 2).  With 2, the 8 waves are two groups of 4: both serve the same (up to 4·QG) query tiles, a step
+// stages 2·KT tiles and each group computes its KT of them; the two partial states of a query tile meet in LDS at the
+// end.  For multi-head shapes with few streams per CU: twice the waves and twice the bytes in flight per workgroup.
+template <int D, int QG, int KT, int PFD, int NW = 4, int MW = 1, bool ONCE = false, int KG = 1>
 __global__ __launch_bounds__(64 * NW, (QG == 1 && D <= 128) ? (NW == 4 ? DREAM_Q1_WAVES : DREAM_W8Q1_WAVES) : 1) void attn_bf16_kernel(AttnArgs a)
 {
     using G = Geom<D, QG, KT>;
+    using GS = Geom<D, QG, KT * KG>;             // what a step stages
+    static_assert(KG == 1 || (KG == 2 && NW == 8), "two key groups: 8 waves");
     constexpr int KSTR = G::KSTR, VSTR = G::VSTR, NDT = G::NDT, NKS = G::NKS;
-    constexpr int CH = 32 * D / 8 / (64 * NW);   // 16-byte chunks per thread per tensor per tile
-    constexpr int ROWS = 64 * NW * 8 / D;        // tile rows one pass of the workgroup covers
-    static_assert(CH >= 1 && CH * ROWS == 32, "a tile is a whole number of passes");
-    constexpr int NLD = KT * CH;   // 16-byte chunks per thread per tensor per step
+    constexpr int QW = NW / KG;                  // waves that own different query tiles
+    constexpr int NT = 64 * NW, LPR = D / 8, CPT = 32 * LPR;   // threads; 16-byte chunks per row and per tile (one tensor)
+    constexpr int NLD = KT * KG * CPT / NT;                    // chunks per thread per tensor per step
+    static_assert(NLD >= 1 && NLD * NT == KT * KG * CPT, "the chunks of a step divide evenly among the threads");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     uint16_t *lds = reinterpret_cast<uint16_t *>(smem_raw);
-    int32_t *lds_parent = reinterpret_cast<int32_t *>(smem_raw + (size_t)2 * G::STAGE_ELEMS * 2);
+    int32_t *lds_parent = reinterpret_cast<int32_t *>(smem_raw + (size_t)2 * GS::STAGE_ELEMS * 2);
 
     const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps bookkeeping in scalar registers
+    const int wave_all = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps bookkeeping in scalar registers
+    const int wave = wave_all % QW, kgrp = wave_all / QW;             // query-tile slot and key group of this wave
     const int c = lane & 15, g = lane >> 4;
 
     // workgroup id -> (K/V stream, query group): ids that share a stream are congruent mod 8 (same XCD)
@@ -420,7 +432,7 @@ __global__ __launch_bounds__(64 * NW, (QG == 1 && D <= 128) ? (NW == 4 ? DREAM_Q
     const int t_begin = split * tps;
     const int t_end = min(t_begin + tps, tiles_total);
     const int n_my = max(t_end - t_begin, 0);
-    const int n_steps = (n_my + KT - 1) / KT;
+    const int n_steps = (n_my + KT * KG - 1) / (KT * KG);
     const int key_end = min(kv_len, t_end * 32);   // keys at or past it belong to nobody or to the next split
 
     const uint16_t *kbase = reinterpret_cast<const uint16_t *>(a.k) + ((int64_t)b * a.n_kv_heads + kvh) * a.s_max * D;
@@ -431,23 +443,34 @@ __global__ __launch_bounds__(64 * NW, (QG == 1 && D <= 128) ? (NW == 4 ? DREAM_Q
     // zero probability); tile indices past this workgroup's range are clamped too, so the number of loads
     // issued never depends on control flow and prefetches stay in flight across iterations.
     u32x4 kreg[PFD][NLD], vreg[PFD][NLD];
-    const int ld_row = tid / (D / 8), ld_col = tid % (D / 8);
+    // chunk j of this thread within a step: tile ld_tile(j) of the step, row ld_row(j), 16-byte column ld_col(j)
+    // (a tile is CPT / NT passes of the workgroup, or, with more threads than a tile has chunks, a pass covers NT / CPT tiles)
+    auto ld_tile = [&](int j) {
+        if constexpr (CPT >= NT)
+            return j / (CPT / NT);
+        else
+            return tid / CPT + j * (NT / CPT);
+    };
+    auto ld_row = [&](int j) {
+        if constexpr (CPT >= NT)
+            return tid / LPR + (j % (CPT / NT)) * (NT / LPR);
+        else
+            return (tid % CPT) / LPR;
+    };
+    const int ld_col = tid % LPR;   // (NT is a multiple of LPR)
     auto load_step = [&](int i, u32x4(&kr)[NLD], u32x4(&vr)[NLD]) {
 #pragma unroll
-        for (int kt = 0; kt < KT; kt++) {
-            const int t = min(t_begin + i * KT + kt, t_end - 1);
-#pragma unroll
-            for (int j = 0; j < CH; j++) {
-                const int key = min(t * 32 + ld_row + j * ROWS, kv_len - 1);
-                const u32x4 *kp = reinterpret_cast<const u32x4 *>(kbase + (int64_t)key * D + ld_col * 8);
-                const u32x4 *vp = reinterpret_cast<const u32x4 *>(vbase + (int64_t)key * D + ld_col * 8);
-                if constexpr (ONCE) {
-                    kr[kt * CH + j] = __builtin_nontemporal_load(kp);
-                    vr[kt * CH + j] = __builtin_nontemporal_load(vp);
-                } else {
-                    kr[kt * CH + j] = *kp;
-                    vr[kt * CH + j] = *vp;
-                }
+        for (int j = 0; j < NLD; j++) {
+            const int t = min(t_begin + i * KT * KG + ld_tile(j), t_end - 1);
+            const int key = min(t * 32 + ld_row(j), kv_len - 1);
+            const u32x4 *kp = reinterpret_cast<const u32x4 *>(kbase + (int64_t)key * D + ld_col * 8);
+            const u32x4 *vp = reinterpret_cast<const u32x4 *>(vbase + (int64_t)key * D + ld_col * 8);
+            if constexpr (ONCE) {
+                kr[j] = __builtin_nontemporal_load(kp);
+                vr[j] = __builtin_nontemporal_load(vp);
+            } else {
+                kr[j] = *kp;
+                vr[j] = *vp;
             }
         }
     };
@@ -464,7 +487,7 @@ __global__ __launch_bounds__(64 * NW, (QG == 1 && D <= 128) ? (NW == 4 ? DREAM_Q
     bool wave_active = false;
 #pragma unroll
     for (int qt = 0; qt < QG; qt++) {
-        RowOwner ro = row_owner(a, kvh, qg, wave, QG, qt, c, NW);
+        RowOwner ro = row_owner(a, kvh, qg, wave, QG, qt, c, QW);
         q_valid[qt] = ro.row >= 0;
         wave_active = wave_active || q_valid[qt];
         const int row = q_valid[qt] ? ro.row : 0;
@@ -505,23 +528,19 @@ __global__ __launch_bounds__(64 * NW, (QG == 1 && D <= 128) ? (NW == 4 ? DREAM_Q
 
     // one step of KT tiles: registers -> LDS stage, barrier, refill the register set, compute from LDS
     auto step = [&](int i, u32x4(&kr)[NLD], u32x4(&vr)[NLD]) {
-        uint16_t *stage = lds + (i & 1) * G::STAGE_ELEMS;
-        {
-            uint16_t *dk = stage + ld_row * KSTR + ld_col * 8, *dv = stage + 32 * KSTR + ld_row * VSTR + ld_col * 8;
+        uint16_t *stage = lds + (i & 1) * GS::STAGE_ELEMS;
 #pragma unroll
-            for (int kt = 0; kt < KT; kt++) {
-#pragma unroll
-                for (int j = 0; j < CH; j++) {
-                    *reinterpret_cast<u32x4 *>(dk + kt * G::TILE_ELEMS + j * ROWS * KSTR) = kr[kt * CH + j];
-                    *reinterpret_cast<u32x4 *>(dv + kt * G::TILE_ELEMS + j * ROWS * VSTR) = vr[kt * CH + j];
-                }
-            }
+        for (int j = 0; j < NLD; j++) {
+            uint16_t *tile = stage + ld_tile(j) * G::TILE_ELEMS;
+            *reinterpret_cast<u32x4 *>(tile + ld_row(j) * KSTR + ld_col * 8) = kr[j];
+            *reinterpret_cast<u32x4 *>(tile + 32 * KSTR + ld_row(j) * VSTR + ld_col * 8) = vr[j];
         }
         __syncthreads();
         load_step(i + PFD, kr, vr);
         if (!wave_active)
             return;
-        tiles_compute<D, QG, KT, D, MW>(stage, (t_begin + i * KT) * 32, P, key_end, a.n_tree, a.scale_log2, qf, qmask, st, c, g);
+        tiles_compute<D, QG, KT, D, MW>(stage + kgrp * KT * G::TILE_ELEMS, (t_begin + (i * KG + kgrp) * KT) * 32, P, key_end, a.n_tree, a.scale_log2, qf,
+                                        qmask, st, c, g);
     };
 
     // every load issued so far (queries, masks, first tiles) has to land before the loop: the in-order
@@ -540,7 +559,18 @@ __global__ __launch_bounds__(64 * NW, (QG == 1 && D <= 128) ? (NW == 4 ? DREAM_Q
             if (i + pf < n_steps)
                 step(i + pf, kreg[pf], vreg[pf]);
     }
-    __syncthreads();   // every wave is done with the last tile: the stage areas can be reused for the output rows
+    __syncthreads();   // every wave is done with the last tile: the stage areas can be reused for states and output rows
+    constexpr int STATE = StateGeom<D, QG>::STATE_FLOATS;
+    if (KG == 2) {
+        // the second key group parks its states; the first adds them to its own (a barrier in between, so no early exit)
+        float *sbuf = reinterpret_cast<float *>(smem_raw) + wave * STATE;
+        if (kgrp == 1 && wave_active)
+            state_store<QG, NDT>(st, sbuf, lane);
+        __syncthreads();
+        if (kgrp == 1 || !wave_active)
+            return;
+        state_merge<QG, NDT>(st, sbuf, lane);
+    }
     if (!wave_active)
         return;
 
@@ -563,12 +593,13 @@ __global__ __launch_bounds__(64 * NW, (QG == 1 && D <= 128) ? (NW == 4 ? DREAM_Q
     // as whole 16-byte-per-lane rows, full cache lines per instruction, with the nontemporal hint (nobody in this
     // launch reads them; measured together with the staging: 82.5 -> 78 us at 32 LLaVA sequences, either alone nothing).
     constexpr float LN2 = 0.6931471805599453f;
-    constexpr int OSTR = D + 8, LPR = D / 8, RPP = 64 / LPR;   // staging row stride; lanes per row; rows per store instruction
-    static_assert((size_t)NW * 16 * OSTR * 2 <= (size_t)2 * G::STAGE_ELEMS * 2, "the output staging reuses the tile stages");
-    uint16_t *ot = lds + wave * 16 * OSTR;
+    constexpr int OSTR = D + 8, RPP = 64 / LPR;   // staging row stride; rows per store instruction (LPR lanes per row)
+    constexpr size_t OT_BASE = KG == 2 ? (size_t)QW * STATE * sizeof(float) : 0;   // behind the parked states, which may still be read
+    static_assert(OT_BASE + (size_t)QW * 16 * OSTR * 2 <= (size_t)2 * GS::STAGE_ELEMS * 2, "states and output staging reuse the tile stages");
+    uint16_t *ot = reinterpret_cast<uint16_t *>(smem_raw + OT_BASE) + wave * 16 * OSTR;
 #pragma unroll
     for (int qt = 0; qt < QG; qt++) {
-        RowOwner ro = row_owner(a, kvh, qg, wave, QG, qt, c, NW);
+        RowOwner ro = row_owner(a, kvh, qg, wave, QG, qt, c, QW);
         const float l = st.l[qt];
         const float inv = l > 0.0f ? 1.0f / l : 0.0f;
 #pragma unroll
@@ -585,7 +616,7 @@ __global__ __launch_bounds__(64 * NW, (QG == 1 && D <= 128) ? (NW == 4 ? DREAM_Q
 #pragma unroll
         for (int pass = 0; pass < 16 / RPP; pass++) {
             const int r2 = pass * RPP + lane / LPR, col = (lane % LPR) * 8;
-            RowOwner ro2 = row_owner(a, kvh, qg, wave, QG, qt, r2, NW);
+            RowOwner ro2 = row_owner(a, kvh, qg, wave, QG, qt, r2, QW);
             if (ro2.row >= 0) {
                 uint16_t *op = reinterpret_cast<uint16_t *>(a.out) + (((int64_t)b * a.n_q + ro2.row) * a.n_q_heads + ro2.head) * D + col;
                 __builtin_nontemporal_store(*reinterpret_cast<const u32x4 *>(ot + r2 * OSTR + col), reinterpret_cast<u32x4 *>(op));
@@ -960,6 +991,7 @@ struct Plan {
     int nw;           // waves per workgroup of the shared-tile kernel (4 or 8)
     int mw;           // 64-bit words of a node's visibility mask (1, or 4 for trees above 64 nodes)
     int once;         // 1: the variant whose K/V loads carry the nontemporal hint (one query group per KV head)
+    int kg;           // key groups per workgroup of the shared-tile kernel (1; 2 = 8 waves as two groups of 4)
     bool wave_mode;   // one query tile per workgroup, waves split the keys, no key split (attn_wave_kernel)
     int wave_nw;      // waves per workgroup in that mode
     int wave_ds;      // workgroups that share the output columns of a query tile in that mode (1, 2 or 4)
@@ -1000,6 +1032,7 @@ int make_plan(const dream_attn_desc *d, int n_q, int64_t max_kv_len, Plan *p)
     p->nw = 4;
     p->mw = 1;
     p->once = 0;
+    p->kg = 1;
     p->n_qg = ceil_div(n_qtiles, 4 * qg);
     // few, short streams with at most 16 query tiles each: a workgroup per query tile fills at least half the chip
     // without splitting keys, which saves the merge launch (short: up to 64 key tiles at head_dim 128, twice that
@@ -1041,7 +1074,7 @@ int make_plan(const dream_attn_desc *d, int n_q, int64_t max_kv_len, Plan *p)
         const int qg8_max = d->head_dim == 256 ? 1 : 2;
         int qg8 = q_tiles_override() > 0 ? (q_tiles_override() > qg8_max ? qg8_max : q_tiles_override()) : (n_qtiles > 8 ? qg8_max : 1);
         const bool can8 = d->dtype == DREAM_BF16 && d->head_dim >= 128 && kv_splits_override() <= 1 && tw != 4;
-        const bool want8 = tw == 8 || (q_tiles_override() == 0 && n_qtiles > 4 && base >= 256);
+        const bool want8 = n_qtiles > 4 && (tw == 8 || (q_tiles_override() == 0 && base >= 256));   // (up to 4 tiles: see the two key groups below)
         // (the 8-wave variants read K/V with the nontemporal hint, so a KV head must not need two of them)
         if (can8 && want8 && ceil_div(n_qtiles, 8 * qg8) == 1) {
             p->nw = 8;
@@ -1088,6 +1121,12 @@ int make_plan(const dream_attn_desc *d, int n_q, int64_t max_kv_len, Plan *p)
         p->pfd = DREAM_W8_PFD;
     } else if (qg == 1 && p->pfd == 2 && p->n_qg == 1) {
         p->once = 1;
+        // multi-head shapes that leave a CU with at most DREAM_KG2_MAX_WG 4-wave workgroups: 8 waves as two key groups
+        const int tw = tile_waves_override();
+        if (s == 1 && d->head_dim <= 128 && tw != 4 && (tw == 8 || groups <= 256 * DREAM_KG2_MAX_WG)) {
+            p->nw = 8;
+            p->kg = 2;
+        }
     }
     p->state_floats = (size_t)qg * (d->head_dim / 16) * 256 + (size_t)qg * 2 * 64;
     p->off_part = DREAM_WORKSPACE_MIN_BYTES;
@@ -1110,6 +1149,7 @@ void make_wide_plan(const dream_attn_desc *d, int n_q, Plan *p)
     p->nw = 4;
     p->mw = 4;
     p->once = 0;
+    p->kg = 1;
     p->n_qg = ceil_div(G * p->tiles_per_head, 4);
     p->n_splits = 1;
     p->n_groups = (int)(base * p->n_qg);
@@ -1141,13 +1181,13 @@ int validate_desc(const dream_attn_desc *d, const char *who)
 
 // The dynamic-LDS limit of a kernel is raised once (dream_init does it for every variant up front; a variant
 // that is reached first by a call does it then).  Two threads may both set it once: harmless.
-template <int D, int QG, int KT, int PFD, int NW = 4, int MW = 1, bool ONCE = false>
+template <int D, int QG, int KT, int PFD, int NW = 4, int MW = 1, bool ONCE = false, int KG = 1>
 int ensure_bf16_lds()
 {
-    using G = Geom<D, QG, KT>;
+    using G = Geom<D, QG, KT * KG>;
     static std::atomic<bool> attr_set{false};
     if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_kernel<D, QG, KT, PFD, NW, MW, ONCE>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_bf16_kernel<D, QG, KT, PFD, NW, MW, ONCE, KG>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)G::LDS_BYTES) != hipSuccess)
             return fail(DREAM_ERR_HIP, "attention: cannot reserve %zu bytes of LDS", G::LDS_BYTES);
         attr_set = true;
@@ -1155,11 +1195,11 @@ int ensure_bf16_lds()
     return DREAM_OK;
 }
 
-template <int D, int QG, int KT, int PFD, int NW = 4, int MW = 1, bool ONCE = false>
+template <int D, int QG, int KT, int PFD, int NW = 4, int MW = 1, bool ONCE = false, int KG = 1>
 int launch_bf16(const AttnArgs &a, const Plan &p, hipStream_t st)
 {
-    using G = Geom<D, QG, KT>;
-    if (int rc = ensure_bf16_lds<D, QG, KT, PFD, NW, MW, ONCE>())
+    using G = Geom<D, QG, KT * KG>;
+    if (int rc = ensure_bf16_lds<D, QG, KT, PFD, NW, MW, ONCE, KG>())
         return rc;
     if (ONCE && a.n_qg != 1)
         return fail(DREAM_ERR_INVALID_ARG, "attention: the read-once kernel variant needs one query group per KV head, not %d", a.n_qg);
@@ -1167,7 +1207,7 @@ int launch_bf16(const AttnArgs &a, const Plan &p, hipStream_t st)
         return fail(DREAM_ERR_INVALID_ARG, "attention: the 8-wave shared-tile kernel does not split the key range");
     if (a.mask_words > MW)
         return fail(DREAM_ERR_INVALID_ARG, "attention: a tree of %d nodes needs %d mask words, this kernel has %d", a.n_tree, a.mask_words, MW);
-    hipLaunchKernelGGL((attn_bf16_kernel<D, QG, KT, PFD, NW, MW, ONCE>), dim3(p.grid), dim3(64 * NW), G::LDS_BYTES, st, a);
+    hipLaunchKernelGGL((attn_bf16_kernel<D, QG, KT, PFD, NW, MW, ONCE, KG>), dim3(p.grid), dim3(64 * NW), G::LDS_BYTES, st, a);
     int rc = check_launch("attn_bf16_kernel");
     if (rc || p.n_splits == 1)
         return rc;
@@ -1214,15 +1254,16 @@ int launch_wave(const AttnArgs &a, const Plan &p, hipStream_t st)
 // its dynamic-LDS limit.  The launch, dream_init, dream_attn_plan_describe and dream_attn_variants all read it.
 enum { FAMILY_TILE = 0, FAMILY_WAVE = 1 };
 struct Variant {
-    int family, d, p1, p2, p3, p4, p5, p6;   // tile: (QG, KT, PFD, waves, mask words, read-once); wave: (NW, DS, QT, 0, 1, 0)
+    int family, d, p1, p2, p3, p4, p5, p6, p7;   // tile: (QG, KT, PFD, waves, mask words, read-once, key groups); wave: (NW, DS, QT, 0, 1, 0, 1)
     int (*launch)(const AttnArgs &, const Plan &, hipStream_t);
     int (*ensure)();
 };
-#define TILE_VARIANT(D, QG, KT, PFD) {FAMILY_TILE, D, QG, KT, PFD, 4, 1, 0, &launch_bf16<D, QG, KT, PFD>, &ensure_bf16_lds<D, QG, KT, PFD>}
-#define ONCE_VARIANT(D, QG, KT, PFD) {FAMILY_TILE, D, QG, KT, PFD, 4, 1, 1, &launch_bf16<D, QG, KT, PFD, 4, 1, true>, &ensure_bf16_lds<D, QG, KT, PFD, 4, 1, true>}
-#define WIDE_VARIANT(D, QG, KT, PFD) {FAMILY_TILE, D, QG, KT, PFD, 4, 4, 0, &launch_bf16<D, QG, KT, PFD, 4, 4>, &ensure_bf16_lds<D, QG, KT, PFD, 4, 4>}
-#define TILE8_VARIANT(D, QG, KT, PFD) {FAMILY_TILE, D, QG, KT, PFD, 8, 1, 1, &launch_bf16<D, QG, KT, PFD, 8, 1, true>, &ensure_bf16_lds<D, QG, KT, PFD, 8, 1, true>}
-#define WAVE_VARIANT(D, NW, DS, QT) {FAMILY_WAVE, D, NW, DS, QT, 0, 1, 0, &launch_wave<D, NW, DS, QT>, &ensure_wave_lds<D, NW, DS, QT>}
+#define TILE_VARIANT(D, QG, KT, PFD) {FAMILY_TILE, D, QG, KT, PFD, 4, 1, 0, 1, &launch_bf16<D, QG, KT, PFD>, &ensure_bf16_lds<D, QG, KT, PFD>}
+#define ONCE_VARIANT(D, QG, KT, PFD) {FAMILY_TILE, D, QG, KT, PFD, 4, 1, 1, 1, &launch_bf16<D, QG, KT, PFD, 4, 1, true>, &ensure_bf16_lds<D, QG, KT, PFD, 4, 1, true>}
+#define KG2_VARIANT(D, QG, KT, PFD) {FAMILY_TILE, D, QG, KT, PFD, 8, 1, 1, 2, &launch_bf16<D, QG, KT, PFD, 8, 1, true, 2>, &ensure_bf16_lds<D, QG, KT, PFD, 8, 1, true, 2>}
+#define WIDE_VARIANT(D, QG, KT, PFD) {FAMILY_TILE, D, QG, KT, PFD, 4, 4, 0, 1, &launch_bf16<D, QG, KT, PFD, 4, 4>, &ensure_bf16_lds<D, QG, KT, PFD, 4, 4>}
+#define TILE8_VARIANT(D, QG, KT, PFD) {FAMILY_TILE, D, QG, KT, PFD, 8, 1, 1, 1, &launch_bf16<D, QG, KT, PFD, 8, 1, true>, &ensure_bf16_lds<D, QG, KT, PFD, 8, 1, true>}
+#define WAVE_VARIANT(D, NW, DS, QT) {FAMILY_WAVE, D, NW, DS, QT, 0, 1, 0, 1, &launch_wave<D, NW, DS, QT>, &ensure_wave_lds<D, NW, DS, QT>}
 const Variant VARIANTS[] = {
     // shared-tile kernel, one query tile per wave: a short key range in one step (2-4 tiles), or streamed
     TILE_VARIANT(64, 1, 2, 1), TILE_VARIANT(64, 1, 3, 1), TILE_VARIANT(64, 1, 4, 1), TILE_VARIANT(64, 1, 2, 2),
@@ -1232,6 +1273,8 @@ const Variant VARIANTS[] = {
     TILE_VARIANT(64, 2, 1, 2), TILE_VARIANT(64, 4, 1, 2), TILE_VARIANT(128, 2, 1, 2), TILE_VARIANT(128, 4, 1, 1), TILE_VARIANT(256, 2, 1, 1),
     // streamed, the workgroup the only reader of its K/V rows (one query group per KV head): name arguments ...,4,1,1
     ONCE_VARIANT(64, 1, 2, 2), ONCE_VARIANT(128, 1, 1, 2), ONCE_VARIANT(256, 1, 1, 2),
+    // the same with 8 waves as two key groups (few streams per CU): name arguments ...,8,1,1,2
+    KG2_VARIANT(64, 1, 2, 2), KG2_VARIANT(128, 1, 1, 2),
     // 8 waves per workgroup (unsplit key range, grouped queries, always the only reader): a fifth name argument 8
     TILE8_VARIANT(128, 1, 1, DREAM_W8_PFD), TILE8_VARIANT(128, 2, 1, DREAM_W8_PFD), TILE8_VARIANT(256, 1, 1, DREAM_W8_PFD),
     // trees of 65-256 nodes (four mask words): a sixth name argument 4
@@ -1247,6 +1290,7 @@ const Variant VARIANTS[] = {
 #undef TILE_VARIANT
 #undef TILE8_VARIANT
 #undef ONCE_VARIANT
+#undef KG2_VARIANT
 #undef WIDE_VARIANT
 #undef WAVE_VARIANT
 constexpr int N_VARIANTS = sizeof(VARIANTS) / sizeof(VARIANTS[0]);
@@ -1256,10 +1300,10 @@ const Variant *find_variant(const dream_attn_desc *d, const Plan &p)
 {
     const int family = p.wave_mode ? FAMILY_WAVE : FAMILY_TILE;
     const int p1 = p.wave_mode ? p.wave_nw : p.qg, p2 = p.wave_mode ? p.wave_ds : p.kt, p3 = p.wave_mode ? p.wave_qt : p.pfd;
-    const int p4 = p.wave_mode ? 0 : p.nw, p5 = p.wave_mode ? 1 : p.mw, p6 = p.wave_mode ? 0 : p.once;
+    const int p4 = p.wave_mode ? 0 : p.nw, p5 = p.wave_mode ? 1 : p.mw, p6 = p.wave_mode ? 0 : p.once, p7 = p.wave_mode ? 1 : p.kg;
     for (int i = 0; i < N_VARIANTS; i++) {
         const Variant &v = VARIANTS[i];
-        if (v.family == family && v.d == d->head_dim && v.p1 == p1 && v.p2 == p2 && v.p3 == p3 && v.p4 == p4 && v.p5 == p5 && v.p6 == p6)
+        if (v.family == family && v.d == d->head_dim && v.p1 == p1 && v.p2 == p2 && v.p3 == p3 && v.p4 == p4 && v.p5 == p5 && v.p6 == p6 && v.p7 == p7)
             return &v;
     }
     return nullptr;
@@ -1269,6 +1313,8 @@ void variant_name(const Variant &v, char *buf, size_t n)
 {
     if (v.family == FAMILY_WAVE)
         snprintf(buf, n, "attn_wave_kernel<%d,%d,%d,%d>", v.d, v.p1, v.p2, v.p3);
+    else if (v.p7 != 1)
+        snprintf(buf, n, "attn_bf16_kernel<%d,%d,%d,%d,%d,%d,%d,%d>", v.d, v.p1, v.p2, v.p3, v.p4, v.p5, v.p6, v.p7);
     else if (v.p6 && v.p4 == 4)
         snprintf(buf, n, "attn_bf16_kernel<%d,%d,%d,%d,%d,%d,%d>", v.d, v.p1, v.p2, v.p3, v.p4, v.p5, v.p6);
     else if (v.p5 != 1)

@@ -20,15 +20,18 @@ VARIANT_CASES = [
     VariantCase("attn_bf16_kernel<128,1,4,1>", 1, 2, 2, 128, 17, 4, 200, 2, 0),
     VariantCase("attn_bf16_kernel<128,1,1,2>", 1, 4, 2, 128, 60, 6, 150, 1, 1),
     VariantCase("attn_bf16_kernel<256,1,1,2>", 1, 4, 2, 256, 60, 6, 150, 0, 1),
-    # the same three with one query group per KV head: K/V loads with the nontemporal hint
-    VariantCase("attn_bf16_kernel<64,1,2,2,4,1,1>", 1, 2, 2, 64, 17, 4, 150, 1, 0),
-    VariantCase("attn_bf16_kernel<128,1,1,2,4,1,1>", 1, 2, 2, 128, 17, 4, 150, 1, 0),
+    # the same three with one query group per KV head: K/V loads with the nontemporal hint (waves = 4: not the two-key-group form)
+    VariantCase("attn_bf16_kernel<64,1,2,2,4,1,1>", 1, 2, 2, 64, 17, 4, 150, 1, 0, 4),
+    VariantCase("attn_bf16_kernel<128,1,1,2,4,1,1>", 1, 2, 2, 128, 17, 4, 150, 1, 0, 4),
     VariantCase("attn_bf16_kernel<256,1,1,2,4,1,1>", 1, 2, 2, 256, 17, 4, 150, 0, 0),
     VariantCase("attn_bf16_kernel<64,2,1,2>", 1, 2, 2, 64, 60, 6, 150, 0, 2),
     VariantCase("attn_bf16_kernel<64,4,1,2>", 2, 8, 2, 64, 60, 6, 150, 0, 4),
     VariantCase("attn_bf16_kernel<128,2,1,2>", 1, 2, 2, 128, 60, 6, 150, 0, 2),
     VariantCase("attn_bf16_kernel<128,4,1,1>", 2, 8, 2, 128, 60, 6, 150, 0, 4),
     VariantCase("attn_bf16_kernel<256,2,1,1>", 1, 4, 2, 256, 60, 6, 150, 0, 2),
+    # 8 waves as two key groups (multi-head shapes with few streams per CU)
+    VariantCase("attn_bf16_kernel<64,1,2,2,8,1,1,2>", 2, 4, 4, 64, 60, 6, 333, 1, 0, 8),
+    VariantCase("attn_bf16_kernel<128,1,1,2,8,1,1,2>", 2, 4, 4, 128, 60, 6, 333, 1, 0, 8),
     # 8 waves per workgroup: 8 query tiles of a KV head (one per wave), 16 (two per wave), head_dim 256
     VariantCase("attn_bf16_kernel<128,1,1,2,8>", 2, 4, 2, 128, 60, 6, 150, 0, 0, 8),
     VariantCase("attn_bf16_kernel<128,2,1,2,8>", 2, 8, 2, 128, 60, 6, 150, 0, 0, 8),
@@ -59,13 +62,16 @@ FULL_VERIFY_PLANS = {
     "pixtral": "attn_wave_kernel<128,8,2,1> workgroups=256 splits=1 merge_launch=0",
     "gemma3": "attn_wave_kernel<256,4,4,1> workgroups=256 splits=1 merge_launch=0",
     "smolvlm_b1": "attn_wave_kernel<64,8,2,1> workgroups=256 splits=1 merge_launch=0",
-    "smolvlm_b8": "attn_bf16_kernel<64,1,2,2,4,1,1> workgroups=256 splits=1 merge_launch=0",
+    "smolvlm_b8": "attn_bf16_kernel<64,1,2,2,8,1,1,2> workgroups=256 splits=1 merge_launch=0",
     "smolvlm_b32": "attn_bf16_kernel<64,1,2,2,4,1,1> workgroups=1024 splits=1 merge_launch=0",
 }
 
 # 8-wave shapes beyond the one-case-per-variant list: idle waves (6 query tiles), idle tile slots (12 query tiles, two
 # per wave), and a long ragged key range
 EXTRA_W8_CASES = [
+    # two key groups: idle query-tile waves, sequences whose key range is shorter than one step, an odd number of tiles
+    VariantCase("attn_bf16_kernel<64,1,2,2,8,1,1,2>", 3, 2, 2, 64, 17, 4, 170, 1, 0, 8),
+    VariantCase("attn_bf16_kernel<128,1,1,2,8,1,1,2>", 2, 2, 2, 128, 33, 5, 225, 1, 0, 8),
     VariantCase("attn_bf16_kernel<128,1,1,2,8>", 2, 6, 2, 128, 17, 4, 700, 0, 0, 8),
     VariantCase("attn_bf16_kernel<128,2,1,2,8>", 1, 6, 2, 128, 60, 6, 333, 0, 0, 8),
     VariantCase("attn_bf16_kernel<256,1,1,2,8>", 3, 4, 2, 256, 33, 5, 410, 0, 0, 8),
