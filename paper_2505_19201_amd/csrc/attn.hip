@@ -4,26 +4,28 @@
 // see: the whole cached prefix plus its ancestors in the draft tree (Section 3.1, tree-masking
 // paragraph); verification includes the node itself, the draft's cross-attention does not.
 //
-// bf16 path (attn_bf16_kernel).  A workgroup serves one (sequence, KV head, key-range split, query
+// bf16, shared tiles (attn_bf16_kernel).  A workgroup serves one (sequence, KV head, key-range split, query
 // group).  The query rows that share a KV head - every tree row of every query head of the GQA
-// group - are cut into 16-row tiles; a query group is 4*QG of them and each of the 4 waves owns QG.
-// All 256 threads stream the key range in 32-key K/V tiles with 16-byte coalesced loads kept two
-// or three tiles ahead in registers, park each tile in one of two LDS stages (one barrier per
-// tile), and every wave reads the tile's MFMA fragments from LDS: a K/V byte leaves HBM once and
-// serves all tree rows and all heads of the group.  Scores are formed transposed, S^T = K Q^T, with
+// group - are cut into 16-row tiles; each wave owns QG of them (4 waves, or 8 waves for grouped-query shapes, or
+// 8 waves as two key groups for multi-head shapes with one workgroup per CU).  All threads stream the key range in
+// 32-key K/V tiles with 16-byte coalesced loads kept one or two steps ahead in registers, park each tile in one of
+// two LDS stages (one barrier per step), and every wave reads the tile's MFMA fragments from LDS: a K/V byte leaves
+// HBM once and serves all tree rows and all heads of the group.  Scores are formed transposed, S^T = K Q^T, with
 // v_mfma_f32_16x16x32_bf16, so a lane owns one query column: the online-softmax state is a
 // per-lane scalar and the fp32 score registers, converted to bf16, already are the B operand of
 // the second contraction O^T += V^T P^T, whose A operand (V transposed) comes from the LDS
 // transpose read ds_read_b64_tr_b16.  The softmax reference of a column is raised only when a
-// score exceeds it by 8 octaves, so accumulators are rescaled a handful of times per call.
+// score exceeds it by 8 octaves, so accumulators are rescaled a handful of times per call.  Where a workgroup is the
+// only reader of its K/V rows the loads carry the nontemporal hint; output rows leave as whole lines with it.
 //
 // One CU can keep only a few tens of KB of loads in flight, so a short stream is bandwidth-starved
-// unless all 256 CUs pull a share of it: when B * Hkv * query groups is small the key range is split
-// over several workgroups, each writes its (reference, sum, O) state to the workspace, and
+// unless all 256 CUs pull a share of it: when B * Hkv * query groups is small either attn_wave_kernel serves a
+// query tile per workgroup in one launch (waves stream disjoint key tiles and merge in LDS), or the key range is
+// split over several workgroups, each writes its (reference, sum, O) state to the workspace, and
 // attn_merge_kernel merges the states of a group in split order (deterministic) and writes the
-// rows.  (A last-arrival merge inside the kernel needs device-scope fences, whose L2 write-back
-// and invalidate cost more than the second launch.)  Workgroups that read the same K/V stream (the
-// query groups of one split) get ids congruent mod 8 so that they run on one XCD and share its L2.
+// rows.  (A merge across workgroups inside one launch costs more than the second launch: the L2s of the XCDs are not
+// coherent with each other.)  Workgroups that read the same K/V stream get ids congruent mod 8 so that they run on one
+// XCD and share its L2.
 //
 // fp32 path (attn_f32_kernel): plain vector-ALU kernel, one workgroup per (query row, head,
 // sequence), used for float32 tensors (the small correctness configuration).
@@ -175,14 +177,15 @@ __device__ __forceinline__ RowOwner row_owner(const AttnArgs &a, int kvh, int qg
 // The softmax reference of a column is only raised when a score exceeds it by more than this many
 // octaves, so exp2(score - reference) stays below 2^8 and the accumulators are seldom rescaled.
 #define DREAM_SOFTMAX_SLACK 8.0f
+// Build-time knobs of the launch shapes (each value is the measured best):
 #ifndef DREAM_Q1_WAVES
-#define DREAM_Q1_WAVES 2
+#define DREAM_Q1_WAVES 2     // waves per SIMD the 4-wave one-tile-per-wave variants are compiled for (3: same speed; 4: spills)
 #endif
 #ifndef DREAM_KG2_MAX_WG
 #define DREAM_KG2_MAX_WG 1   // two key groups while a CU would get at most this many 4-wave workgroups (measured: -5 % at 1, +3 % at 4)
 #endif
 #ifndef DREAM_W8Q1_WAVES
-#define DREAM_W8Q1_WAVES 1
+#define DREAM_W8Q1_WAVES 1   // the same for the 8-wave variants (2 workgroups per CU would need 128 registers: spills, slower)
 #endif
 #ifndef DREAM_W8_PFD
 #define DREAM_W8_PFD 2   // steps in flight of the 8-wave shared-tile form
