@@ -111,7 +111,7 @@ def main() -> int:
                 r["streaming_regime"] = streaming_regime(torch, dream, di, di.CONFIGS[name])
             out["configs"][name] = {"step_latency_us": r["step_latency_us"], "tokens_per_s": r["value"], "streaming_regime": r.get("streaming_regime"),
                                     "tokens_per_s_at_paper_tau": r["tokens_per_s_at_paper_tau"], "phase_us": r["phase_us"],
-                                    "per_request_us": r["per_request_us"], "roofline": r["roofline"], "read_ceiling": r["read_ceiling"],
+                                    "per_request_us": r["per_request_us"], "per_call_us": r["per_call_us"], "roofline": r["roofline"], "read_ceiling": r["read_ceiling"],
                                     "workload": r["config"]["workload"]}
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(cfg, args.layers or cfg.n_layers, out["config"]["tokens_per_step"])
@@ -256,6 +256,8 @@ def run_config(torch, dream, di, args, cfg, steps, warmup, full):
     torch.cuda.synchronize()
     compress_lse_us = graph_time_us(torch, lambda: [compress_with_lse() for _ in range(4)], reps=5) / 4
 
+    accept_call_us = graph_time_us(torch, lambda: [phase_accept() for _ in range(8)], reps=5) / 8
+    xattn_call_us = graph_time_us(torch, lambda: [phase_xattn() for _ in range(2)], reps=5) / (2 * len(levels))
     launch_us = phase_ms[0] * 1e3 / L
     bytes_launch = verify_bytes_per_launch(cfg)
     achieved = bytes_launch / (launch_us * 1e-6) / 1e9
@@ -278,6 +280,8 @@ def run_config(torch, dream, di, args, cfg, steps, warmup, full):
                    "kv_splits": args.splits or "auto"},
         "phase_us": {n: round(ms * 1e3, 2) for (n, _), ms in zip(phases, phase_ms)},
         "per_request_us": {"visual_compress": round(compress_us, 2), "visual_compress_given_row_lse": round(compress_lse_us, 2)},
+        # the phases above are one graph each, so each carries a graph launch (several us); per call inside a graph:
+        "per_call_us": {"accept_path": round(accept_call_us, 2), "draft_xattn_level": round(xattn_call_us, 2)},
         "step_with_compress_us": round(ms_per_step * 1e3 + compress_us, 2),
         "tokens_per_s_at_paper_tau": round(B * PAPER_TAU.get(cfg.name, 0.0) / (ms_per_step * 1e-3), 1),
         "roofline": roofline,
