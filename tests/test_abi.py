@@ -288,3 +288,24 @@ def test_header_compiles_as_c_and_host_calls_work(lib, tmp_path):
                    check=True, capture_output=True, text=True)
     out = subprocess.run([exe], check=True, capture_output=True, text=True).stdout
     assert out.startswith("attn_wave_kernel<128,8,2,1>")
+
+
+def test_every_plan_names_a_built_variant(lib):
+    """Host-only sweep of shapes (batch, heads, grouping, head_dim, rows, key range): whatever the launch plan chooses,
+    the variant exists (dream_attn_plan_describe fails with 'not built' otherwise) and its name is in the variant list."""
+    built = set(dream.dream_attn_variants())
+    seen = set()
+    for D in (64, 128, 256):
+        for hkv, g in ((1, 1), (2, 4), (8, 1), (8, 2), (8, 4), (32, 1), (4, 8)):
+            for B in (1, 2, 3, 4, 7, 8, 16, 32, 64, 100):
+                for n_q in (1, 10, 16, 17, 33, 60, 64, 65, 130, 256):
+                    for kv in (n_q, 40, 150, 700, 1340, 2600, 9000):
+                        if kv < n_q:
+                            continue
+                        desc = dream.attn_desc(B, hkv * g, hkv, D, dream.BF16, kv + 3)
+                        plan = dream.dream_attn_plan_describe(desc, n_q, kv)
+                        name = plan.split(" ")[0]
+                        assert name in built, (D, hkv, g, B, n_q, kv, plan)
+                        assert dream.dream_tree_verify_attn_workspace(desc, n_q, kv) >= 256
+                        seen.add(name)
+    assert len(seen) >= 25, sorted(built - seen)   # the sweep reaches most of the table without any override

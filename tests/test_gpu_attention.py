@@ -125,6 +125,31 @@ def test_trees_above_64_nodes(gu):
     assert np.abs(got32 - want32).max() <= TOL["f32"]
 
 
+def test_seeded_random_shapes_with_the_automatic_plan(gu):
+    """48 seeded shapes (batch, head grouping, head_dim, tree size, ragged prefix lengths incl. empty ones) through
+    whatever kernel the launch plan picks, every element against the oracle; the set of plans reached is reported."""
+    rng = np.random.default_rng(20250519)
+    plans = set()
+    for i in range(48):
+        D = int(rng.choice([64, 128, 256]))
+        hkv, g = [(1, 1), (2, 1), (2, 2), (2, 4), (4, 1), (8, 1), (3, 2)][int(rng.integers(7))]
+        B = int(rng.integers(1, 6))
+        T = int(rng.choice([1, 7, 16, 17, 33, 60, 64, 90]))
+        depth = min(6, T - 1)
+        prefix = int(rng.choice([0, 5, 31, 32, 100, 257, 700]))
+        n_vis = (prefix * 3) // 4
+        cfg = di.Config("rand%d" % i, "bf16", B, hkv * g, hkv, D, hkv * g * D, n_vis, prefix - n_vis, T, depth, 1, 4, 1000, 1, 200 + i)
+        pl = [prefix] + [int(rng.integers(0, prefix + 1)) for _ in range(B - 1)]
+        x = di.verify_inputs(cfg, prefix_len=pl)
+        plans.add(gu.verify_plan(x).split(" ")[0])
+        got, lse = gu.run_verify(x)
+        want, want_lse = oracle.tree_attn(x.q, x.k, x.v, "bf16", x.prefix_len, x.parent, True)
+        assert np.isfinite(got).all(), (i, cfg)
+        assert np.abs(got - want).max() <= TOL["bf16"], (i, cfg, np.abs(got - want).max())
+        assert np.abs(lse - want_lse).max() <= 2e-3, (i, cfg)
+    assert len(plans) >= 6, plans
+
+
 def test_custom_scale(gu):
     cfg = _cfg("scale", "bf16", 1, 4, 4, 64, 80, 20, 30, 5, 42)
     x = di.verify_inputs(cfg)
