@@ -150,6 +150,17 @@ def test_seeded_random_shapes_with_the_automatic_plan(gu):
     assert len(plans) >= 6, plans
 
 
+def test_more_query_rows_than_tree_nodes(gu):
+    """dream_draft_xattn with 100 query rows that name nodes of a 60-node tree (nodes repeat): every row against the oracle."""
+    cfg = _cfg("manyrows", "bf16", 2, 4, 2, 128, 150, 43, 60, 6, 46)
+    x = di.verify_inputs(cfg, prefix_len=[193, 80], streams=(di.STREAM_XQ, di.STREAM_XK, di.STREAM_XV))
+    rng = np.random.default_rng(5)
+    nodes = rng.integers(0, 60, size=(cfg.batch, 100)).astype(np.int32)
+    got, qsel = gu.run_xattn(x, nodes, nodes)
+    want, _ = oracle.tree_attn(qsel, x.k, x.v, "bf16", x.prefix_len, x.parent, False, q_node=nodes)
+    assert np.abs(got - want).max() <= TOL["bf16"]
+
+
 def test_custom_scale(gu):
     cfg = _cfg("scale", "bf16", 1, 4, 4, 64, 80, 20, 30, 5, 42)
     x = di.verify_inputs(cfg)
