@@ -13,7 +13,7 @@ graph per phase with HIP events between the graph launches, on the launching str
 breakdown and the time of the verification block, from which the roofline figure of the dominant kernel
 is derived.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line.
 """
 from __future__ import annotations
 
