@@ -441,7 +441,7 @@ __global__ __launch_bounds__(64 * NW, (QG == 1 && D <= 128) ? (NW == 4 ? DREAM_Q
     const uint16_t *kbase = reinterpret_cast<const uint16_t *>(a.k) + ((int64_t)b * a.n_kv_heads + kvh) * a.s_max * D;
     const uint16_t *vbase = reinterpret_cast<const uint16_t *>(a.v) + ((int64_t)b * a.n_kv_heads + kvh) * a.s_max * D;
 
-    // ---- cooperative loads: thread owns CH 16-byte chunks of K and of V per tile.  Rows past the live
+    // ---- cooperative loads: a thread owns NLD 16-byte chunks of K and of V per step.  Rows past the live
     // range are clamped to the last live row (their scores are masked, so only finite values ever meet a
     // zero probability); tile indices past this workgroup's range are clamped too, so the number of loads
     // issued never depends on control flow and prefetches stay in flight across iterations.

@@ -88,7 +88,16 @@ def test_wave_kernel_tile_and_merge_areas(D, DS, NW, QT):
     assert len(cells) == state_floats
 
 
-@pytest.mark.parametrize("D,n_threads", [(64, 256), (128, 256), (256, 256), (128, 512), (256, 512)])
+@pytest.mark.parametrize("D,n_threads", [(64, 256), (128, 256), (256, 256), (128, 512), (256, 512), (64, 512)])
 def test_shared_tile_kernel_tile_area(D, n_threads):
-    """attn_bf16_kernel: all threads of the workgroup (4 or 8 waves) fill one tile."""
-    check_tile(D, D, n_threads)
+    """attn_bf16_kernel: all threads of the workgroup (4 or 8 waves) fill one tile; with more threads than a tile has
+    16-byte chunks (head_dim 64, 512 threads: the two-key-group form) a pass fills n_threads / chunks tiles, thread t
+    working on tile t / chunks as thread t % chunks."""
+    chunks = 32 * (D // 8)
+    check_tile(D, D, min(n_threads, chunks))
+    if n_threads > chunks:
+        assert n_threads % chunks == 0
+        owners = {}
+        for tid in range(n_threads):
+            owners.setdefault(tid // chunks, set()).add(tid % chunks)
+        assert all(v == set(range(chunks)) for v in owners.values()) and len(owners) == n_threads // chunks
