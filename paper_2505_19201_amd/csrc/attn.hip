@@ -179,7 +179,7 @@ __device__ __forceinline__ RowOwner row_owner(const AttnArgs &a, int kvh, int qg
 #define DREAM_SOFTMAX_SLACK 8.0f
 // Build-time knobs of the launch shapes (each value is the measured best):
 #ifndef DREAM_Q1_WAVES
-#define DREAM_Q1_WAVES 2     // waves per SIMD the 4-wave one-tile-per-wave variants are compiled for (3: same speed; 4: spills)
+#define DREAM_Q1_WAVES 2     // waves per SIMD the 4-wave one-tile-per-wave variants are compiled for (3: 1024 workgroups then run as 3 + 1 per CU, 75 against 71 us at 32 LLaVA sequences; 4: spills)
 #endif
 #ifndef DREAM_KG2_MAX_WG
 #define DREAM_KG2_MAX_WG 1   // two key groups while a CU would get at most this many 4-wave workgroups (measured: -5 % at 1, +3 % at 4)
